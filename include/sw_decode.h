@@ -1,0 +1,170 @@
+/*
+ * sw_decode.h -- C ABI of the MI355X (gfx950) decode-attention library.
+ *
+ * The operation is one token-generation step's attention, as the paper states
+ * the step (section 2.2, "Generative LLM inference phases": the newest token
+ * and the request's KV cache are the inputs of the forward pass; section 3.5,
+ * "Memory utilization": each active token reads the cache of its entire
+ * context), batched over requests (section 3.4, "Throughput": token phases of
+ * up to 64 requests are batched), at one GPU's tensor-parallel share of the
+ * heads (section 2.5, "Model parallelism": tensor parallelism over 8 GPUs).
+ * The attention itself is the scaled dot-product attention the paper reaches
+ * by citation in section 2.1:
+ *
+ *   for request r, query head h, key/value head g = h / (n_qh / n_kvh),
+ *   L = clamp(seq_lens[r], 0, max_len):
+ *     out[r,h,:] = sum_{t<L} softmax_t( q[r,h,:] . K[r,g,t,:] / sqrt(head_dim) ) * V[r,g,t,:]
+ *     out[r,h,:] = +0 when L == 0.
+ *
+ * Inputs and output are IEEE binary16; products and sums are accumulated in
+ * binary32; the output is rounded to binary16 with round-to-nearest-even.
+ *
+ * Every function returns an int: SW_OK (0) or a negative SW_ERR_* code.
+ * Nothing here throws, aborts or prints.  All scalar and pointer validation
+ * happens before the first HIP call, so bad arguments are reported even on a
+ * machine with no GPU.
+ */
+#ifndef SW_DECODE_H
+#define SW_DECODE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SW_OK               0
+#define SW_ERR_NULL        -1  /* a required pointer is NULL while n_req > 0            */
+#define SW_ERR_SHAPE       -2  /* n_req < 0, n_qh/n_kvh/max_len <= 0, n_qh % n_kvh != 0,
+                                  or a size whose element count overflows the library's
+                                  limits (see sw_decode_attn)                           */
+#define SW_ERR_UNSUPPORTED -3  /* head_dim not in {64, 128}; n_qh / n_kvh > 64          */
+#define SW_ERR_ALIGN       -4  /* q, k_cache, v_cache or out not 16-byte aligned,
+                                  seq_lens not 4-byte aligned                            */
+#define SW_ERR_HIP         -5  /* a HIP call failed (no device, allocation, launch);
+                                  text in sw_last_error()                                */
+#define SW_ERR_PARAM       -6  /* sw_set_param: unknown key or value out of range        */
+#define SW_ERR_STATE       -7  /* sw_prof_*: called out of order                          */
+
+#define SW_F16 1               /* sw_kv_layout_t.dtype: IEEE binary16                    */
+
+/*
+ * How the library wants the K and V caches laid out.  Strides are in ELEMENTS
+ * (binary16 values), not bytes.  Element (r, g, t, j) of a cache -- request r,
+ * key/value head g, token position t, dimension j -- lives at
+ *     base + r*stride_req + g*stride_kvh + t*stride_tok + j*stride_dim.
+ * The logical order is [req][kv_head][token][dim] with dim contiguous
+ * (stride_dim == 1) and a token's row dense (stride_tok == head_dim); the
+ * strides of the two outer axes may carry padding, so callers must index
+ * through them and never assume a dense array.  Positions t >= seq_lens[r]
+ * and all padding are never read into a result; their content is arbitrary.
+ */
+typedef struct sw_kv_layout_t {
+    int32_t dtype;        /* SW_F16                                                    */
+    int32_t elem_bytes;   /* 2                                                         */
+    int64_t stride_req;   /* elements between consecutive requests                     */
+    int64_t stride_kvh;   /* elements between consecutive key/value heads              */
+    int64_t stride_tok;   /* elements between consecutive token positions (= head_dim) */
+    int64_t stride_dim;   /* 1                                                         */
+    int64_t total_elems;  /* elements to allocate for ONE cache buffer (K or V)         */
+    int32_t base_align;   /* required alignment of each buffer's base address, bytes   */
+    int32_t reserved;     /* 0                                                         */
+} sw_kv_layout_t;
+
+/*
+ * sw_kv_layout -- layout query for the per-request KV state of the step
+ * (section 2.2: the KV cache keeps the attention context of every earlier
+ * token of a request; section 3.5: it grows with the tokens in the batch).
+ * Pure host arithmetic, no HIP call.  `out` is host memory owned by the
+ * caller.  Errors: SW_ERR_NULL (out), SW_ERR_SHAPE, SW_ERR_UNSUPPORTED.
+ */
+int sw_kv_layout(int n_req, int n_kvh, int head_dim, int max_len, sw_kv_layout_t *out);
+
+/*
+ * sw_decode_attn -- one decode step's attention for a batch of requests
+ * (sections 2.2, 3.4 and 3.5 as cited at the top of this file).
+ *
+ *   q         DEVICE, binary16, dense [n_req][n_qh][head_dim]; the newest
+ *             token's query vectors.  Read only.
+ *   k_cache   DEVICE, binary16, laid out as sw_kv_layout(n_req, n_kvh,
+ *             head_dim, max_len) says.  Read only.
+ *   v_cache   DEVICE, same layout as k_cache, a separate buffer.  Read only.
+ *   seq_lens  DEVICE, int32 [n_req]; the number of cached positions of each
+ *             request, the newest token included.  Never read by the host.
+ *             Values outside [0, max_len] are clamped on the device.
+ *   out       DEVICE, binary16, dense [n_req][n_qh][head_dim].  Fully
+ *             overwritten (rows of requests with length 0 become +0).
+ *   n_req >= 0; n_qh, n_kvh > 0 with n_qh % n_kvh == 0 and n_qh / n_kvh <= 64;
+ *   head_dim in {64, 128}; 0 < max_len <= 2^24; n_req * n_qh and
+ *   n_req * n_kvh at most 2^20.
+ *   stream    a hipStream_t passed as void*; NULL is the default stream.
+ *
+ * The call enqueues its kernels on `stream` and returns without waiting for
+ * them.  All buffers stay owned by the caller, who must keep them alive and
+ * unmodified until the enqueued work has finished; the library keeps no
+ * pointer past that.  Between its kernels the call uses a workspace for
+ * partial results that the library owns: one per (device, stream), grown on
+ * demand (a growing call allocates, which synchronises the device), never
+ * shrunk, released by sw_release() or at process exit.  Two calls on the SAME
+ * stream are ordered; calls on different streams use different workspaces and
+ * may overlap.  The result of a request does not depend on which other
+ * requests share the batch, and repeating a call gives the same bits.
+ * n_req == 0 returns SW_OK without touching the device.
+ * Errors: SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN (all
+ * before any HIP call), SW_ERR_HIP.
+ */
+int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *seq_lens, void *out,
+                   int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                   void *stream);
+
+/*
+ * sw_last_error -- text of the calling thread's most recent failure
+ * (a static or thread-local string; never NULL; valid until the thread's next
+ * failing call).  Support call, not part of the step.
+ */
+const char *sw_last_error(void);
+
+/* sw_version -- library version as major*10000 + minor*100 + patch. */
+int sw_version(void);
+
+/*
+ * sw_release -- frees every workspace the library holds (after synchronising
+ * the devices they live on).  Optional; the caller must make sure that no
+ * call is in flight.  Support call, not part of the step.
+ */
+int sw_release(void);
+
+/*
+ * Tuning and test knobs (support calls, not part of the step).  They change
+ * how the step is scheduled, never what it computes.  Process-wide; set them
+ * while no call is in flight.
+ *   SW_PARAM_CHUNK     context positions per workgroup of the partial kernel
+ *                      (split over context length); 0 = library default;
+ *                      otherwise a multiple of 64 in [64, 65536].
+ *   SW_PARAM_KERNEL    0 = library default choice, 1 = force the vector-ALU
+ *                      partial kernel, 2 = force the matrix-core (MFMA)
+ *                      partial kernel (SW_ERR_UNSUPPORTED at call time if the
+ *                      shape has no such kernel).
+ */
+#define SW_PARAM_CHUNK   1
+#define SW_PARAM_KERNEL  2
+int sw_set_param(int key, int value);
+int sw_get_param(int key, int *value);
+
+/*
+ * Per-kernel timing for measurement (support calls, not part of the step).
+ * Between sw_prof_start and sw_prof_stop every sw_decode_attn call attaches a
+ * pair of HIP events to each kernel it launches (on the call's stream), for
+ * up to `capacity` calls; further calls run untimed.  sw_prof_stop waits for
+ * the recorded events and reports, in microseconds summed over the recorded
+ * calls, the device time of the partial kernel and of the combine kernel,
+ * and how many calls were recorded.  Pointers are host memory.
+ */
+int sw_prof_start(int capacity);
+int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SW_DECODE_H */

@@ -1,0 +1,111 @@
+"""ctypes binding of oracle/sw_oracle.c (argument marshalling only).
+
+TEST INFRASTRUCTURE: see the header of sw_oracle.c.  Nothing in the GPU
+package imports this module.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sw_oracle.c")
+_LIB = os.path.join(_HERE, "libsw_oracle.so")
+_lib = None
+
+
+def lib_path():
+    return _LIB
+
+
+def build(force=False):
+    """Compile sw_oracle.c with gcc (OpenMP over (request, head) units)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + ".tmp.%d" % os.getpid()
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+           "-ffp-contract=off", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.sw_oracle_decode_attn.restype = ctypes.c_int
+        lib.sw_oracle_decode_attn.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+        lib.sw_oracle_half_to_double.restype = ctypes.c_double
+        lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.sw_oracle_max_threads.restype = ctypes.c_int
+        lib.sw_oracle_max_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def half_to_double(bits):
+    return _load().sw_oracle_half_to_double(int(bits) & 0xFFFF)
+
+
+def max_threads():
+    return _load().sw_oracle_max_threads()
+
+
+def _as_u16(a, name):
+    a = np.asarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError("%s must be float16 or uint16 bits, got %s" % (name, a.dtype))
+    if not a.flags["C_CONTIGUOUS"]:
+        raise ValueError("%s must be C-contiguous (strides are passed separately)" % name)
+    return a
+
+
+def decode_attn(q, k, v, seq_lens, n_req, n_qh, n_kvh, head_dim, max_len,
+                stride_req, stride_kvh, stride_tok, n_threads=0, return_stats=False):
+    """Run the oracle.
+
+    q: float16/uint16, n_req*n_qh*head_dim elements, dense.
+    k, v: flat float16/uint16 buffers addressed by the element strides given.
+    Returns ref float64 [n_req, n_qh, head_dim] (and, if return_stats, the
+    per-(request, head) score maximum m, the sum l of exp(s - m), and the
+    thread count used).
+    """
+    lib = _load()
+    q = _as_u16(q, "q")
+    k = _as_u16(k, "k")
+    v = _as_u16(v, "v")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    if lens.size != n_req:
+        raise ValueError("seq_lens has %d entries, n_req is %d" % (lens.size, n_req))
+    if q.size != n_req * n_qh * head_dim:
+        raise ValueError("q has %d elements, expected %d" % (q.size, n_req * n_qh * head_dim))
+    need = 0
+    if n_req > 0:
+        need = ((n_req - 1) * stride_req + (n_kvh - 1) * stride_kvh
+                + (max_len - 1) * stride_tok + head_dim)
+    if k.size < need or v.size < need:
+        raise ValueError("k/v buffers (%d, %d elements) are smaller than the strides address (%d)"
+                         % (k.size, v.size, need))
+    ref = np.zeros((n_req, n_qh, head_dim), dtype=np.float64)
+    m = np.zeros((n_req, n_qh), dtype=np.float64)
+    l = np.zeros((n_req, n_qh), dtype=np.float64)
+    rc = lib.sw_oracle_decode_attn(
+        q.ctypes.data, k.ctypes.data, v.ctypes.data, lens.ctypes.data,
+        ref.ctypes.data, m.ctypes.data, l.ctypes.data,
+        n_req, n_qh, n_kvh, head_dim, max_len,
+        stride_req, stride_kvh, stride_tok, int(n_threads))
+    if rc < 0:
+        raise ValueError("sw_oracle_decode_attn rejected its arguments (code %d)" % rc)
+    if return_stats:
+        return ref, m, l, rc
+    return ref

@@ -1,0 +1,183 @@
+/*
+ * sw_oracle.c -- CPU reference ("oracle") for one decode-attention step.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE. It is a plain, slow, fp64 implementation
+ * used only to check the GPU library and to time a CPU baseline next to it.
+ * The GPU library never calls, links or includes anything from this directory,
+ * and nothing here includes anything of the GPU library.
+ *
+ * What it computes.  The paper (section 2.2, "Generative LLM inference
+ * phases") states the token-generation step: the forward pass of a request's
+ * newest token takes that token and the request's whole KV cache as inputs,
+ * and (section 3.5, "Memory utilization") every active token reads the cache
+ * of its entire context.  The attention it refers to (section 2.1, by
+ * citation) is scaled dot-product attention, so for every request r and
+ * query head h, with g = h / (n_qh / n_kvh) the key/value head that serves h,
+ * and L = clamp(seq_lens[r], 0, max_len):
+ *
+ *     s_t   = (sum_j q[r,h,j] * K[r,g,t,j]) / sqrt(head_dim),   t = 0..L-1
+ *     m     = max_t s_t
+ *     p_t   = exp(s_t - m)
+ *     l     = sum_t p_t
+ *     ref_j = (sum_t p_t * V[r,g,t,j]) / l
+ *
+ * and ref = 0 when L = 0.  It is the definition written out: two passes, no
+ * running maximum, no chunking, no blocking.  Inputs are IEEE binary16 bit
+ * patterns, widened exactly to double by the decoder below; everything after
+ * that is double.  Each (r, h) unit is computed sequentially by one thread, so
+ * the result does not depend on the thread count.
+ *
+ * Pins: closed forms (one token, identical keys, a dominant key), brute force
+ * against a dense matrix formulation, shift / permutation invariance,
+ * convexity, the chunk-merge identity, GQA-as-replicated-MHA and a one-hot-V
+ * comparison against a library softmax (tests/test_oracle_pins.py).
+ * The paper prints no worked numerical example of this step, so parity with
+ * the paper's own numbers is unpinned; parity is against the definition.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Exact widening of an IEEE 754 binary16 bit pattern to double.
+ * sign 1 bit, exponent 5 bits (bias 15), fraction 10 bits. */
+static double half_bits_to_double(uint16_t b)
+{
+    int sign = (b >> 15) & 1;
+    int expo = (b >> 10) & 0x1f;
+    int frac = b & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -24);            /* zero and subnormals: frac * 2^-24 */
+    } else if (expo == 31) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(1024 + frac), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+    }
+    return sign ? -v : v;
+}
+
+/* Exposed so that the tests can pin the decoder against numpy's float16. */
+double sw_oracle_half_to_double(uint16_t bits) { return half_bits_to_double(bits); }
+
+static int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+/*
+ * One (request, query head) unit.  kg / vg point at token 0 of the serving
+ * key/value head; consecutive tokens are stride_tok elements apart.
+ * scores is scratch of at least L doubles.
+ */
+static void attend_one(const uint16_t *qrow, const uint16_t *kg, const uint16_t *vg,
+                       int L, int d, int64_t stride_tok, double *scores,
+                       double *ref, double *m_out, double *l_out)
+{
+    if (L <= 0) {
+        for (int j = 0; j < d; ++j) ref[j] = 0.0;
+        if (m_out) *m_out = -INFINITY;
+        if (l_out) *l_out = 0.0;
+        return;
+    }
+    const double scale = 1.0 / sqrt((double)d);
+    double m = -INFINITY;
+    for (int t = 0; t < L; ++t) {
+        const uint16_t *krow = kg + (int64_t)t * stride_tok;
+        double acc = 0.0;
+        for (int j = 0; j < d; ++j)
+            acc += half_bits_to_double(qrow[j]) * half_bits_to_double(krow[j]);
+        scores[t] = acc * scale;
+        if (scores[t] > m) m = scores[t];
+    }
+    double l = 0.0;
+    for (int t = 0; t < L; ++t) {
+        scores[t] = exp(scores[t] - m);
+        l += scores[t];
+    }
+    for (int j = 0; j < d; ++j) {
+        double acc = 0.0;
+        for (int t = 0; t < L; ++t)
+            acc += scores[t] * half_bits_to_double(vg[(int64_t)t * stride_tok + j]);
+        ref[j] = acc / l;
+    }
+    if (m_out) *m_out = m;
+    if (l_out) *l_out = l;
+}
+
+/*
+ * Whole batch.  All pointers are host memory.
+ *   q        binary16 bits, dense [n_req][n_qh][head_dim]
+ *   k, v     binary16 bits; element (r, g, t, j) is at
+ *            r*stride_req + g*stride_kvh + t*stride_tok + j
+ *   seq_lens int32 [n_req]; values outside [0, max_len] are clamped
+ *   ref      double, dense [n_req][n_qh][head_dim]   (not rounded to binary16)
+ *   m_out, l_out   optional (may be NULL) double [n_req][n_qh]: the score
+ *            maximum and the sum of exp(s - m); used by the chunk-merge pin
+ *   n_threads  <= 0 means "all the runtime offers"
+ * Returns the number of threads used (>= 1), or a negative value on a bad
+ * argument.
+ */
+int sw_oracle_decode_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                          const int32_t *seq_lens, double *ref,
+                          double *m_out, double *l_out,
+                          int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                          int64_t stride_req, int64_t stride_kvh, int64_t stride_tok,
+                          int n_threads)
+{
+    if (n_req < 0 || n_qh <= 0 || n_kvh <= 0 || head_dim <= 0 || max_len <= 0) return -1;
+    if (n_qh % n_kvh != 0) return -2;
+    if (n_req == 0) return 1;
+    if (!q || !k || !v || !seq_lens || !ref) return -3;
+
+    const int group = n_qh / n_kvh;
+    const int64_t units = (int64_t)n_req * n_qh;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    if ((int64_t)n_threads > units) n_threads = (int)units;
+    used = n_threads;
+#else
+    (void)n_threads;
+#endif
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(n_threads)
+#endif
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)max_len);
+        if (!scores) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t u = 0; u < units; ++u) {
+            if (!scores) continue;
+            int r = (int)(u / n_qh);
+            int h = (int)(u % n_qh);
+            int g = h / group;
+            int L = clampi(seq_lens[r], 0, max_len);
+            const uint16_t *qrow = q + ((int64_t)r * n_qh + h) * head_dim;
+            const uint16_t *kg = k + (int64_t)r * stride_req + (int64_t)g * stride_kvh;
+            const uint16_t *vg = v + (int64_t)r * stride_req + (int64_t)g * stride_kvh;
+            attend_one(qrow, kg, vg, L, head_dim, stride_tok, scores,
+                       ref + u * head_dim,
+                       m_out ? m_out + u : NULL, l_out ? l_out + u : NULL);
+        }
+        free(scores);
+    }
+    return failed ? -4 : used;
+}
+
+int sw_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,164 @@
+"""Seeded synthetic decode batches (inputs only -- none of the method's arithmetic).
+
+The paper characterises the token phase on production traces that are not
+public here; it gives the models (table "Models we evaluate": Llama2-70B,
+BLOOM-176B), the tensor-parallel degree (section 2.5: 8 GPUs), the decode batch
+range (section 3.4: up to 64) and the context-length medians (section 3.1:
+prompt median 1500 tokens for coding, 1020 for conversation).  These
+generators stand in for those traces: same shapes, lengths drawn around those
+medians, values i.i.d. N(0, 1) rounded once to binary16.
+
+Both the CPU oracle's tests and the GPU library's tests and bench draw their
+inputs here, so that they see the same bytes.  numpy only.
+"""
+from dataclasses import dataclass, field
+
+import numpy as np
+
+BASE_SEED = 231118677
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    n_req: int
+    n_qh: int
+    n_kvh: int
+    head_dim: int
+    max_len: int
+    lens: tuple            # ("fixed", [..]) | ("uniform", lo, hi) | ("lognormal", median, sigma, lo, hi)
+    k_row_scale: tuple = ()   # () or (probability, factor)
+    n_layers: int = 1      # layers of the model the share belongs to (for steps/s)
+    seed_index: int = 0
+
+
+CONFIGS = {
+    # 1. tiny multi-head case the CPU oracle finishes in milliseconds
+    "tiny_mha": Config("tiny_mha", 4, 8, 8, 64, 128, ("fixed", (1, 17, 64, 128)),
+                       n_layers=1, seed_index=1),
+    # 2. Llama-2-70B, one GPU's share at 8-way tensor parallelism: 8 query heads on 1 KV head
+    "llama70b_tp8": Config("llama70b_tp8", 64, 8, 1, 128, 4096, ("uniform", 1000, 2600),
+                           n_layers=80, seed_index=2),
+    # 3. BLOOM-176B, one GPU's share: 112 / 8 = 14 heads, multi-head attention
+    "bloom176b_tp8": Config("bloom176b_tp8", 32, 14, 14, 128, 8192,
+                            ("lognormal", 1000.0, 0.8, 16, 8192), n_layers=70, seed_index=3),
+    # 4. large skewed batch, Llama share, 10 % of the key rows scaled by 8
+    "skewed_256": Config("skewed_256", 256, 8, 1, 128, 8192,
+                         ("lognormal", 1020.0, 1.0, 16, 8192), k_row_scale=(0.1, 8.0),
+                         n_layers=80, seed_index=4),
+    # 5. few requests, long context
+    "longctx_8x32k": Config("longctx_8x32k", 8, 8, 1, 128, 32768,
+                            ("fixed", (32768,) * 8), n_layers=80, seed_index=5),
+}
+
+
+def _streams(seed, n=5):
+    """Independent Philox sub-streams: seq_lens, q, K, V, K-row-scale mask."""
+    return [np.random.Generator(np.random.Philox(s))
+            for s in np.random.SeedSequence(int(seed)).spawn(n)]
+
+
+def draw_seq_lens(cfg, rng):
+    kind = cfg.lens[0]
+    if kind == "fixed":
+        lens = np.asarray(cfg.lens[1], dtype=np.int64)
+        if lens.size != cfg.n_req:
+            raise ValueError("fixed lens need n_req entries")
+    elif kind == "uniform":
+        lens = rng.integers(cfg.lens[1], cfg.lens[2] + 1, size=cfg.n_req)
+    elif kind == "lognormal":
+        _, median, sigma, lo, hi = cfg.lens
+        z = rng.standard_normal(cfg.n_req)
+        lens = np.clip(np.rint(np.exp(np.log(median) + sigma * z)), lo, hi)
+    else:
+        raise ValueError(kind)
+    return lens.astype(np.int32)
+
+
+@dataclass
+class Batch:
+    """One decode batch: q dense, K/V as compact valid rows in (req, kv_head, token, dim) order."""
+    cfg: Config
+    seed: int
+    seq_lens: np.ndarray              # int32 [n_req] (as handed to the library; may be out of range)
+    q: np.ndarray                     # float16 [n_req, n_qh, head_dim]
+    k_rows: list = field(default_factory=list)   # per request: float16 [n_kvh, L_r, head_dim]
+    v_rows: list = field(default_factory=list)
+
+    @property
+    def valid_lens(self):
+        return np.clip(self.seq_lens, 0, self.cfg.max_len)
+
+    @property
+    def total_tokens(self):
+        return int(self.valid_lens.astype(np.int64).sum())
+
+    @property
+    def kv_bytes(self):
+        """Bytes of K and V rows at valid positions: tokens * n_kvh * head_dim * 2 B * 2."""
+        return self.total_tokens * self.cfg.n_kvh * self.cfg.head_dim * 4
+
+
+def make_batch(cfg, seed=None, seq_lens=None):
+    """Draw one batch for `cfg`.  seq_lens overrides the config's length recipe."""
+    if isinstance(cfg, str):
+        cfg = CONFIGS[cfg]
+    if seed is None:
+        seed = BASE_SEED + cfg.seed_index
+    r_len, r_q, r_k, r_v, r_mask = _streams(seed)
+    if seq_lens is None:
+        lens = draw_seq_lens(cfg, r_len)
+    else:
+        lens = np.asarray(seq_lens, dtype=np.int32)
+        if lens.size != cfg.n_req:
+            raise ValueError("seq_lens override needs n_req entries")
+    d = cfg.head_dim
+    q = r_q.standard_normal((cfg.n_req, cfg.n_qh, d), dtype=np.float32).astype(np.float16)
+    k_rows, v_rows = [], []
+    valid = np.clip(lens, 0, cfg.max_len)
+    for r in range(cfg.n_req):
+        L = int(valid[r])
+        k = r_k.standard_normal((cfg.n_kvh, L, d), dtype=np.float32)
+        v = r_v.standard_normal((cfg.n_kvh, L, d), dtype=np.float32)
+        if cfg.k_row_scale:
+            prob, factor = cfg.k_row_scale
+            hit = r_mask.random((cfg.n_kvh, L)) < prob
+            k = np.where(hit[:, :, None], k * np.float32(factor), k)
+        k_rows.append(k.astype(np.float16))
+        v_rows.append(v.astype(np.float16))
+    return Batch(cfg, int(seed), lens, q, k_rows, v_rows)
+
+
+def custom_config(name, n_req, n_qh, n_kvh, head_dim, max_len, n_layers=1):
+    """A free-form shape for edge-case tests; pass seq_lens to make_batch."""
+    return Config(name, n_req, n_qh, n_kvh, head_dim, max_len, ("fixed", (0,) * n_req),
+                  n_layers=n_layers, seed_index=0)
+
+
+def pack_cache(rows, cfg, stride_req, stride_kvh, stride_tok, total_elems, pad_bits=0):
+    """Scatter compact valid rows into one flat cache buffer addressed by element strides.
+
+    Everything that is not a valid position (positions >= the request's length,
+    stride padding) is filled with the bit pattern pad_bits, e.g. 0x7E00 (a NaN)
+    to show that the library never lets padding reach a result.
+    Returns a flat uint16 array of total_elems elements.
+    """
+    buf = np.full(int(total_elems), np.uint16(pad_bits), dtype=np.uint16)
+    d = cfg.head_dim
+    view = np.lib.stride_tricks.as_strided(
+        buf, shape=(cfg.n_req, cfg.n_kvh, cfg.max_len, d),
+        strides=(2 * stride_req, 2 * stride_kvh, 2 * stride_tok, 2), writeable=True)
+    for r, blk in enumerate(rows):
+        L = blk.shape[1]
+        if L:
+            view[r, :, :L, :] = blk.view(np.uint16)
+    return buf
+
+
+def dense_layout(cfg):
+    """Plain dense strides (for CPU-only tests that have no library to ask)."""
+    d = cfg.head_dim
+    st = d
+    sg = cfg.max_len * d
+    sr = cfg.n_kvh * sg
+    return sr, sg, st, cfg.n_req * sr

@@ -1,0 +1,281 @@
+"""Pins of the CPU oracle against what the definition and the mathematics fix.
+
+None of these tests touches the GPU library.  Each pin is chosen so that a
+plausible slip in oracle/sw_oracle.c (a dropped scale, a wrong head mapping, a
+transposed index, a missing max subtraction, a wrong stride) fails at least
+one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+from paper_2311_18677_amd import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def run_dense(q, k, v, lens, n_threads=0, stats=False):
+    """q [R,Hq,d], k/v [R,Hk,M,d] float16 dense arrays."""
+    R, Hq, d = q.shape
+    _, Hk, M, _ = k.shape
+    return oracle.decode_attn(
+        np.ascontiguousarray(q), np.ascontiguousarray(k).reshape(-1),
+        np.ascontiguousarray(v).reshape(-1), lens, R, Hq, Hk, d, M,
+        Hk * M * d, M * d, d, n_threads=n_threads, return_stats=stats)
+
+
+def brute(q, k, v, lens):
+    """Dense matrix formulation written separately: softmax(Q K^T / sqrt(d)) V."""
+    R, Hq, d = q.shape
+    Hk = k.shape[1]
+    G = Hq // Hk
+    out = np.zeros((R, Hq, d))
+    q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+    for r in range(R):
+        L = int(lens[r])
+        if L == 0:
+            continue
+        for h in range(Hq):
+            Kmat = k64[r, h // G, :L, :]
+            Vmat = v64[r, h // G, :L, :]
+            w = scipy.special.softmax(Kmat @ q64[r, h] / math.sqrt(d))
+            out[r, h] = w @ Vmat
+    return out
+
+
+def rnd(shape, seed, scale=1.0):
+    g = np.random.Generator(np.random.Philox(seed))
+    return (g.standard_normal(shape) * scale).astype(np.float16)
+
+
+def test_half_decoder_all_bit_patterns():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_golden_softmax_012():
+    rows = {}
+    with open(os.path.join(HERE, "golden", "softmax_012.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *vals = line.split()
+            rows[key] = [float(x) for x in vals]
+    q = np.array(rows["q"], dtype=np.float16).reshape(1, 1, 4)
+    k = np.array([rows["k0"], rows["k1"], rows["k2"]], dtype=np.float16).reshape(1, 1, 3, 4)
+    v = np.array([rows["v0"], rows["v1"], rows["v2"]], dtype=np.float16).reshape(1, 1, 3, 4)
+    ref = run_dense(q, k, v, [3])
+    assert np.allclose(ref[0, 0], rows["out"], rtol=0, atol=1e-15)
+
+
+def test_p1_single_token_returns_v_exactly():
+    q, k, v = rnd((3, 4, 64), 1), rnd((3, 2, 5, 64), 2), rnd((3, 2, 5, 64), 3)
+    ref = run_dense(q, k, v, [1, 1, 1])
+    for r in range(3):
+        for h in range(4):
+            assert np.array_equal(ref[r, h], v[r, h // 2, 0].astype(np.float64))
+
+
+def test_p2_identical_keys_give_mean_of_v():
+    q, v = rnd((2, 2, 128), 4), rnd((2, 2, 37, 128), 5)
+    k = np.repeat(rnd((2, 2, 1, 128), 6), 37, axis=2)
+    ref = run_dense(q, k, v, [37, 20])
+    assert np.allclose(ref[0], v[0, :, :37].astype(np.float64).mean(axis=1), rtol=1e-13, atol=1e-15)
+    assert np.allclose(ref[1], v[1, :, :20].astype(np.float64).mean(axis=1), rtol=1e-13, atol=1e-15)
+    # q = 0 is the same closed form
+    ref0 = run_dense(np.zeros_like(q), rnd((2, 2, 37, 128), 7), v, [37, 37])
+    assert np.allclose(ref0, v.astype(np.float64).mean(axis=2), rtol=1e-13, atol=1e-15)
+
+
+def test_p3_dominant_key_returns_its_v():
+    d, L, hot = 64, 50, 31
+    q = np.zeros((1, 1, d), np.float16)
+    q[0, 0, 0] = 16.0
+    k = rnd((1, 1, L, d), 8, 0.01)
+    k[0, 0, :, 0] = 0.0
+    k[0, 0, hot, 0] = 40.0          # score 16*40/8 = 80, all others 0: margin 80 > 60
+    v = rnd((1, 1, L, d), 9)
+    ref = run_dense(q, k, v, [L])
+    assert np.max(np.abs(ref[0, 0] - v[0, 0, hot].astype(np.float64))) <= 1e-20 * L * 10
+
+
+@pytest.mark.parametrize("R,Hq,Hk,d,M", [(1, 1, 1, 2, 3), (3, 4, 2, 4, 9), (2, 4, 4, 64, 7),
+                                           (2, 6, 2, 64, 9), (1, 8, 1, 128, 33)])
+def test_p4_brute_force_matrix_formulation(R, Hq, Hk, d, M):
+    q, k, v = rnd((R, Hq, d), 10), rnd((R, Hk, M, d), 11), rnd((R, Hk, M, d), 12)
+    lens = [(M - 2 * r) if (M - 2 * r) > 0 else 1 for r in range(R)]
+    ref = run_dense(q, k, v, lens)
+    want = brute(q, k, v, lens)
+    assert np.allclose(ref, want, rtol=1e-12, atol=1e-14)
+
+
+def test_p5_key_shift_invariance():
+    # adding a constant vector c to every key adds q.c/sqrt(d) to every score
+    d, L = 64, 40
+    q = rnd((1, 2, d), 13)
+    # multiples of 2^-8 in [-0.4, 0.4], so that adding 0.5 is exact in binary16
+    k_small = (np.clip(np.rint(rnd((1, 1, L, d), 14).astype(np.float32) * 32), -100, 100) / 256).astype(np.float16)
+    c = np.zeros(d, np.float16)
+    c[::3] = 0.5
+    k_shift = (k_small.astype(np.float32) + c.astype(np.float32)).astype(np.float16)
+    assert np.array_equal(k_shift.astype(np.float64), k_small.astype(np.float64) + c.astype(np.float64))
+    v = rnd((1, 1, L, d), 15)
+    a = run_dense(q, k_small, v, [L])
+    b = run_dense(q, k_shift, v, [L])
+    assert np.allclose(a, b, rtol=1e-10, atol=1e-13)
+
+
+def test_p6_joint_permutation_of_keys_and_values():
+    d, L = 128, 61
+    q, k, v = rnd((1, 3, d), 16), rnd((1, 3, L, d), 17), rnd((1, 3, L, d), 18)
+    perm = np.random.Generator(np.random.Philox(19)).permutation(L)
+    a = run_dense(q, k, v, [L])
+    b = run_dense(q, k[:, :, perm], v[:, :, perm], [L])
+    assert np.allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_p7_convexity_and_weight_sum():
+    d, L = 64, 90
+    q, k, v = rnd((2, 2, d), 20), rnd((2, 2, L, d), 21), rnd((2, 2, L, d), 22)
+    ref = run_dense(q, k, v, [L, L // 2])
+    for r, Lr in enumerate([L, L // 2]):
+        vv = v[r, :, :Lr].astype(np.float64)
+        assert np.all(ref[r] >= vv.min(axis=1) - 1e-15)
+        assert np.all(ref[r] <= vv.max(axis=1) + 1e-15)
+    ones = np.ones_like(v)
+    assert np.allclose(run_dense(q, k, ones, [L, L // 2]), 1.0, rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("cuts", [(0, 13, 40), (0, 0, 40), (0, 1, 2, 39, 40), (0, 40, 40)])
+def test_p8_chunk_merge_identity(cuts):
+    # splitting [0, L) anywhere, running the oracle per piece and merging the
+    # pieces' (o, m, l) gives the one-shot result; an empty piece has
+    # m = -inf, l = 0 and contributes nothing.
+    d, L, Hq, Hk = 64, 40, 4, 2
+    q, k, v = rnd((1, Hq, d), 23), rnd((1, Hk, L, d), 24), rnd((1, Hk, L, d), 25)
+    whole = run_dense(q, k, v, [L])
+    parts = []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        n = b - a
+        kk = np.ascontiguousarray(k[:, :, a:b]) if n else np.zeros((1, Hk, 1, d), np.float16)
+        vv = np.ascontiguousarray(v[:, :, a:b]) if n else np.zeros((1, Hk, 1, d), np.float16)
+        ref, m, l, _ = run_dense(q, kk, vv, [n], stats=True)
+        parts.append((ref, m, l))
+    m_all = np.max(np.stack([p[1] for p in parts]), axis=0)
+    num = np.zeros_like(whole)
+    den = np.zeros_like(m_all)
+    for ref, m, l in parts:
+        w = np.where(l > 0, np.exp(np.where(l > 0, m - m_all, 0.0)), 0.0)
+        num += (w * l)[..., None] * ref
+        den += w * l
+    assert np.allclose(num / den[..., None], whole, rtol=1e-12, atol=1e-14)
+
+
+def test_p9_gqa_equals_mha_with_replicated_kv_heads():
+    d, L, Hq, Hk = 64, 23, 8, 2
+    G = Hq // Hk
+    q, k, v = rnd((2, Hq, d), 26), rnd((2, Hk, L, d), 27), rnd((2, Hk, L, d), 28)
+    a = run_dense(q, k, v, [L, 5])
+    b = run_dense(q, np.repeat(k, G, axis=1), np.repeat(v, G, axis=1), [L, 5])
+    assert np.array_equal(a, b)
+    # and the mapping is by contiguous groups: head h uses kv head h // G
+    for h in range(Hq):
+        one = run_dense(q[:, h:h + 1], k[:, h // G:h // G + 1], v[:, h // G:h // G + 1], [L, 5])
+        assert np.array_equal(one[:, 0], a[:, h])
+
+
+def test_p10_one_hot_values_expose_the_softmax():
+    d, L = 64, 64
+    q, k = rnd((1, 1, d), 29), rnd((1, 1, L, d), 30)
+    v = np.zeros((1, 1, L, d), np.float16)
+    v[0, 0, np.arange(L), np.arange(L)] = 1.0
+    ref = run_dense(q, k, v, [L])
+    s = k[0, 0].astype(np.float64) @ q[0, 0].astype(np.float64) / math.sqrt(d)
+    assert np.allclose(ref[0, 0], scipy.special.softmax(s), rtol=1e-12, atol=1e-16)
+
+
+def test_p11_large_scores_do_not_overflow():
+    d, L = 4, 6
+    q = np.full((1, 1, d), 65504.0, np.float16)
+    k = np.zeros((1, 1, L, d), np.float16)
+    k[0, 0, :, 0] = [65504, -65504, 65472, 100, 0, 65504]
+    v = rnd((1, 1, L, d), 31)
+    ref = run_dense(q, k, v, [L])
+    assert np.all(np.isfinite(ref))
+    # extended-precision rerun of the definition
+    ld = np.longdouble
+    s = (k[0, 0].astype(ld) @ q[0, 0].astype(ld)) / np.sqrt(ld(d))
+    p = np.exp(s - s.max())
+    want = (p[:, None] * v[0, 0].astype(ld)).sum(axis=0) / p.sum()
+    assert np.allclose(ref[0, 0], want.astype(np.float64), rtol=1e-12, atol=1e-14)
+    # config-4-style x8 key rows
+    k2 = rnd((1, 1, 50, 64), 32)
+    k2[0, 0, ::7] *= 8
+    q2, v2 = rnd((1, 1, 64), 33), rnd((1, 1, 50, 64), 34)
+    assert np.allclose(run_dense(q2, k2, v2, [50]), brute(q2, k2, v2, [50]), rtol=1e-12, atol=1e-14)
+
+
+def test_length_clamp_and_zero_length():
+    d, M = 64, 10
+    q, k, v = rnd((4, 2, d), 35), rnd((4, 2, M, d), 36), rnd((4, 2, M, d), 37)
+    ref, m, l, _ = run_dense(q, k, v, [0, -5, M + 7, 3], stats=True)
+    assert np.array_equal(ref[0], np.zeros((2, d))) and not np.signbit(ref[0]).any()
+    assert np.array_equal(ref[1], np.zeros((2, d)))
+    assert np.all(l[:2] == 0) and np.all(np.isneginf(m[:2]))
+    assert np.array_equal(ref[2], run_dense(q[2:3], k[2:3], v[2:3], [M])[0])
+    assert np.allclose(ref[3], brute(q[3:4], k[3:4], v[3:4], [3])[0], rtol=1e-12, atol=1e-14)
+
+
+def test_padding_is_never_read_and_strides_are_honoured():
+    cfg = wl.custom_config("pad", 3, 4, 2, 64, 16)
+    b = wl.make_batch(cfg, seed=77, seq_lens=[5, 16, 9])
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    sg2 = sg + 3 * 64          # padded strides
+    sr2 = cfg.n_kvh * sg2 + 64
+    tot2 = cfg.n_req * sr2
+    outs = []
+    st3 = st + 8               # padded token rows as well
+    sg3 = cfg.max_len * st3 + 24
+    sr3 = cfg.n_kvh * sg3
+    for (a, bb, c, t) in [(sr, sg, st, tot), (sr2, sg2, st, tot2), (sr3, sg3, st3, cfg.n_req * sr3)]:
+        for pad in (0, 0x7E00, 0x7BFF):
+            kb = wl.pack_cache(b.k_rows, cfg, a, bb, c, t, pad)
+            vb = wl.pack_cache(b.v_rows, cfg, a, bb, c, t, pad)
+            outs.append(oracle.decode_attn(b.q, kb, vb, b.seq_lens, 3, 4, 2, 64, 16, a, bb, c))
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+    assert np.all(np.isfinite(outs[0]))
+
+
+def test_thread_count_does_not_change_bits():
+    q, k, v = rnd((5, 4, 64), 38), rnd((5, 2, 33, 64), 39), rnd((5, 2, 33, 64), 40)
+    lens = [33, 1, 0, 17, 8]
+    a = run_dense(q, k, v, lens, n_threads=1)
+    b = run_dense(q, k, v, lens, n_threads=4)
+    assert np.array_equal(a, b)
+
+
+def test_tiny_config_matches_brute_force():
+    b = wl.make_batch("tiny_mha")
+    cfg = b.cfg
+    assert list(b.seq_lens) == [1, 17, 64, 128]
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    kb = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0x7E00)
+    vb = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0x7E00)
+    ref = oracle.decode_attn(b.q, kb, vb, b.seq_lens, 4, 8, 8, 64, 128, sr, sg, st)
+    kd = np.zeros((4, 8, 128, 64), np.float16)
+    vd = np.zeros((4, 8, 128, 64), np.float16)
+    for r in range(4):
+        L = b.seq_lens[r]
+        kd[r, :, :L] = b.k_rows[r]
+        vd[r, :, :L] = b.v_rows[r]
+    assert np.allclose(ref, brute(b.q, kd, vd, b.seq_lens), rtol=1e-12, atol=1e-14)
