@@ -1,0 +1,201 @@
+"""Thin ctypes binding of include/sw_decode.h (argument marshalling only).
+
+Every step of the decode-attention path runs in the HIP kernels of
+libsw_decode.so.  There is no fallback: if the library has not been built the
+first call raises.  PyTorch appears only in the helpers that allocate device
+memory; the ABI functions take any object with a data_ptr() method, or a raw
+integer address.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsw_decode.so")
+
+SW_OK = 0
+SW_ERR_NULL = -1
+SW_ERR_SHAPE = -2
+SW_ERR_UNSUPPORTED = -3
+SW_ERR_ALIGN = -4
+SW_ERR_HIP = -5
+SW_ERR_PARAM = -6
+SW_ERR_STATE = -7
+SW_F16 = 1
+SW_PARAM_CHUNK = 1
+SW_PARAM_KERNEL = 2
+
+EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_last_error", "sw_version", "sw_release",
+           "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
+
+
+class sw_kv_layout_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("elem_bytes", ctypes.c_int32),
+                ("stride_req", ctypes.c_int64), ("stride_kvh", ctypes.c_int64),
+                ("stride_tok", ctypes.c_int64), ("stride_dim", ctypes.c_int64),
+                ("total_elems", ctypes.c_int64),
+                ("base_align", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class SwError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("sw_decode error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load libsw_decode.so; raise if it is not built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libsw_decode.so is not built (%s); run `python -m paper_2311_18677_amd.build`"
+            % LIB_PATH)
+    # PyTorch ships its own copy of the HIP runtime.  The streams and device
+    # pointers handed to this library come from torch, so both must live in ONE
+    # runtime instance: torch is imported first, and the library's dependency on
+    # libamdhip64.so.7 then binds to the copy torch has already loaded.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.sw_kv_layout.restype = ci
+    lib.sw_kv_layout.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sw_kv_layout_t)]
+    lib.sw_decode_attn.restype = ci
+    lib.sw_decode_attn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.sw_last_error.restype = ctypes.c_char_p
+    lib.sw_last_error.argtypes = []
+    lib.sw_version.restype = ci
+    lib.sw_version.argtypes = []
+    lib.sw_release.restype = ci
+    lib.sw_release.argtypes = []
+    lib.sw_set_param.restype = ci
+    lib.sw_set_param.argtypes = [ci, ci]
+    lib.sw_get_param.restype = ci
+    lib.sw_get_param.argtypes = [ci, ctypes.POINTER(ci)]
+    lib.sw_prof_start.restype = ci
+    lib.sw_prof_start.argtypes = [ci]
+    lib.sw_prof_stop.restype = ci
+    lib.sw_prof_stop.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                 ctypes.POINTER(ci)]
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if hasattr(s, "cuda_stream"):
+        return s.cuda_stream
+    return int(s)
+
+
+def _check(rc):
+    if rc != SW_OK:
+        raise SwError(rc, sw_last_error())
+    return rc
+
+
+def sw_last_error():
+    return load().sw_last_error().decode("utf-8", "replace")
+
+
+def sw_version():
+    return load().sw_version()
+
+
+def sw_kv_layout(n_req, n_kvh, head_dim, max_len, check=True):
+    """Returns the sw_kv_layout_t the library fills in (or the error code if check=False)."""
+    lay = sw_kv_layout_t()
+    rc = load().sw_kv_layout(n_req, n_kvh, head_dim, max_len, ctypes.byref(lay))
+    if check:
+        _check(rc)
+        return lay
+    return rc, lay
+
+
+def sw_decode_attn(q, k_cache, v_cache, seq_lens, out, n_req, n_qh, n_kvh, head_dim, max_len,
+                   stream=None, check=True):
+    """One decode step's attention; enqueues on `stream` and returns without waiting."""
+    rc = load().sw_decode_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out),
+                               n_req, n_qh, n_kvh, head_dim, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_release():
+    return _check(load().sw_release())
+
+
+def sw_set_param(key, value, check=True):
+    rc = load().sw_set_param(key, value)
+    return _check(rc) if check else rc
+
+
+def sw_get_param(key):
+    v = ctypes.c_int(0)
+    _check(load().sw_get_param(key, ctypes.byref(v)))
+    return v.value
+
+
+def sw_prof_start(capacity):
+    return _check(load().sw_prof_start(capacity))
+
+
+def sw_prof_stop():
+    """Returns (partial_us_sum, combine_us_sum, n_calls)."""
+    p, c, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
+    _check(load().sw_prof_stop(ctypes.byref(p), ctypes.byref(c), ctypes.byref(n)))
+    return p.value, c.value, n.value
+
+
+# ---- device-memory plumbing (PyTorch) ------------------------------------------------
+
+def upload_batch(batch, device="cuda:0", pad_bits=0):
+    """Allocate device buffers for a workloads.Batch in the library's layout and fill them.
+
+    Returns a dict with q, k_cache, v_cache, seq_lens, out (torch tensors), the
+    layout, and the host copies of the packed caches (for the CPU oracle in tests).
+    """
+    import numpy as np
+    import torch
+    from . import workloads as wl
+
+    cfg = batch.cfg
+    lay = sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+    k_host = wl.pack_cache(batch.k_rows, cfg, lay.stride_req, lay.stride_kvh, lay.stride_tok,
+                           lay.total_elems, pad_bits)
+    v_host = wl.pack_cache(batch.v_rows, cfg, lay.stride_req, lay.stride_kvh, lay.stride_tok,
+                           lay.total_elems, pad_bits)
+    dev = torch.device(device)
+    as_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
+    res = {
+        "layout": lay,
+        "k_host": k_host,
+        "v_host": v_host,
+        "q": as_dev(np.ascontiguousarray(batch.q).view(np.uint16).reshape(-1)),
+        "k_cache": as_dev(k_host),
+        "v_cache": as_dev(v_host),
+        "seq_lens": torch.from_numpy(np.ascontiguousarray(batch.seq_lens, dtype=np.int32)).to(dev),
+        "out": torch.full((cfg.n_req, cfg.n_qh, cfg.head_dim), float("nan"),
+                          dtype=torch.float16, device=dev),
+    }
+    for name in ("q", "k_cache", "v_cache", "out"):
+        assert res[name].data_ptr() % lay.base_align == 0, name
+    return res
+
+
+def run_batch(bufs, cfg, stream=None):
+    """sw_decode_attn on buffers made by upload_batch."""
+    return sw_decode_attn(bufs["q"], bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"],
+                          bufs["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len,
+                          stream)

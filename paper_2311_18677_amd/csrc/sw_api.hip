@@ -1,0 +1,314 @@
+// Host side of the C ABI declared in include/sw_decode.h: argument checks,
+// layout arithmetic, the per-(device, stream) workspace, kernel choice and
+// launch.  No torch, no oracle, no CPU fallback: without a GPU sw_decode_attn
+// reports SW_ERR_HIP.
+#include "sw_decode.h"
+#include "sw_internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <utility>
+#include <vector>
+
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+
+thread_local std::string t_last_error = "";
+
+int fail(int code, const std::string &msg)
+{
+    t_last_error = msg;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what)
+{
+    (void)hipGetLastError();   // clear the sticky error so that later calls start clean
+    return fail(SW_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+struct Workspace {
+    float *base = nullptr;
+    size_t bytes = 0;
+};
+
+std::mutex g_mu;
+std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+// tuning knobs (0 = default)
+int g_chunk = 0;
+int g_kernel = 0;
+
+// per-kernel timing
+struct ProfRec { hipEvent_t ev[4]; };
+bool g_prof_on = false;
+int g_prof_cap = 0;
+std::vector<ProfRec> g_prof;
+
+int check_shape(int n_req, int n_kvh, int head_dim, int max_len)
+{
+    if (n_req < 0 || n_kvh <= 0 || max_len <= 0)
+        return fail(SW_ERR_SHAPE, "n_req must be >= 0, n_kvh and max_len > 0");
+    if (head_dim != 64 && head_dim != 128)
+        return fail(SW_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (max_len > (1 << 24))
+        return fail(SW_ERR_SHAPE, "max_len above 2^24");
+    if ((long long)n_req * n_kvh > (1LL << 20))
+        return fail(SW_ERR_SHAPE, "n_req * n_kvh above 2^20");
+    return SW_OK;
+}
+
+// Slab of one (request, key/value head): max_len dense rows plus 8 rows of
+// padding, so that the slabs of a batch do not all start a large power of two
+// apart (workgroups stream many slabs at the same offset at the same time).
+long long slab_elems(int head_dim, int max_len)
+{
+    return (long long)(max_len + 8) * head_dim;
+}
+
+// Default positions per workgroup of the partial kernel.
+int default_chunk(int n_req, int n_kvh, int max_len)
+{
+    (void)n_req; (void)n_kvh; (void)max_len;
+    return 256;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sw_version(void) { return kVersion; }
+
+const char *sw_last_error(void) { return t_last_error.c_str(); }
+
+int sw_kv_layout(int n_req, int n_kvh, int head_dim, int max_len, sw_kv_layout_t *out)
+{
+    if (!out) return fail(SW_ERR_NULL, "out is NULL");
+    int rc = check_shape(n_req, n_kvh, head_dim, max_len);
+    if (rc != SW_OK) return rc;
+    const long long slab = slab_elems(head_dim, max_len);
+    out->dtype = SW_F16;
+    out->elem_bytes = 2;
+    out->stride_dim = 1;
+    out->stride_tok = head_dim;
+    out->stride_kvh = slab;
+    out->stride_req = slab * n_kvh;
+    out->total_elems = slab * n_kvh * (long long)n_req;
+    out->base_align = 256;
+    out->reserved = 0;
+    return SW_OK;
+}
+
+int sw_set_param(int key, int value)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    switch (key) {
+    case SW_PARAM_CHUNK:
+        if (value != 0 && (value < 64 || value > 65536 || value % SW_CHUNK_QUANTUM))
+            return fail(SW_ERR_PARAM, "chunk must be 0 or a multiple of 64 in [64, 65536]");
+        g_chunk = value;
+        return SW_OK;
+    case SW_PARAM_KERNEL:
+        if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "kernel must be 0, 1 or 2");
+        g_kernel = value;
+        return SW_OK;
+    default:
+        return fail(SW_ERR_PARAM, "unknown parameter key");
+    }
+}
+
+int sw_get_param(int key, int *value)
+{
+    if (!value) return fail(SW_ERR_NULL, "value is NULL");
+    std::lock_guard<std::mutex> lk(g_mu);
+    switch (key) {
+    case SW_PARAM_CHUNK:  *value = g_chunk;  return SW_OK;
+    case SW_PARAM_KERNEL: *value = g_kernel; return SW_OK;
+    default: return fail(SW_ERR_PARAM, "unknown parameter key");
+    }
+}
+
+int sw_prof_start(int capacity)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_prof_on) return fail(SW_ERR_STATE, "sw_prof_start called twice");
+    if (capacity <= 0 || capacity > (1 << 20)) return fail(SW_ERR_PARAM, "capacity out of range");
+    g_prof.clear();
+    g_prof.reserve((size_t)capacity);
+    g_prof_cap = capacity;
+    g_prof_on = true;
+    return SW_OK;
+}
+
+int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_prof_on) return fail(SW_ERR_STATE, "sw_prof_stop without sw_prof_start");
+    g_prof_on = false;
+    double p = 0.0, c = 0.0;
+    int n = 0, rc = SW_OK;
+    for (ProfRec &rec : g_prof) {
+        float ms0 = 0.f, ms1 = 0.f;
+        hipError_t e = hipEventSynchronize(rec.ev[3]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms0, rec.ev[0], rec.ev[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms1, rec.ev[2], rec.ev[3]);
+        if (e == hipSuccess) {
+            p += 1e3 * ms0;
+            c += 1e3 * ms1;
+            ++n;
+        } else if (rc == SW_OK) {
+            rc = fail_hip(e, "reading profile events");
+        }
+        for (hipEvent_t ev : rec.ev) (void)hipEventDestroy(ev);
+    }
+    g_prof.clear();
+    if (partial_us_sum) *partial_us_sum = p;
+    if (combine_us_sum) *combine_us_sum = c;
+    if (n_calls) *n_calls = n;
+    return rc;
+}
+
+int sw_release(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    int rc = SW_OK;
+    int cur = 0;
+    if (g_ws.empty()) return SW_OK;
+    if (hipGetDevice(&cur) != hipSuccess) cur = 0;
+    for (auto &kv : g_ws) {
+        hipError_t e = hipSetDevice(kv.first.first);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e == hipSuccess && kv.second.base) e = hipFree(kv.second.base);
+        if (e != hipSuccess && rc == SW_OK) rc = fail_hip(e, "sw_release");
+    }
+    g_ws.clear();
+    (void)hipSetDevice(cur);
+    return rc;
+}
+
+int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *seq_lens, void *out,
+                   int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                   void *stream_v)
+{
+    // ---- validation: nothing below this block runs on bad arguments, and
+    // nothing in it touches HIP ----
+    if (n_qh <= 0) return fail(SW_ERR_SHAPE, "n_qh must be > 0");
+    if (n_kvh <= 0 || n_qh % n_kvh != 0)
+        return fail(SW_ERR_SHAPE, "n_kvh must be > 0 and divide n_qh");
+    int rc = check_shape(n_req, n_kvh, head_dim, max_len);
+    if (rc != SW_OK) return rc;
+    const int group = n_qh / n_kvh;
+    if (group > 64) return fail(SW_ERR_UNSUPPORTED, "more than 64 query heads per key/value head");
+    if ((long long)n_req * n_qh > (1LL << 20)) return fail(SW_ERR_SHAPE, "n_req * n_qh above 2^20");
+    if (n_req == 0) return SW_OK;
+    if (!q || !k_cache || !v_cache || !seq_lens || !out)
+        return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens and out must be non-NULL");
+    if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u)
+        return fail(SW_ERR_ALIGN, "q, k_cache, v_cache and out must be 16-byte aligned");
+    if ((uintptr_t)seq_lens & 3u) return fail(SW_ERR_ALIGN, "seq_lens must be 4-byte aligned");
+
+    hipStream_t stream = (hipStream_t)stream_v;
+
+    int chunk, kernel;
+    bool prof;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        chunk = g_chunk;
+        kernel = g_kernel;
+        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
+    }
+    if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
+    // keep the partial kernel's grid below 2^31 workgroups
+    while (((long long)(max_len + chunk - 1) / chunk) * n_req * n_kvh > 0x7fffffffLL) chunk *= 2;
+    const int n_chunks = (max_len + chunk - 1) / chunk;
+
+    SwArgs a;
+    a.q = (const uint16_t *)q;
+    a.k = (const uint16_t *)k_cache;
+    a.v = (const uint16_t *)v_cache;
+    a.seq_lens = seq_lens;
+    a.out = (uint16_t *)out;
+    a.n_req = n_req;
+    a.n_qh = n_qh;
+    a.n_kvh = n_kvh;
+    a.group = group;
+    a.head_dim = head_dim;
+    a.max_len = max_len;
+    a.chunk = chunk;
+    a.n_chunks = n_chunks;
+    a.stride_kvh = slab_elems(head_dim, max_len);
+    a.stride_req = a.stride_kvh * n_kvh;
+    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
+
+    bool use_mfma = sw_partial_mfma_supported(a);
+    if (kernel == 1) use_mfma = false;
+    if (kernel == 2 && !use_mfma)
+        return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
+
+    // ---- workspace: slots of (head_dim + 2) floats per (request, query head, chunk) ----
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    const size_t slots = (size_t)n_req * n_qh * n_chunks;
+    const size_t o_bytes = slots * head_dim * sizeof(float);
+    const size_t need = o_bytes + slots * 2 * sizeof(float);
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        Workspace &ws = g_ws[std::make_pair(dev, stream)];
+        if (ws.bytes < need) {
+            if (ws.base) {
+                e = hipStreamSynchronize(stream);   // earlier calls on this stream may still use it
+                if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+                e = hipFree(ws.base);
+                ws.base = nullptr;
+                ws.bytes = 0;
+                if (e != hipSuccess) return fail_hip(e, "hipFree");
+            }
+            const size_t grow = need + need / 4;
+            e = hipMalloc((void **)&ws.base, grow);
+            if (e != hipSuccess) {
+                ws.base = nullptr;
+                return fail_hip(e, "hipMalloc(workspace)");
+            }
+            ws.bytes = grow;
+        }
+        a.ws_o = ws.base;
+        a.ws_ml = ws.base + slots * head_dim;
+    }
+
+    SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
+    ProfRec rec;
+    if (prof) {
+        for (int i = 0; i < 4; ++i) {
+            e = hipEventCreate(&rec.ev[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
+                return fail_hip(e, "hipEventCreate");
+            }
+        }
+        ev_p = {rec.ev[0], rec.ev[1]};
+        ev_c = {rec.ev[2], rec.ev[3]};
+    }
+
+    e = use_mfma ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
+                 : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
+    if (e == hipSuccess) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
+    if (e != hipSuccess) {
+        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        return fail_hip(e, "kernel launch");
+    }
+    if (prof) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
+        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+    }
+    return SW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal interface between the host dispatcher (sw_api.hip) and the kernel
+// translation units.  Not installed; the public ABI is include/sw_decode.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+#include <stdint.h>
+
+// Everything a kernel needs, passed by value.
+//
+// Split over context length: positions [0, L) of a request are cut into
+// chunks of `chunk` positions; workgroup (unit = r*n_kvh + g, c) of the
+// partial kernel handles chunk c of key/value head g of request r for the
+// query heads that head serves, and leaves per query head an unnormalised
+// partial result in the workspace:
+//   ws_o [((r*n_qh + h)*n_chunks + c)*head_dim + j] = sum_t 2^(s2_t - m2) * V[t][j]
+//   ws_ml[((r*n_qh + h)*n_chunks + c)*2 + {0,1}]    = m2, sum_t 2^(s2_t - m2)
+// where s2 = score * log2(e) (so that the exponentials are exp2) and m2 is
+// the chunk's maximum of s2.  Chunks at or past L are never written nor read.
+struct SwArgs {
+    const uint16_t *q;
+    const uint16_t *k;
+    const uint16_t *v;
+    const int32_t  *seq_lens;
+    uint16_t       *out;
+    float          *ws_o;
+    float          *ws_ml;
+    int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
+    int   head_dim, max_len;
+    int   chunk, n_chunks;             // n_chunks = ceil(max_len / chunk)
+    long long stride_req, stride_kvh;  // elements; the token stride is head_dim
+    float scale_log2e;                 // log2(e) / sqrt(head_dim)
+};
+
+// Optional per-kernel timing: when both are non-null the launch attaches them
+// to the dispatch so that their difference is the kernel's device time.
+struct SwLaunchEvents {
+    hipEvent_t start;
+    hipEvent_t stop;
+};
+
+// Vector-ALU partial kernel: any group size (looped in tiles of up to 8 heads).
+hipError_t sw_launch_partial_valu(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+// Matrix-core partial kernel: group sizes up to 16, head_dim 64 or 128.
+bool       sw_partial_mfma_supported(const SwArgs &a);
+hipError_t sw_launch_partial_mfma(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+// Merge of the chunks' partial results, normalisation and rounding to binary16.
+hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+
+// Granularity the chunk length must be a multiple of (all kernels).
+constexpr int SW_CHUNK_QUANTUM = 64;
+
+template <typename... KArgs, typename... Args>
+static inline hipError_t sw_launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds,
+                                   hipStream_t stream, const SwLaunchEvents *ev, Args... args)
+{
+    if (ev && ev->start && ev->stop) {
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ev->start, ev->stop, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, args...);
+    }
+    return hipGetLastError();
+}

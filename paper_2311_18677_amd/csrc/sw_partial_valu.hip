@@ -1,0 +1,229 @@
+// Partial decode attention on the vector ALUs (gfx950, wave64).
+//
+// One workgroup (4 waves) handles one chunk of one (request, key/value head)
+// for a tile of up to GT query heads of that head's group.  A K or V row of D
+// binary16 values is read by D/8 neighbouring lanes, 16 bytes each, so one
+// wave-wide load instruction fetches 64/(D/8) whole rows as one contiguous
+// kilobyte.  Scores are formed with the packed binary16 dot product
+// (fp32 accumulate) and summed across the row's lanes with DPP; the softmax
+// runs online per 16-token tile in base 2; P.V accumulates in fp32.
+// The step is the token-phase attention of the paper (section 2.2; every
+// cached position is read once, section 3.5).
+#include "sw_internal.h"
+
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+struct __attribute__((aligned(16))) Row8 { half2_t h[4]; };
+
+constexpr float kNegBig = -1.0e30f;   // below any reachable score; stays finite under subtraction
+constexpr int   kWaves  = 4;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LPR (8 or 16) neighbouring lanes that share a row; every lane gets the total.
+template <int LPR>
+__device__ __forceinline__ float row_allreduce_sum(float x)
+{
+    x += dpp_mov<0xB1>(x);    // quad_perm [1,0,3,2]
+    x += dpp_mov<0x4E>(x);    // quad_perm [2,3,0,1]
+    x += dpp_mov<0x141>(x);   // row_half_mirror: lane i <-> 7-i within 8
+    if (LPR == 16) x += dpp_mov<0x140>(x);   // row_mirror: lane i <-> 15-i within 16
+    return x;
+}
+
+template <int D, int GT>
+__global__ __launch_bounds__(64 * kWaves)
+void sw_partial_valu_kernel(SwArgs a)
+{
+    constexpr int LPR = D / 8;        // lanes per row
+    constexpr int RPW = 64 / LPR;     // rows per wave-wide load
+    constexpr int U   = 16 / RPW;     // loads per 16-token tile
+    constexpr int TPW = 16;           // tokens per wave per iteration
+
+    // blockIdx.x = c * n_units + unit: all units' chunk 0 are dispatched first,
+    // then chunk 1, ...; chunks past a request's length exit at once.
+    const int n_units = a.n_req * a.n_kvh;
+    const int c    = blockIdx.x / n_units;
+    const int unit = blockIdx.x - c * n_units;
+    const int ht   = blockIdx.y;
+    const int r    = unit / a.n_kvh;
+    const int g    = unit - r * a.n_kvh;
+
+    int L = a.seq_lens[r];
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    const int t_begin = c * a.chunk;
+    if (t_begin >= L) return;
+    const int t_end = min(L, t_begin + a.chunk);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int sub  = lane % LPR;      // which 8 dims of the row
+    const int row  = lane / LPR;      // which row of a wave-wide load
+
+    const int h0 = g * a.group + ht * GT;         // first query head of this tile
+    const int n_valid = min(GT, a.group - ht * GT);
+
+    half2_t qv[GT][4];
+#pragma unroll
+    for (int hh = 0; hh < GT; ++hh) {
+        Row8 x = {};
+        if (hh < n_valid)
+            x = *reinterpret_cast<const Row8 *>(a.q + ((long long)r * a.n_qh + h0 + hh) * D + sub * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qv[hh][i] = x.h[i];
+    }
+
+    float m[GT], l[GT], o[GT][8];
+#pragma unroll
+    for (int hh = 0; hh < GT; ++hh) {
+        m[hh] = kNegBig;
+        l[hh] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[hh][j] = 0.f;
+    }
+
+    const uint16_t *kbase = a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh + sub * 8;
+    const uint16_t *vbase = a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh + sub * 8;
+
+    for (int tile = t_begin + wave * TPW; tile < t_end; tile += kWaves * TPW) {
+        Row8 kk[U], vv[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = tile + u * RPW + row;
+            ok[u] = t < t_end;
+            kk[u] = Row8{};
+            vv[u] = Row8{};
+            if (ok[u]) {
+                kk[u] = *reinterpret_cast<const Row8 *>(kbase + (long long)t * D);
+                vv[u] = *reinterpret_cast<const Row8 *>(vbase + (long long)t * D);
+            }
+        }
+#pragma unroll
+        for (int hh = 0; hh < GT; ++hh) {
+            float s[U];
+            float mt = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float acc = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc = __builtin_amdgcn_fdot2(qv[hh][i], kk[u].h[i], acc, false);
+                acc = row_allreduce_sum<LPR>(acc);
+                s[u] = ok[u] ? acc * a.scale_log2e : -INFINITY;
+                mt = fmaxf(mt, s[u]);
+            }
+            const float m_new = fmaxf(m[hh], mt);
+            const float alpha = __builtin_amdgcn_exp2f(m[hh] - m_new);
+            m[hh] = m_new;
+            float p[U];
+            float psum = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                p[u] = __builtin_amdgcn_exp2f(s[u] - m_new);
+                psum += p[u];
+            }
+            l[hh] = l[hh] * alpha + psum;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float o0 = o[hh][2 * i] * alpha;
+                float o1 = o[hh][2 * i + 1] * alpha;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    o0 = fmaf(p[u], (float)vv[u].h[i].x, o0);
+                    o1 = fmaf(p[u], (float)vv[u].h[i].y, o1);
+                }
+                o[hh][2 * i]     = o0;
+                o[hh][2 * i + 1] = o1;
+            }
+        }
+    }
+
+    // ---- merge the RPW row groups of each wave (they saw disjoint tokens) ----
+#pragma unroll
+    for (int hh = 0; hh < GT; ++hh) {
+        float mw = m[hh];
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+        const float f = __builtin_amdgcn_exp2f(m[hh] - mw);
+        float lw = l[hh] * f;
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) lw += __shfl_xor(lw, off);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float x = o[hh][j] * f;
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
+            o[hh][j] = x;
+        }
+        m[hh] = mw;
+        l[hh] = lw;
+    }
+
+    // ---- merge the waves through LDS, write the chunk's partial result ----
+    __shared__ float sm_o[kWaves][GT][D];
+    __shared__ float sm_m[kWaves][GT];
+    __shared__ float sm_l[kWaves][GT];
+    if (row == 0) {
+#pragma unroll
+        for (int hh = 0; hh < GT; ++hh) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sm_o[wave][hh][sub * 8 + j] = o[hh][j];
+            if (sub == 0) {
+                sm_m[wave][hh] = m[hh];
+                sm_l[wave][hh] = l[hh];
+            }
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < n_valid * D; idx += 64 * kWaves) {
+        const int hh = idx / D;
+        const int j  = idx - hh * D;
+        float mx = sm_m[0][hh];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_m[w][hh]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float f = __builtin_amdgcn_exp2f(sm_m[w][hh] - mx);
+            num = fmaf(f, sm_o[w][hh][j], num);
+            den = fmaf(f, sm_l[w][hh], den);
+        }
+        const long long slot = ((long long)r * a.n_qh + h0 + hh) * a.n_chunks + c;
+        a.ws_o[slot * D + j] = num;
+        if (j == 0) {
+            a.ws_ml[slot * 2]     = mx;
+            a.ws_ml[slot * 2 + 1] = den;
+        }
+    }
+}
+
+template <int D, int GT>
+hipError_t launch(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
+{
+    const int tiles = (a.group + GT - 1) / GT;
+    dim3 grid((unsigned)((long long)a.n_req * a.n_kvh * a.n_chunks), (unsigned)tiles, 1);
+    return sw_launch(sw_partial_valu_kernel<D, GT>, grid, dim3(64 * kWaves), 0, stream, ev, a);
+}
+
+template <int D>
+hipError_t launch_d(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
+{
+    if (a.group == 1) return launch<D, 1>(a, stream, ev);
+    if (a.group == 2) return launch<D, 2>(a, stream, ev);
+    if (a.group <= 4) return launch<D, 4>(a, stream, ev);
+    return launch<D, 8>(a, stream, ev);
+}
+
+}  // namespace
+
+hipError_t sw_launch_partial_valu(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
+{
+    if ((long long)a.n_req * a.n_kvh * a.n_chunks > 0x7fffffffLL) return hipErrorInvalidValue;
+    return a.head_dim == 128 ? launch_d<128>(a, stream, ev) : launch_d<64>(a, stream, ev);
+}

@@ -1,0 +1,111 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header
+declares, answers layout queries and rejects bad arguments before any HIP call.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2311_18677_amd import binding as sw
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sw_decode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sw_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = sw.load()
+    names = declared_symbols()
+    assert set(names) == set(sw.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sw.sw_version() >= 100
+
+
+def test_kv_layout_values():
+    lay = sw.sw_kv_layout(64, 1, 128, 4096)
+    assert lay.dtype == sw.SW_F16 and lay.elem_bytes == 2
+    assert lay.stride_dim == 1 and lay.stride_tok == 128
+    assert lay.stride_kvh >= 4096 * 128 and lay.stride_req == lay.stride_kvh * 1
+    assert lay.total_elems == lay.stride_req * 64
+    assert lay.base_align >= 16 and lay.base_align % 16 == 0
+    assert (lay.stride_kvh * 2) % 256 == 0          # rows stay 256-byte aligned
+    lay = sw.sw_kv_layout(4, 8, 64, 128)
+    assert lay.stride_tok == 64 and lay.stride_req == 8 * lay.stride_kvh
+    assert lay.total_elems == 4 * lay.stride_req
+    lay = sw.sw_kv_layout(0, 8, 64, 128)
+    assert lay.total_elems == 0
+
+
+def test_kv_layout_errors():
+    assert sw.sw_kv_layout(1, 1, 96, 16, check=False)[0] == sw.SW_ERR_UNSUPPORTED
+    assert sw.sw_kv_layout(-1, 1, 64, 16, check=False)[0] == sw.SW_ERR_SHAPE
+    assert sw.sw_kv_layout(1, 0, 64, 16, check=False)[0] == sw.SW_ERR_SHAPE
+    assert sw.sw_kv_layout(1, 1, 64, 0, check=False)[0] == sw.SW_ERR_SHAPE
+    assert sw.load().sw_kv_layout(1, 1, 64, 16, None) == sw.SW_ERR_NULL
+    assert "NULL" in sw.sw_last_error()
+
+
+GOOD = dict(q=0x1000, k=0x2000, v=0x3000, lens=0x4000, out=0x5000)
+
+
+def call(q=GOOD["q"], k=GOOD["k"], v=GOOD["v"], lens=GOOD["lens"], out=GOOD["out"],
+         n_req=2, n_qh=8, n_kvh=2, d=128, max_len=64):
+    return sw.sw_decode_attn(q, k, v, lens, out, n_req, n_qh, n_kvh, d, max_len, None, check=False)
+
+
+def test_decode_attn_rejects_bad_arguments_without_touching_the_device():
+    # every call below fails validation, so none reaches a HIP call
+    assert call(q=None) == sw.SW_ERR_NULL
+    assert call(k=None) == sw.SW_ERR_NULL
+    assert call(v=None) == sw.SW_ERR_NULL
+    assert call(lens=None) == sw.SW_ERR_NULL
+    assert call(out=None) == sw.SW_ERR_NULL
+    assert call(n_req=-1) == sw.SW_ERR_SHAPE
+    assert call(n_qh=0) == sw.SW_ERR_SHAPE
+    assert call(n_kvh=0) == sw.SW_ERR_SHAPE
+    assert call(n_qh=8, n_kvh=3) == sw.SW_ERR_SHAPE
+    assert call(max_len=0) == sw.SW_ERR_SHAPE
+    assert call(max_len=(1 << 24) + 1) == sw.SW_ERR_SHAPE
+    assert call(d=96) == sw.SW_ERR_UNSUPPORTED
+    assert call(d=256) == sw.SW_ERR_UNSUPPORTED
+    assert call(n_qh=130, n_kvh=2) == sw.SW_ERR_UNSUPPORTED
+    assert call(q=0x1008) == sw.SW_ERR_ALIGN
+    assert call(k=0x2002) == sw.SW_ERR_ALIGN
+    assert call(v=0x3004) == sw.SW_ERR_ALIGN
+    assert call(out=0x5008) == sw.SW_ERR_ALIGN
+    assert call(lens=0x4002) == sw.SW_ERR_ALIGN
+    assert len(sw.sw_last_error()) > 0
+
+
+def test_empty_batch_is_ok_and_launches_nothing():
+    assert call(n_req=0) == sw.SW_OK
+    assert call(n_req=0, q=None, k=None, v=None, lens=None, out=None) == sw.SW_OK
+
+
+def test_params_roundtrip_and_validation():
+    assert sw.sw_get_param(sw.SW_PARAM_CHUNK) == 0
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 512)
+    assert sw.sw_get_param(sw.SW_PARAM_CHUNK) == 512
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
+    assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 100, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 32, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(sw.SW_PARAM_KERNEL, 3, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(99, 1, check=False) == sw.SW_ERR_PARAM
+    with pytest.raises(sw.SwError):
+        sw.sw_set_param(99, 1)
+
+
+def test_prof_state_errors():
+    lib = sw.load()
+    assert lib.sw_prof_stop(None, None, None) == sw.SW_ERR_STATE
+    assert lib.sw_prof_start(0) == sw.SW_ERR_PARAM
+    assert lib.sw_prof_start(4) == sw.SW_OK
+    assert lib.sw_prof_start(4) == sw.SW_ERR_STATE
+    p, c, n = sw.sw_prof_stop()
+    assert (p, c, n) == (0.0, 0.0, 0)

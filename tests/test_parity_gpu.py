@@ -1,0 +1,216 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Floating point within max-abs 2e-3 / row rel-L2
+1e-3; length and index handling bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2311_18677_amd import binding as sw
+from paper_2311_18677_amd import workloads as wl
+from helpers import assert_parity, oracle_on_packed
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = {"valu": 1, "mfma": 2}
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
+    yield
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
+
+
+def gpu_out(batch, pad_bits=0, stream=None, bufs=None):
+    import torch
+    if bufs is None:
+        bufs = sw.upload_batch(batch, pad_bits=pad_bits)
+    print("run", batch.cfg.name, "seed", batch.seed, "n_req", batch.cfg.n_req,
+          "chunk", sw.sw_get_param(sw.SW_PARAM_CHUNK), "kernel", sw.sw_get_param(sw.SW_PARAM_KERNEL),
+          flush=True)
+    sw.run_batch(bufs, batch.cfg, stream)
+    torch.cuda.synchronize()
+    return bufs["out"].cpu().numpy(), bufs
+
+
+
+
+@pytest.mark.parametrize("which", ["default", "valu", "mfma"])
+@pytest.mark.parametrize("name", ["tiny_mha", "llama70b_tp8", "bloom176b_tp8", "skewed_256",
+                                  "longctx_8x32k"])
+def test_configs_match_oracle(name, which):
+    batch = wl.make_batch(name)
+    if which != "default":
+        sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    try:
+        out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+            pytest.skip("no matrix-core kernel for this shape")
+        raise
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    errs = assert_parity(out, ref, name)
+    print(name, which, "max_abs %.3e row_rel_l2 %.3e whole_rel_l2 %.3e" % errs)
+
+
+GROUP_SHAPES = [  # (n_qh, n_kvh, head_dim)
+    (1, 1, 64), (2, 1, 64), (3, 3, 128), (4, 2, 128), (6, 2, 64), (3, 1, 128), (5, 1, 128),
+    (7, 1, 64), (8, 1, 64), (16, 2, 128), (14, 1, 128), (16, 1, 128), (24, 1, 128), (64, 1, 64),
+    (12, 4, 128),
+]
+
+
+@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("n_qh,n_kvh,d", GROUP_SHAPES)
+def test_group_sizes_and_ragged_lengths(n_qh, n_kvh, d, which):
+    lens = [0, 1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 127, 129, 255, 256, 257, 300, 511, 513, 700]
+    cfg = wl.custom_config("g%d_%d_%d" % (n_qh, n_kvh, d), len(lens), n_qh, n_kvh, d, 704)
+    batch = wl.make_batch(cfg, seed=1000 + n_qh * 7 + n_kvh + d, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    try:
+        out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+            pytest.skip("no matrix-core kernel for this shape")
+        raise
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, cfg.name)
+
+
+@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("chunk", [64, 128, 256, 512, 1024])
+def test_chunk_boundaries(chunk, which):
+    lens = [chunk - 1, chunk, chunk + 1, 2 * chunk - 1, 2 * chunk, 2 * chunk + 1, 3 * chunk + 7, 1]
+    cfg = wl.custom_config("cb%d" % chunk, len(lens), 8, 1, 128, 3 * chunk + 64)
+    batch = wl.make_batch(cfg, seed=2000 + chunk, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, chunk)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    try:
+        out, bufs = gpu_out(batch, pad_bits=0x7BFF)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+            pytest.skip("no matrix-core kernel for this shape")
+        raise
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, cfg.name)
+
+
+@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("n_qh,n_kvh,d", [(8, 8, 64), (8, 1, 128), (14, 14, 128)])
+def test_padding_never_reaches_the_result(n_qh, n_kvh, d, which):
+    lens = [1, 5, 64, 100, 257, 0, 300]
+    cfg = wl.custom_config("pad", len(lens), n_qh, n_kvh, d, 320)
+    batch = wl.make_batch(cfg, seed=3000 + d, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    try:
+        base, _ = gpu_out(batch, pad_bits=0)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+            pytest.skip("no matrix-core kernel for this shape")
+        raise
+    for pad in (0x7E00, 0x7BFF, 0xFC00):        # NaN, 65504, -inf
+        out, _ = gpu_out(batch, pad_bits=pad)
+        assert np.array_equal(out.view(np.uint16), base.view(np.uint16)), hex(pad)
+
+
+@pytest.mark.parametrize("which", ["valu", "mfma"])
+def test_length_edge_cases_bit_exact(which):
+    # length 1 returns the V row bit for bit; length 0 and negative give +0;
+    # lengths above max_len are clamped to max_len
+    M = 96
+    lens = [1, 0, -3, M + 50, M, 1]
+    cfg = wl.custom_config("edge", len(lens), 8, 2, 128, M)
+    batch = wl.make_batch(cfg, seed=4000, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    try:
+        out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+            pytest.skip("no matrix-core kernel for this shape")
+        raise
+    bits = out.view(np.uint16)
+    for r in (0, 5):
+        for h in range(8):
+            assert np.array_equal(bits[r, h], batch.v_rows[r][h // 4, 0].view(np.uint16))
+    assert np.all(bits[1] == 0) and np.all(bits[2] == 0)
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, "edge")
+    # the clamped request equals the same request with length M
+    batch2 = wl.make_batch(cfg, seed=4000, seq_lens=[1, 0, -3, M, M, 1])
+    out2, _ = gpu_out(batch2, pad_bits=0x7E00)
+    assert np.array_equal(out2.view(np.uint16), bits)
+
+
+@pytest.mark.parametrize("which", ["valu", "mfma"])
+def test_permutation_batch_independence_and_repeatability(which):
+    import torch
+    lens = [700, 3, 256, 1023, 64, 511, 90, 1]
+    cfg = wl.custom_config("perm", len(lens), 8, 1, 128, 1024)
+    batch = wl.make_batch(cfg, seed=5000, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    try:
+        out, bufs = gpu_out(batch)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+            pytest.skip("no matrix-core kernel for this shape")
+        raise
+    # same call again: same bits
+    out_again, _ = gpu_out(batch, bufs=bufs)
+    assert np.array_equal(out.view(np.uint16), out_again.view(np.uint16))
+    # permuted requests: permuted rows, same bits
+    perm = [5, 2, 7, 0, 3, 6, 1, 4]
+    pb = wl.Batch(cfg, batch.seed, batch.seq_lens[perm], batch.q[perm],
+                  [batch.k_rows[i] for i in perm], [batch.v_rows[i] for i in perm])
+    out_p, _ = gpu_out(pb)
+    assert np.array_equal(out_p.view(np.uint16), out.view(np.uint16)[perm])
+    # a request alone in its batch: same bits as inside the batch
+    for r in (0, 3):
+        c1 = wl.custom_config("solo", 1, 8, 1, 128, 1024)
+        sb = wl.Batch(c1, batch.seed, batch.seq_lens[r:r + 1], batch.q[r:r + 1],
+                      [batch.k_rows[r]], [batch.v_rows[r]])
+        out_s, _ = gpu_out(sb)
+        assert np.array_equal(out_s.view(np.uint16)[0], out.view(np.uint16)[r])
+
+
+def test_non_default_stream_and_two_streams():
+    import torch
+    batch = wl.make_batch("tiny_mha")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    o0, bufs = gpu_out(batch)
+    with torch.cuda.stream(s1):
+        b1 = sw.upload_batch(batch)
+    with torch.cuda.stream(s2):
+        b2 = sw.upload_batch(batch)
+    torch.cuda.synchronize()
+    sw.run_batch(b1, batch.cfg, s1)
+    sw.run_batch(b2, batch.cfg, s2)
+    torch.cuda.synchronize()
+    assert np.array_equal(b1["out"].cpu().numpy().view(np.uint16), o0.view(np.uint16))
+    assert np.array_equal(b2["out"].cpu().numpy().view(np.uint16), o0.view(np.uint16))
+
+
+def test_prof_reports_kernel_times():
+    import torch
+    batch = wl.make_batch("tiny_mha")
+    bufs = sw.upload_batch(batch)
+    sw.run_batch(bufs, batch.cfg)
+    torch.cuda.synchronize()
+    sw.sw_prof_start(3)
+    for _ in range(5):
+        sw.run_batch(bufs, batch.cfg)
+    p, c, n = sw.sw_prof_stop()
+    assert n == 3 and 0 < p < 1e5 and 0 < c < 1e5
+
+
+def test_sampled_outputs_at_full_size_in_bench_configuration():
+    """Config 2 exactly as bench.py launches it (default chunk and kernel):
+    every row against the oracle, plus the properties that hold at any size."""
+    batch = wl.make_batch("llama70b_tp8")
+    out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, "llama70b_tp8")
+    o = out.astype(np.float64)
+    for r in range(batch.cfg.n_req):
+        v = batch.v_rows[r][0].astype(np.float64)
+        assert np.all(o[r] <= v.max(axis=0) + 2e-3) and np.all(o[r] >= v.min(axis=0) - 2e-3)
