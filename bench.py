@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-attention hot path on one MI355X.
+
+A "step" is one sw_decode_attn call: one layer's decode attention for the whole
+batch (both kernels).  Inputs are resident in HBM before the timed region; the
+calls rotate over several distinct cache sets so that the K/V rows come from
+HBM, not from the last-level cache.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+LLC_BYTES = 256 << 20           # last-level (Infinity) cache the rotation must exceed 4x
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--workload", default="llama70b_tp8")
+    ap.add_argument("--sets", type=int, default=0, help="distinct cache sets (0 = enough for 4x the LLC)")
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+                    help="graph: replay a HIP graph of one rotation; eager: one host call per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--kernel", type=int, default=0)
+    return ap.parse_args()
+
+
+def make_device_set(cfg, lay, seed, torch, np, wl, dev):
+    """A cache set generated on the device: same shapes, lengths from the config's
+    recipe, values N(0,1) in binary16 (every position, so padding is arbitrary data)."""
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence(int(seed))))
+    lens = wl.draw_seq_lens(cfg, rng)
+    g = torch.Generator(device=dev)
+    g.manual_seed(int(seed))
+    bufs = {}
+    for name in ("k_cache", "v_cache"):
+        t = torch.empty(lay.total_elems, dtype=torch.float16, device=dev)
+        t.normal_(0.0, 1.0, generator=g)
+        bufs[name] = t
+    if cfg.k_row_scale:
+        prob, factor = cfg.k_row_scale
+        rows = bufs["k_cache"].view(-1, cfg.head_dim)
+        hit = torch.rand(rows.shape[0], device=dev, generator=g) < prob
+        rows[hit] *= factor
+    q = torch.empty(cfg.n_req * cfg.n_qh * cfg.head_dim, dtype=torch.float16, device=dev)
+    q.normal_(0.0, 1.0, generator=g)
+    bufs["q"] = q
+    bufs["seq_lens"] = torch.from_numpy(lens).to(dev)
+    bufs["out"] = torch.zeros((cfg.n_req, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
+    valid = np.clip(lens, 0, cfg.max_len).astype(np.int64)
+    bufs["kv_bytes"] = int(valid.sum()) * cfg.n_kvh * cfg.head_dim * 4
+    return bufs
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
+    summary for this workload (profiles/pmc_<workload>.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_%s.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("hbm_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2311_18677_amd import binding as sw
+    from paper_2311_18677_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    sw.load()
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, args.chunk)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, args.kernel)
+
+    cfg = wl.CONFIGS[args.workload]
+    lay = sw.sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+
+    # ---- inputs: set 0 from the host recipe (also the oracle's input), the rest on device
+    batch0 = wl.make_batch(cfg)
+    set0 = sw.upload_batch(batch0, device="cuda:0", pad_bits=0)
+    set0["kv_bytes"] = batch0.kv_bytes
+    n_sets = args.sets or max(2, -(-4 * LLC_BYTES // max(batch0.kv_bytes, 1)))
+    sets = [set0]
+    for i in range(1, n_sets):
+        sets.append(make_device_set(cfg, lay, wl.BASE_SEED + 1000 * cfg.seed_index + i,
+                                    torch, np, wl, dev))
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_decode_attn(s["q"], s["k_cache"], s["v_cache"], s["seq_lens"], s["out"],
+                          cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
+
+    # first call on the stream sizes the workspace (allocates); keep it out of everything timed
+    call(sets[0], stream)
+    stream.synchronize()
+
+    steps, warmup = args.steps, args.warmup
+    mode = args.mode
+    graph = None
+    if mode == "graph":
+        # one graph = one rotation over all sets; replayed ceil(steps / n_sets) times
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for s in sets:
+                    call(s, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+        except Exception as e:      # noqa: BLE001 -- report and fall back to eager launches
+            print("bench.py: graph capture failed (%s); using eager launches" % e, file=sys.stderr)
+            graph = None
+            mode = "eager"
+
+    def run_steps(n):
+        """Exactly n steps: whole rotations as graph replays, the remainder as eager calls."""
+        if graph is not None:
+            full, rem = divmod(n, n_sets)
+            with torch.cuda.stream(stream):
+                for _ in range(full):
+                    graph.replay()
+            for i in range(rem):
+                call(sets[i], stream)
+            return
+        for i in range(n):
+            call(sets[i % n_sets], stream)
+
+    run_steps(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    bytes_done = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
+    mean_bytes = bytes_done / steps
+    gbps = bytes_done / elapsed / 1e9
+    steps_per_s = steps / elapsed
+
+    # ---- per-kernel device time (HIP events attached to each dispatch, same stream, eager)
+    prof_calls = min(steps, 50 * n_sets)
+    sw.sw_prof_start(prof_calls)
+    for i in range(prof_calls):
+        call(sets[i % n_sets], stream)
+    p_us, c_us, n_rec = sw.sw_prof_stop()
+    prof_bytes = sum(sets[i % n_sets]["kv_bytes"] for i in range(n_rec)) / max(n_rec, 1)
+    partial_us = p_us / max(n_rec, 1)
+    combine_us = c_us / max(n_rec, 1)
+    achieved = prof_bytes / (partial_us * 1e-6) / 1e9 if partial_us > 0 else 0.0
+
+    # ---- parity of set 0 and the CPU baseline (the oracle as it stands, on the host cores)
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+        call(sets[0], stream)
+        stream.synchronize()
+        out = set0["out"].cpu().numpy().astype(np.float64)
+        reps, t_cpu, ref, used = 0, 0.0, None, 0
+        while t_cpu < 10.0 and reps < 50:
+            c0 = time.perf_counter()
+            ref, _, _, used = oracle.decode_attn(
+                batch0.q, set0["k_host"], set0["v_host"], batch0.seq_lens, cfg.n_req, cfg.n_qh,
+                cfg.n_kvh, cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh,
+                lay.stride_tok, return_stats=True)
+            t_cpu += time.perf_counter() - c0
+            reps += 1
+        cpu_gbps = batch0.kv_bytes * reps / t_cpu / 1e9
+        cpu_baseline = {"value": cpu_gbps, "unit": "GB/s", "cores": int(used), "kind": "oracle",
+                        "sample": "set 0 of %s (whole batch, %d K/V bytes), %d repetitions, %.1f s"
+                                  % (cfg.name, batch0.kv_bytes, reps, t_cpu),
+                        "decode_steps_per_s": reps / t_cpu}
+        diff = out - ref
+        den = np.sqrt((ref ** 2).sum(-1))
+        rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
+        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+
+    line = {
+        "metric": "achieved HBM GB/s on K/V reads (% of MI355X peak) + decode steps/sec",
+        "value": gbps,
+        "unit": "GB/s",
+        "pct_of_peak": 100.0 * gbps / HBM_PEAK_GBPS,
+        "decode_steps_per_s": steps_per_s,
+        "model_steps_per_s_attention_only": steps_per_s / cfg.n_layers,
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": 1e3 * elapsed / steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_qh": cfg.n_qh, "n_kvh": cfg.n_kvh,
+                   "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
+                   "kv_bytes_per_step": mean_bytes, "cache_sets": n_sets, "launch": mode,
+                   "chunk": sw.sw_get_param(sw.SW_PARAM_CHUNK),
+                   "kernel": sw.sw_get_param(sw.SW_PARAM_KERNEL)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(cfg.name),
+                     "kernel": "partial (dominant)", "kernel_us": partial_us,
+                     "combine_us": combine_us, "bytes_per_launch": prof_bytes,
+                     "launches_timed": n_rec},
+        "cpu_baseline": cpu_baseline,
+        "parity_set0": parity,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
