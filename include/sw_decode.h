@@ -141,7 +141,7 @@ int sw_release(void);
  * while no call is in flight.
  *   SW_PARAM_CHUNK     context positions per workgroup of the partial kernel
  *                      (split over context length); 0 = library default;
- *                      otherwise a multiple of 64 in [64, 65536].
+ *                      otherwise a power of two in [64, 65536].
  *   SW_PARAM_KERNEL    0 = library default choice, 1 = force the vector-ALU
  *                      partial kernel, 2 = force the matrix-core (MFMA)
  *                      partial kernel (SW_ERR_UNSUPPORTED at call time if the

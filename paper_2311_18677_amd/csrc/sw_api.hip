@@ -109,8 +109,8 @@ int sw_set_param(int key, int value)
     std::lock_guard<std::mutex> lk(g_mu);
     switch (key) {
     case SW_PARAM_CHUNK:
-        if (value != 0 && (value < 64 || value > 65536 || value % SW_CHUNK_QUANTUM))
-            return fail(SW_ERR_PARAM, "chunk must be 0 or a multiple of 64 in [64, 65536]");
+        if (value != 0 && (value < 64 || value > 65536 || (value & (value - 1))))
+            return fail(SW_ERR_PARAM, "chunk must be 0 or a power of two in [64, 65536]");
         g_chunk = value;
         return SW_OK;
     case SW_PARAM_KERNEL:
@@ -241,6 +241,8 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
     a.head_dim = head_dim;
     a.max_len = max_len;
     a.chunk = chunk;
+    a.chunk_shift = 0;
+    while ((1 << a.chunk_shift) < chunk) ++a.chunk_shift;
     a.n_chunks = n_chunks;
     a.stride_kvh = slab_elems(head_dim, max_len);
     a.stride_req = a.stride_kvh * n_kvh;

@@ -16,7 +16,7 @@ void sw_combine_kernel(SwArgs a)
     const int j  = threadIdx.x;
     int L = a.seq_lens[r];
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int nc = (L + a.chunk - 1) / a.chunk;
+    const int nc = (L + a.chunk - 1) >> a.chunk_shift;
     _Float16 *out = reinterpret_cast<_Float16 *>(a.out) + (long long)rh * D + j;
     if (nc == 0) {
         *out = (_Float16)0.f;

@@ -26,7 +26,7 @@ struct SwArgs {
     float          *ws_ml;
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
-    int   chunk, n_chunks;             // n_chunks = ceil(max_len / chunk)
+    int   chunk, chunk_shift, n_chunks; // chunk = 1 << chunk_shift; n_chunks = ceil(max_len / chunk)
     long long stride_req, stride_kvh;  // elements; the token stride is head_dim
     float scale_log2e;                 // log2(e) / sqrt(head_dim)
 };

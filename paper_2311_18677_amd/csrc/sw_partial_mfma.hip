@@ -37,6 +37,7 @@
 // the next V as soon as the current V has; registers stay at 128 so that four
 // workgroups (16 waves) per compute unit keep ~256 KB of loads in flight.
 #include "sw_internal.h"
+#include "sw_worklist.h"
 
 #include <type_traits>
 
@@ -70,6 +71,7 @@ __device__ __forceinline__ uint4_t load16(const uint16_t *p)
     return *reinterpret_cast<const uint4_t *>(p);
 }
 
+template <int PER>
 __global__ __launch_bounds__(64 * kWaves, 4)
 void sw_partial_mfma_kernel(SwArgs a)
 {
@@ -78,17 +80,11 @@ void sw_partial_mfma_kernel(SwArgs a)
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
 
-    const int n_units = a.n_req * a.n_kvh;
-    const int c    = blockIdx.x / n_units;
-    const int unit = blockIdx.x - c * n_units;
-    const int r    = unit / a.n_kvh;
-    const int g    = unit - r * a.n_kvh;
-
-    int L = a.seq_lens[r];
-    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int t_begin = c * a.chunk;
-    if (t_begin >= L) return;
-    const int t_end = min(L, t_begin + a.chunk);
+    const SwWork w = sw_find_work<PER>(a, blockIdx.x);
+    if (!w.valid) return;
+    const int r = w.r, g = w.g, c = w.c;
+    const int t_begin = c << a.chunk_shift;
+    const int t_end = min(w.L, t_begin + a.chunk);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -308,5 +304,11 @@ hipError_t sw_launch_partial_mfma(const SwArgs &a, hipStream_t stream, const SwL
     if (!sw_partial_mfma_supported(a)) return hipErrorNotSupported;
     const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    return sw_launch(sw_partial_mfma_kernel, dim3((unsigned)blocks), dim3(64 * kWaves), 0, stream, ev, a);
+    const dim3 grid((unsigned)blocks), block(64 * kWaves);
+    switch (sw_worklist_per(a.n_req)) {
+    case 1:  return sw_launch(sw_partial_mfma_kernel<1>, grid, block, 0, stream, ev, a);
+    case 4:  return sw_launch(sw_partial_mfma_kernel<4>, grid, block, 0, stream, ev, a);
+    case 16: return sw_launch(sw_partial_mfma_kernel<16>, grid, block, 0, stream, ev, a);
+    default: return sw_launch(sw_partial_mfma_kernel<0>, grid, block, 0, stream, ev, a);
+    }
 }

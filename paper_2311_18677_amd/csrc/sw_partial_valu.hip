@@ -10,6 +10,7 @@
 // The step is the token-phase attention of the paper (section 2.2; every
 // cached position is read once, section 3.5).
 #include "sw_internal.h"
+#include "sw_worklist.h"
 
 namespace {
 
@@ -36,7 +37,7 @@ __device__ __forceinline__ float row_allreduce_sum(float x)
     return x;
 }
 
-template <int D, int GT>
+template <int D, int GT, int PER>
 __global__ __launch_bounds__(64 * kWaves)
 void sw_partial_valu_kernel(SwArgs a)
 {
@@ -45,20 +46,12 @@ void sw_partial_valu_kernel(SwArgs a)
     constexpr int U   = 16 / RPW;     // loads per 16-token tile
     constexpr int TPW = 16;           // tokens per wave per iteration
 
-    // blockIdx.x = c * n_units + unit: all units' chunk 0 are dispatched first,
-    // then chunk 1, ...; chunks past a request's length exit at once.
-    const int n_units = a.n_req * a.n_kvh;
-    const int c    = blockIdx.x / n_units;
-    const int unit = blockIdx.x - c * n_units;
-    const int ht   = blockIdx.y;
-    const int r    = unit / a.n_kvh;
-    const int g    = unit - r * a.n_kvh;
-
-    int L = a.seq_lens[r];
-    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int t_begin = c * a.chunk;
-    if (t_begin >= L) return;
-    const int t_end = min(L, t_begin + a.chunk);
+    const SwWork w = sw_find_work<PER>(a, blockIdx.x);
+    if (!w.valid) return;
+    const int r = w.r, g = w.g, c = w.c;
+    const int ht = blockIdx.y;
+    const int t_begin = c << a.chunk_shift;
+    const int t_end = min(w.L, t_begin + a.chunk);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -208,7 +201,13 @@ hipError_t launch(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
 {
     const int tiles = (a.group + GT - 1) / GT;
     dim3 grid((unsigned)((long long)a.n_req * a.n_kvh * a.n_chunks), (unsigned)tiles, 1);
-    return sw_launch(sw_partial_valu_kernel<D, GT>, grid, dim3(64 * kWaves), 0, stream, ev, a);
+    const dim3 block(64 * kWaves);
+    switch (sw_worklist_per(a.n_req)) {
+    case 1:  return sw_launch(sw_partial_valu_kernel<D, GT, 1>, grid, block, 0, stream, ev, a);
+    case 4:  return sw_launch(sw_partial_valu_kernel<D, GT, 4>, grid, block, 0, stream, ev, a);
+    case 16: return sw_launch(sw_partial_valu_kernel<D, GT, 16>, grid, block, 0, stream, ev, a);
+    default: return sw_launch(sw_partial_valu_kernel<D, GT, 0>, grid, block, 0, stream, ev, a);
+    }
 }
 
 template <int D>

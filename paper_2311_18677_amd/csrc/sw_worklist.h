@@ -1,0 +1,113 @@
+// Workgroup -> work item mapping of the partial kernels.
+//
+// A work item is one chunk of one (request, key/value head).  How many items a
+// request has depends on its length, which only the device knows, so the grid
+// is sized for max_len and each workgroup finds its own item: the items are
+// numbered request by request (request r owns n_kvh * ceil(L_r / chunk)
+// consecutive numbers, key/value head major, chunk minor), and workgroup b
+// takes item b.  Workgroups past the last item exit.  Compared with mapping
+// blockIdx straight onto (request, head, chunk) this puts every real item at
+// the front of the dispatch order, so no item waits behind empty workgroups.
+//
+// Every wave computes the mapping on its own (no LDS, no barrier): a lane
+// holds up to kMaxPerLane consecutive requests, the per-lane counts are
+// prefix-summed across the wave with DPP, and a ballot finds the owning lane.
+// Batches of more than 64 * kMaxPerLane requests use the direct mapping.
+#pragma once
+#include "sw_internal.h"
+
+struct SwWork {
+    int  r;       // request
+    int  g;       // key/value head
+    int  c;       // chunk index
+    int  L;       // clamped length of request r
+    bool valid;   // false: this workgroup has nothing to do
+};
+
+constexpr int kSwMaxPerLane   = 16;
+constexpr int kSwMaxScanReqs  = 64 * kSwMaxPerLane;
+
+__device__ __forceinline__ int sw_clamp_len(int L, int max_len)
+{
+    return L < 0 ? 0 : (L > max_len ? max_len : L);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ int sw_wave_inclusive_scan(int x)
+{
+    // within rows of 16 lanes: lanes shifted in from outside the row read 0
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);   // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);   // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);   // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);   // row_shr:8
+    // across rows: lane 15 of a row into rows 1 and 3, then lane 31 into rows 2 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);  // row_bcast:15
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);  // row_bcast:31
+    return x;
+}
+
+// PER = requests held per lane (1, 4 or 16; 0 selects the direct mapping).
+// Must be called by all 64 lanes of a wave (uses cross-lane operations).  The
+// chunk length is a power of two, and the host keeps n_req * n_kvh * n_chunks
+// below 2^31, so item numbers fit 32 bits.
+template <int PER>
+__device__ __forceinline__ SwWork sw_find_work(const SwArgs &a, unsigned b)
+{
+    SwWork w;
+    w.valid = false;
+    w.r = w.g = w.c = w.L = 0;
+    if constexpr (PER == 0) {
+        // direct mapping: b = c * n_units + unit
+        const unsigned n_units = (unsigned)a.n_req * (unsigned)a.n_kvh;
+        const unsigned c = b / n_units, unit = b - c * n_units;
+        w.r = (int)(unit / (unsigned)a.n_kvh);
+        w.g = (int)(unit - (unsigned)w.r * (unsigned)a.n_kvh);
+        w.c = (int)c;
+        w.L = sw_clamp_len(a.seq_lens[w.r], a.max_len);
+        w.valid = ((long long)w.c << a.chunk_shift) < w.L;
+        return w;
+    } else {
+        const int lane = threadIdx.x & 63;
+        int len[PER], cnt[PER];
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int r = lane * PER + j;
+            len[j] = 0;
+            if (r < a.n_req) len[j] = sw_clamp_len(a.seq_lens[r], a.max_len);
+            cnt[j] = (len[j] + a.chunk - 1) >> a.chunk_shift;
+            mine += cnt[j];
+        }
+        const int incl = sw_wave_inclusive_scan(mine);   // chunks of all requests up to this lane's last
+        const unsigned long long hit = __ballot((unsigned)incl * (unsigned)a.n_kvh > b);
+        if (hit == 0) return w;                          // past the last item
+        const int owner = __builtin_ctzll(hit);          // first lane whose range reaches item b
+        unsigned before = (unsigned)__builtin_amdgcn_readlane(incl - mine, owner);   // chunks before the owner's requests
+        bool found = false;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const unsigned cj = (unsigned)__builtin_amdgcn_readlane(cnt[j], owner);
+            const int lj = __builtin_amdgcn_readlane(len[j], owner);
+            if (!found && (before + cj) * (unsigned)a.n_kvh > b) {
+                const unsigned rem = b - before * (unsigned)a.n_kvh;   // < cj * n_kvh
+                // the clamps below change nothing when the scan is right; they keep
+                // every later address in bounds whatever the lanes delivered
+                const unsigned gg = a.n_kvh == 1 ? 0u : rem / (cj ? cj : 1u);
+                w.r = max(0, min(owner * PER + j, a.n_req - 1));
+                w.g = (int)min(gg, (unsigned)(a.n_kvh - 1));
+                w.c = (int)(rem - (unsigned)w.g * cj) & 0x7fffffff;
+                w.L = min(max(lj, 0), a.max_len);
+                w.valid = ((long long)w.c << a.chunk_shift) < w.L;
+                found = true;
+            }
+            before += cj;
+        }
+        return w;
+    }
+}
+
+// Which mapping the host picks for a batch size.
+static inline int sw_worklist_per(int n_req)
+{
+    return n_req <= 64 ? 1 : (n_req <= 256 ? 4 : (n_req <= kSwMaxScanReqs ? kSwMaxPerLane : 0));
+}

@@ -95,6 +95,7 @@ def test_params_roundtrip_and_validation():
     sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
     assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 100, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 32, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 192, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(sw.SW_PARAM_KERNEL, 3, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(99, 1, check=False) == sw.SW_ERR_PARAM
     with pytest.raises(sw.SwError):
