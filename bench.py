@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also launch plain device copies of this size (for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings); 0 = none")
     return ap.parse_args()
 
 
@@ -110,6 +113,16 @@ def main():
         sets.append(make_device_set(cfg, lay, wl.BASE_SEED + 1000 * cfg.seed_index + i,
                                     torch, np, wl, dev))
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        # a plain copy of known size: reads N bytes and writes N bytes per launch
+        n = args.copy_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     stream = torch.cuda.Stream(device=dev)
 

@@ -146,9 +146,14 @@ int sw_release(void);
  *                      partial kernel, 2 = force the matrix-core (MFMA)
  *                      partial kernel (SW_ERR_UNSUPPORTED at call time if the
  *                      shape has no such kernel).
+ *   SW_PARAM_COMBINE   how the chunks of a request are merged: 0 = library default,
+ *                      1 = a second (combine) kernel, 2 = in the same launch, by
+ *                      the workgroup that finishes a request's head group last.
+ *                      Each is deterministic; the two differ by rounding only.
  */
 #define SW_PARAM_CHUNK   1
 #define SW_PARAM_KERNEL  2
+#define SW_PARAM_COMBINE 3
 int sw_set_param(int key, int value);
 int sw_get_param(int key, int *value);
 
@@ -158,7 +163,8 @@ int sw_get_param(int key, int *value);
  * pair of HIP events to each kernel it launches (on the call's stream), for
  * up to `capacity` calls; further calls run untimed.  sw_prof_stop waits for
  * the recorded events and reports, in microseconds summed over the recorded
- * calls, the device time of the partial kernel and of the combine kernel,
+ * calls, the device time of the partial kernel and of the combine kernel
+ * (0 when the chunks are merged in the same launch),
  * and how many calls were recorded.  Pointers are host memory.
  */
 int sw_prof_start(int capacity);

@@ -33,8 +33,10 @@ int fail_hip(hipError_t e, const char *what)
 }
 
 struct Workspace {
-    float *base = nullptr;
+    float *base = nullptr;       // partial results
     size_t bytes = 0;
+    unsigned *counters = nullptr;   // ticket counters of the single-launch variant (kept at zero)
+    size_t n_counters = 0;
 };
 
 std::mutex g_mu;
@@ -43,9 +45,10 @@ std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 // tuning knobs (0 = default)
 int g_chunk = 0;
 int g_kernel = 0;
+int g_combine = 0;
 
 // per-kernel timing
-struct ProfRec { hipEvent_t ev[4]; };
+struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
 bool g_prof_on = false;
 int g_prof_cap = 0;
 std::vector<ProfRec> g_prof;
@@ -76,6 +79,14 @@ int default_chunk(int n_req, int n_kvh, int max_len)
 {
     (void)n_req; (void)n_kvh; (void)max_len;
     return 256;
+}
+
+// Whether the last workgroup of each unit merges the chunks itself (one launch)
+// or a second kernel does.
+bool default_fused(int n_req, int n_kvh, int max_len)
+{
+    (void)n_req; (void)n_kvh; (void)max_len;
+    return false;
 }
 
 }  // namespace
@@ -117,6 +128,10 @@ int sw_set_param(int key, int value)
         if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "kernel must be 0, 1 or 2");
         g_kernel = value;
         return SW_OK;
+    case SW_PARAM_COMBINE:
+        if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "combine must be 0, 1 or 2");
+        g_combine = value;
+        return SW_OK;
     default:
         return fail(SW_ERR_PARAM, "unknown parameter key");
     }
@@ -129,6 +144,7 @@ int sw_get_param(int key, int *value)
     switch (key) {
     case SW_PARAM_CHUNK:  *value = g_chunk;  return SW_OK;
     case SW_PARAM_KERNEL: *value = g_kernel; return SW_OK;
+    case SW_PARAM_COMBINE: *value = g_combine; return SW_OK;
     default: return fail(SW_ERR_PARAM, "unknown parameter key");
     }
 }
@@ -154,9 +170,9 @@ int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls)
     int n = 0, rc = SW_OK;
     for (ProfRec &rec : g_prof) {
         float ms0 = 0.f, ms1 = 0.f;
-        hipError_t e = hipEventSynchronize(rec.ev[3]);
+        hipError_t e = hipEventSynchronize(rec.has_combine ? rec.ev[3] : rec.ev[1]);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms0, rec.ev[0], rec.ev[1]);
-        if (e == hipSuccess) e = hipEventElapsedTime(&ms1, rec.ev[2], rec.ev[3]);
+        if (e == hipSuccess && rec.has_combine) e = hipEventElapsedTime(&ms1, rec.ev[2], rec.ev[3]);
         if (e == hipSuccess) {
             p += 1e3 * ms0;
             c += 1e3 * ms1;
@@ -184,6 +200,7 @@ int sw_release(void)
         hipError_t e = hipSetDevice(kv.first.first);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess && kv.second.base) e = hipFree(kv.second.base);
+        if (e == hipSuccess && kv.second.counters) e = hipFree(kv.second.counters);
         if (e != hipSuccess && rc == SW_OK) rc = fail_hip(e, "sw_release");
     }
     g_ws.clear();
@@ -215,12 +232,13 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
 
     hipStream_t stream = (hipStream_t)stream_v;
 
-    int chunk, kernel;
+    int chunk, kernel, combine;
     bool prof;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         chunk = g_chunk;
         kernel = g_kernel;
+        combine = g_combine;
         prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
     }
     if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
@@ -253,6 +271,8 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
     if (kernel == 2 && !use_mfma)
         return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
 
+    const bool fused = combine == 0 ? default_fused(n_req, n_kvh, max_len) : combine == 2;
+
     // ---- workspace: slots of (head_dim + 2) floats per (request, query head, chunk) ----
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -282,10 +302,36 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
         }
         a.ws_o = ws.base;
         a.ws_ml = ws.base + slots * head_dim;
+        a.counters = nullptr;
+        if (fused) {
+            // one counter per (request, key/value head, head tile); n_req * n_qh covers it
+            const size_t n_cnt = (size_t)n_req * n_qh;
+            if (ws.n_counters < n_cnt) {
+                if (ws.counters) {
+                    e = hipStreamSynchronize(stream);
+                    if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+                    e = hipFree(ws.counters);
+                    ws.counters = nullptr;
+                    ws.n_counters = 0;
+                    if (e != hipSuccess) return fail_hip(e, "hipFree");
+                }
+                const size_t grow = n_cnt + n_cnt / 4 + 64;
+                e = hipMalloc((void **)&ws.counters, grow * sizeof(unsigned));
+                if (e == hipSuccess) e = hipMemset(ws.counters, 0, grow * sizeof(unsigned));
+                if (e != hipSuccess) {
+                    if (ws.counters) (void)hipFree(ws.counters);
+                    ws.counters = nullptr;
+                    return fail_hip(e, "hipMalloc(counters)");
+                }
+                ws.n_counters = grow;
+            }
+            a.counters = ws.counters;
+        }
     }
 
     SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
     ProfRec rec;
+    rec.has_combine = !fused;
     if (prof) {
         for (int i = 0; i < 4; ++i) {
             e = hipEventCreate(&rec.ev[i]);
@@ -300,7 +346,7 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
 
     e = use_mfma ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
                  : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
-    if (e == hipSuccess) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
+    if (e == hipSuccess && !fused) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
     if (e != hipSuccess) {
         if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
         return fail_hip(e, "kernel launch");

@@ -1,54 +1,92 @@
 // Second kernel of the split over context length: merges the chunks' partial
 // results of each (request, query head), normalises and rounds to binary16.
 //   m = max_c m_c;  out = sum_c 2^(m_c - m) o_c / sum_c 2^(m_c - m) l_c
-// The chunks are visited in index order, so the result's bits depend only on
-// the request's own length.
+//
+// One workgroup of 256 threads per output row: 8 chunk groups x (D/4) lanes.
+// Group k walks chunks k, k+8, k+16, ... with a running maximum (all of a
+// thread's loads for up to four chunks are in flight together), then the 8
+// groups merge through LDS in group order.  The summation order depends only
+// on the request's own chunk count, so its bits do not depend on the batch.
 #include "sw_internal.h"
 
 namespace {
 
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
+constexpr int   kGroups = 8;
+constexpr float kNegBig = -1.0e30f;
+
 template <int D>
-__global__ __launch_bounds__(D)
+__global__ __launch_bounds__(kGroups * (D / 4))
 void sw_combine_kernel(SwArgs a)
 {
-    const int rh = blockIdx.x;                 // r * n_qh + h
+    constexpr int V4 = D / 4;
+    __shared__ float4_t sm_num[kGroups][V4];
+    __shared__ float2_t sm_md[kGroups][V4];      // (running max, denominator) per group and lane
+
+    const int rh = blockIdx.x;                   // r * n_qh + h
     const int r  = rh / a.n_qh;
-    const int j  = threadIdx.x;
+    const int k  = threadIdx.x / V4;             // chunk group
+    const int j4 = threadIdx.x - k * V4;
     int L = a.seq_lens[r];
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
     const int nc = (L + a.chunk - 1) >> a.chunk_shift;
-    _Float16 *out = reinterpret_cast<_Float16 *>(a.out) + (long long)rh * D + j;
+    half4_t *out = reinterpret_cast<half4_t *>(reinterpret_cast<_Float16 *>(a.out) + (long long)rh * D) + j4;
     if (nc == 0) {
-        *out = (_Float16)0.f;
+        if (k == 0) *out = half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
         return;
     }
-    const float *ml = a.ws_ml + (long long)rh * a.n_chunks * 2;
-    const float *po = a.ws_o + (long long)rh * a.n_chunks * D + j;
-    float mx = ml[0];
-    for (int c = 1; c < nc; ++c) mx = fmaxf(mx, ml[2 * c]);
-    float num = 0.f, den = 0.f;
-    int c = 0;
-    for (; c + 4 <= nc; c += 4) {
-        float f[4], x[4], lc[4];
+    const float2_t *ml = reinterpret_cast<const float2_t *>(a.ws_ml) + (long long)rh * a.n_chunks;
+    const float4_t *po = reinterpret_cast<const float4_t *>(a.ws_o + (long long)rh * a.n_chunks * D) + j4;
+
+    float m = kNegBig, den = 0.f;
+    float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int c0 = k; c0 < nc; c0 += 4 * kGroups) {
+        float2_t mlc[4];
+        float4_t x[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            f[i]  = ml[2 * (c + i)];
-            lc[i] = ml[2 * (c + i) + 1];
-            x[i]  = po[(long long)(c + i) * D];
+        for (int u = 0; u < 4; ++u) {
+            const int c = min(c0 + u * kGroups, nc - 1);     // clamped: in bounds, masked below
+            mlc[u] = ml[c];
+            x[u]   = po[(long long)c * V4];
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float w = __builtin_amdgcn_exp2f(f[i] - mx);
-            num = fmaf(w, x[i], num);
-            den = fmaf(w, lc[i], den);
+        for (int u = 0; u < 4; ++u) {
+            if (c0 + u * kGroups < nc) {
+                const float m_new = fmaxf(m, mlc[u][0]);
+                const float f_old = __builtin_amdgcn_exp2f(m - m_new);
+                const float f_new = __builtin_amdgcn_exp2f(mlc[u][0] - m_new);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) num[t] = fmaf(f_new, x[u][t], num[t] * f_old);
+                den = fmaf(f_new, mlc[u][1], den * f_old);
+                m = m_new;
+            }
         }
     }
-    for (; c < nc; ++c) {
-        const float w = __builtin_amdgcn_exp2f(ml[2 * c] - mx);
-        num = fmaf(w, po[(long long)c * D], num);
-        den = fmaf(w, ml[2 * c + 1], den);
+    sm_num[k][j4] = num;
+    sm_md[k][j4]  = float2_t{m, den};
+    __syncthreads();
+    if (k != 0) return;
+    float mx = sm_md[0][j4][0];
+#pragma unroll
+    for (int g = 1; g < kGroups; ++g) mx = fmaxf(mx, sm_md[g][j4][0]);
+    float4_t tot = float4_t{0.f, 0.f, 0.f, 0.f};
+    float dtot = 0.f;
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+        const float2_t md = sm_md[g][j4];
+        const float f = __builtin_amdgcn_exp2f(md[0] - mx);   // empty groups: 2^(-1e30 - mx) = 0
+        const float4_t v = sm_num[g][j4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) tot[t] = fmaf(f, v[t], tot[t]);
+        dtot = fmaf(f, md[1], dtot);
     }
-    *out = (_Float16)(num / den);              // round to nearest even
+    half4_t res;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) res[t] = (_Float16)(tot[t] / dtot);   // round to nearest even
+    *out = res;
 }
 
 }  // namespace
@@ -57,6 +95,6 @@ hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunch
 {
     dim3 grid((unsigned)(a.n_req * a.n_qh));
     if (a.head_dim == 128)
-        return sw_launch(sw_combine_kernel<128>, grid, dim3(128), 0, stream, ev, a);
-    return sw_launch(sw_combine_kernel<64>, grid, dim3(64), 0, stream, ev, a);
+        return sw_launch(sw_combine_kernel<128>, grid, dim3(kGroups * 32), 0, stream, ev, a);
+    return sw_launch(sw_combine_kernel<64>, grid, dim3(kGroups * 16), 0, stream, ev, a);
 }

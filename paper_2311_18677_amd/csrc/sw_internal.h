@@ -24,6 +24,7 @@ struct SwArgs {
     uint16_t       *out;
     float          *ws_o;
     float          *ws_ml;
+    unsigned       *counters;           // single-launch variant: one ticket counter per unit, else null
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
     int   chunk, chunk_shift, n_chunks; // chunk = 1 << chunk_shift; n_chunks = ceil(max_len / chunk)

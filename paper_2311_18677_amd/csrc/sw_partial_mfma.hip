@@ -38,6 +38,7 @@
 // workgroups (16 waves) per compute unit keep ~256 KB of loads in flight.
 #include "sw_internal.h"
 #include "sw_worklist.h"
+#include "sw_fused.h"
 
 #include <type_traits>
 
@@ -51,7 +52,7 @@ constexpr int   kWaves    = 4;
 constexpr int   kD        = 128;
 constexpr int   kTile     = 32;            // tokens per wave per iteration
 constexpr int   kRowBytes = 256;           // a staged K row (chunks XOR-swizzled, no padding)
-constexpr int   kHeadStride = 132;         // floats; merge buffer [head][gq*33 + 8i + e]
+constexpr int   kHeadStride = 132;         // floats; merge buffer row = head, 128 dims + 4 of padding
 constexpr int   kWaveLds  = 16 * kHeadStride * 4;   // 8448 B per wave: K tile (8192) or merge buffer
 constexpr float kNegBig   = -1.0e30f;
 
@@ -71,7 +72,7 @@ __device__ __forceinline__ uint4_t load16(const uint16_t *p)
     return *reinterpret_cast<const uint4_t *>(p);
 }
 
-template <int PER>
+template <int PER, bool FUSED>
 __global__ __launch_bounds__(64 * kWaves, 4)
 void sw_partial_mfma_kernel(SwArgs a)
 {
@@ -79,6 +80,9 @@ void sw_partial_mfma_kernel(SwArgs a)
     __shared__ __attribute__((aligned(16))) unsigned char sm_q[16 * kRowBytes];
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
+    __shared__ int sm_flag;
+
+    if (FUSED && blockIdx.x < (unsigned)a.n_req) sw_fused_zero_rows<kD>(a, (int)blockIdx.x);
 
     const SwWork w = sw_find_work<PER>(a, blockIdx.x);
     if (!w.valid) return;
@@ -255,41 +259,47 @@ void sw_partial_mfma_kernel(SwArgs a)
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
 
-    // ---- merge the waves through LDS (each wave reuses its own K staging area)
+    // ---- merge the waves through LDS (each wave reuses its own K staging area):
+    // row = head (stride 132 floats), column = dim; this lane owns dims
+    // 32gq + 8i + e, i.e. for each i two aligned groups of four consecutive dims
     float *mo = reinterpret_cast<float *>(wlds);
     if (n16 < a.group) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                mo[n16 * kHeadStride + gq * 33 + 8 * i + e] = o[e][i];   // dim 32gq + 8i + e
+            for (int hf = 0; hf < 2; ++hf)
+                *reinterpret_cast<float4_t *>(mo + n16 * kHeadStride + 32 * gq + 8 * i + 4 * hf) =
+                    float4_t{o[4 * hf][i], o[4 * hf + 1][i], o[4 * hf + 2][i], o[4 * hf + 3][i]};
         if (gq == 0) {
             sm_m[wave][n16] = m;
             sm_l[wave][n16] = l;
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < a.group * kD; idx += 64 * kWaves) {
-        const int hh = idx >> 7;
-        const int j  = idx & 127;
+    for (int idx = threadIdx.x; idx < a.group * (kD / 4); idx += 64 * kWaves) {
+        const int hh = idx >> 5;
+        const int j4 = idx & 31;
         float mx = sm_m[0][hh];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_m[w][hh]);
-        float num = 0.f, den = 0.f;
+        float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             const float f = __builtin_amdgcn_exp2f(sm_m[w][hh] - mx);
-            const float *wo = reinterpret_cast<const float *>(lds + w * kWaveLds);
-            num = fmaf(f, wo[hh * kHeadStride + (j >> 5) * 33 + (j & 31)], num);
+            const float4_t x = *reinterpret_cast<const float4_t *>(
+                reinterpret_cast<const float *>(lds + w * kWaveLds) + hh * kHeadStride + 4 * j4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) num[t] = fmaf(f, x[t], num[t]);
             den = fmaf(f, sm_l[w][hh], den);
         }
         const long long slot = ((long long)r * a.n_qh + g * a.group + hh) * a.n_chunks + c;
-        a.ws_o[slot * kD + j] = num;
-        if (j == 0) {
-            a.ws_ml[slot * 2]     = mx;
-            a.ws_ml[slot * 2 + 1] = den;
-        }
+        sw_store_partial4(a.ws_o + slot * kD + 4 * j4, num, FUSED);
+        if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, FUSED);
     }
+    if (FUSED)
+        sw_fused_tail<kD>(a, r, g * a.group, a.group, (w.L + a.chunk - 1) >> a.chunk_shift,
+                          a.counters + (r * a.n_kvh + g), &sm_flag);
 }
 
 }  // namespace
@@ -305,10 +315,15 @@ hipError_t sw_launch_partial_mfma(const SwArgs &a, hipStream_t stream, const SwL
     const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(64 * kWaves);
-    switch (sw_worklist_per(a.n_req)) {
-    case 1:  return sw_launch(sw_partial_mfma_kernel<1>, grid, block, 0, stream, ev, a);
-    case 4:  return sw_launch(sw_partial_mfma_kernel<4>, grid, block, 0, stream, ev, a);
-    case 16: return sw_launch(sw_partial_mfma_kernel<16>, grid, block, 0, stream, ev, a);
-    default: return sw_launch(sw_partial_mfma_kernel<0>, grid, block, 0, stream, ev, a);
-    }
+    const int per = sw_worklist_per(a.n_req);
+#define SW_MFMA_CASE(P)                                                                         \
+    if (per == P)                                                                               \
+        return a.counters ? sw_launch(sw_partial_mfma_kernel<P, true>, grid, block, 0, stream, ev, a)  \
+                          : sw_launch(sw_partial_mfma_kernel<P, false>, grid, block, 0, stream, ev, a);
+    SW_MFMA_CASE(1)
+    SW_MFMA_CASE(4)
+    SW_MFMA_CASE(16)
+    SW_MFMA_CASE(0)
+#undef SW_MFMA_CASE
+    return hipErrorInvalidValue;
 }

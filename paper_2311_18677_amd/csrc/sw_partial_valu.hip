@@ -11,6 +11,7 @@
 // cached position is read once, section 3.5).
 #include "sw_internal.h"
 #include "sw_worklist.h"
+#include "sw_fused.h"
 
 namespace {
 
@@ -45,6 +46,10 @@ void sw_partial_valu_kernel(SwArgs a)
     constexpr int RPW = 64 / LPR;     // rows per wave-wide load
     constexpr int U   = 16 / RPW;     // loads per 16-token tile
     constexpr int TPW = 16;           // tokens per wave per iteration
+
+    const bool fused = a.counters != nullptr;
+    if (fused && blockIdx.y == 0 && blockIdx.x < (unsigned)a.n_req)
+        sw_fused_zero_rows<D>(a, (int)blockIdx.x);
 
     const SwWork w = sw_find_work<PER>(a, blockIdx.x);
     if (!w.valid) return;
@@ -162,6 +167,7 @@ void sw_partial_valu_kernel(SwArgs a)
     __shared__ float sm_o[kWaves][GT][D];
     __shared__ float sm_m[kWaves][GT];
     __shared__ float sm_l[kWaves][GT];
+    __shared__ int sm_flag;
     if (row == 0) {
 #pragma unroll
         for (int hh = 0; hh < GT; ++hh) {
@@ -174,25 +180,29 @@ void sw_partial_valu_kernel(SwArgs a)
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < n_valid * D; idx += 64 * kWaves) {
-        const int hh = idx / D;
-        const int j  = idx - hh * D;
+    for (int idx = threadIdx.x; idx < n_valid * (D / 4); idx += 64 * kWaves) {
+        const int hh = idx / (D / 4);
+        const int j4 = idx - hh * (D / 4);
         float mx = sm_m[0][hh];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_m[w][hh]);
-        float num = 0.f, den = 0.f;
+        for (int w2 = 1; w2 < kWaves; ++w2) mx = fmaxf(mx, sm_m[w2][hh]);
+        sw_float4_t num = sw_float4_t{0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float f = __builtin_amdgcn_exp2f(sm_m[w][hh] - mx);
-            num = fmaf(f, sm_o[w][hh][j], num);
-            den = fmaf(f, sm_l[w][hh], den);
+        for (int w2 = 0; w2 < kWaves; ++w2) {
+            const float f = __builtin_amdgcn_exp2f(sm_m[w2][hh] - mx);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) num[t] = fmaf(f, sm_o[w2][hh][4 * j4 + t], num[t]);
+            den = fmaf(f, sm_l[w2][hh], den);
         }
         const long long slot = ((long long)r * a.n_qh + h0 + hh) * a.n_chunks + c;
-        a.ws_o[slot * D + j] = num;
-        if (j == 0) {
-            a.ws_ml[slot * 2]     = mx;
-            a.ws_ml[slot * 2 + 1] = den;
-        }
+        sw_store_partial4(a.ws_o + slot * D + 4 * j4, num, fused);
+        if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, fused);
+    }
+    if (fused) {
+        const int tiles = (a.group + GT - 1) / GT;
+        sw_fused_tail<D>(a, r, h0, n_valid, (w.L + a.chunk - 1) >> a.chunk_shift,
+                         a.counters + ((long long)(r * a.n_kvh + g) * tiles + ht), &sm_flag);
     }
 }
 

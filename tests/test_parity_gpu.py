@@ -10,16 +10,26 @@ from helpers import assert_parity, oracle_on_packed
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = {"valu": 1, "mfma": 2}
+# mode -> (SW_PARAM_KERNEL, SW_PARAM_COMBINE)
+MODES = {"default": (0, 0), "valu": (1, 1), "mfma": (2, 1), "valu_fused": (1, 2), "mfma_fused": (2, 2)}
+ALL_MODES = ["valu", "mfma", "valu_fused", "mfma_fused"]
+
+
+def set_mode(which):
+    k, c = MODES[which]
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, k)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, c)
 
 
 @pytest.fixture(autouse=True)
 def _defaults():
-    sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
+    def reset():
+        sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
+        sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
+        sw.sw_set_param(sw.SW_PARAM_COMBINE, 0)
+    reset()
     yield
-    sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
+    reset()
 
 
 def gpu_out(batch, pad_bits=0, stream=None, bufs=None):
@@ -28,6 +38,7 @@ def gpu_out(batch, pad_bits=0, stream=None, bufs=None):
         bufs = sw.upload_batch(batch, pad_bits=pad_bits)
     print("run", batch.cfg.name, "seed", batch.seed, "n_req", batch.cfg.n_req,
           "chunk", sw.sw_get_param(sw.SW_PARAM_CHUNK), "kernel", sw.sw_get_param(sw.SW_PARAM_KERNEL),
+          "combine", sw.sw_get_param(sw.SW_PARAM_COMBINE),
           flush=True)
     sw.run_batch(bufs, batch.cfg, stream)
     torch.cuda.synchronize()
@@ -36,17 +47,16 @@ def gpu_out(batch, pad_bits=0, stream=None, bufs=None):
 
 
 
-@pytest.mark.parametrize("which", ["default", "valu", "mfma"])
+@pytest.mark.parametrize("which", ["default"] + ALL_MODES)
 @pytest.mark.parametrize("name", ["tiny_mha", "llama70b_tp8", "bloom176b_tp8", "skewed_256",
                                   "longctx_8x32k"])
 def test_configs_match_oracle(name, which):
     batch = wl.make_batch(name)
-    if which != "default":
-        sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    set_mode(which)
     try:
         out, bufs = gpu_out(batch, pad_bits=0x7E00)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+        if e.code == sw.SW_ERR_UNSUPPORTED and which.startswith("mfma"):
             pytest.skip("no matrix-core kernel for this shape")
         raise
     ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
@@ -61,52 +71,52 @@ GROUP_SHAPES = [  # (n_qh, n_kvh, head_dim)
 ]
 
 
-@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("which", ALL_MODES)
 @pytest.mark.parametrize("n_qh,n_kvh,d", GROUP_SHAPES)
 def test_group_sizes_and_ragged_lengths(n_qh, n_kvh, d, which):
     lens = [0, 1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 127, 129, 255, 256, 257, 300, 511, 513, 700]
     cfg = wl.custom_config("g%d_%d_%d" % (n_qh, n_kvh, d), len(lens), n_qh, n_kvh, d, 704)
     batch = wl.make_batch(cfg, seed=1000 + n_qh * 7 + n_kvh + d, seq_lens=lens)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    set_mode(which)
     try:
         out, bufs = gpu_out(batch, pad_bits=0x7E00)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+        if e.code == sw.SW_ERR_UNSUPPORTED and which.startswith("mfma"):
             pytest.skip("no matrix-core kernel for this shape")
         raise
     ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
     assert_parity(out, ref, cfg.name)
 
 
-@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("which", ALL_MODES)
 @pytest.mark.parametrize("chunk", [64, 128, 256, 512, 1024])
 def test_chunk_boundaries(chunk, which):
     lens = [chunk - 1, chunk, chunk + 1, 2 * chunk - 1, 2 * chunk, 2 * chunk + 1, 3 * chunk + 7, 1]
     cfg = wl.custom_config("cb%d" % chunk, len(lens), 8, 1, 128, 3 * chunk + 64)
     batch = wl.make_batch(cfg, seed=2000 + chunk, seq_lens=lens)
     sw.sw_set_param(sw.SW_PARAM_CHUNK, chunk)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    set_mode(which)
     try:
         out, bufs = gpu_out(batch, pad_bits=0x7BFF)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+        if e.code == sw.SW_ERR_UNSUPPORTED and which.startswith("mfma"):
             pytest.skip("no matrix-core kernel for this shape")
         raise
     ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
     assert_parity(out, ref, cfg.name)
 
 
-@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("which", ALL_MODES)
 @pytest.mark.parametrize("n_qh,n_kvh,d", [(8, 8, 64), (8, 1, 128), (14, 14, 128)])
 def test_padding_never_reaches_the_result(n_qh, n_kvh, d, which):
     lens = [1, 5, 64, 100, 257, 0, 300]
     cfg = wl.custom_config("pad", len(lens), n_qh, n_kvh, d, 320)
     batch = wl.make_batch(cfg, seed=3000 + d, seq_lens=lens)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    set_mode(which)
     try:
         base, _ = gpu_out(batch, pad_bits=0)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+        if e.code == sw.SW_ERR_UNSUPPORTED and which.startswith("mfma"):
             pytest.skip("no matrix-core kernel for this shape")
         raise
     for pad in (0x7E00, 0x7BFF, 0xFC00):        # NaN, 65504, -inf
@@ -114,7 +124,7 @@ def test_padding_never_reaches_the_result(n_qh, n_kvh, d, which):
         assert np.array_equal(out.view(np.uint16), base.view(np.uint16)), hex(pad)
 
 
-@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("which", ALL_MODES)
 def test_length_edge_cases_bit_exact(which):
     # length 1 returns the V row bit for bit; length 0 and negative give +0;
     # lengths above max_len are clamped to max_len
@@ -122,11 +132,11 @@ def test_length_edge_cases_bit_exact(which):
     lens = [1, 0, -3, M + 50, M, 1]
     cfg = wl.custom_config("edge", len(lens), 8, 2, 128, M)
     batch = wl.make_batch(cfg, seed=4000, seq_lens=lens)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    set_mode(which)
     try:
         out, bufs = gpu_out(batch, pad_bits=0x7E00)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+        if e.code == sw.SW_ERR_UNSUPPORTED and which.startswith("mfma"):
             pytest.skip("no matrix-core kernel for this shape")
         raise
     bits = out.view(np.uint16)
@@ -142,17 +152,17 @@ def test_length_edge_cases_bit_exact(which):
     assert np.array_equal(out2.view(np.uint16), bits)
 
 
-@pytest.mark.parametrize("which", ["valu", "mfma"])
+@pytest.mark.parametrize("which", ALL_MODES)
 def test_permutation_batch_independence_and_repeatability(which):
     import torch
     lens = [700, 3, 256, 1023, 64, 511, 90, 1]
     cfg = wl.custom_config("perm", len(lens), 8, 1, 128, 1024)
     batch = wl.make_batch(cfg, seed=5000, seq_lens=lens)
-    sw.sw_set_param(sw.SW_PARAM_KERNEL, KERNELS[which])
+    set_mode(which)
     try:
         out, bufs = gpu_out(batch)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and which == "mfma":
+        if e.code == sw.SW_ERR_UNSUPPORTED and which.startswith("mfma"):
             pytest.skip("no matrix-core kernel for this shape")
         raise
     # same call again: same bits
@@ -171,6 +181,28 @@ def test_permutation_batch_independence_and_repeatability(which):
                       [batch.k_rows[r]], [batch.v_rows[r]])
         out_s, _ = gpu_out(sb)
         assert np.array_equal(out_s.view(np.uint16)[0], out.view(np.uint16)[r])
+
+
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_single_launch_variant_is_repeatable_and_agrees_with_two_kernels(kernel):
+    lens = [700, 3, 256, 1023, 64, 511, 90, 1, 0, 129]
+    cfg = wl.custom_config("fz", len(lens), 8, 1, 128, 1024)
+    batch = wl.make_batch(cfg, seed=5100, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 128)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, 1)
+    two, bufs = gpu_out(batch, pad_bits=0x7E00)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, 2)
+    first = None
+    for _ in range(3):       # repeated calls: the ticket counters must come back to zero
+        bufs["out"].fill_(float("nan"))
+        one, _ = gpu_out(batch, bufs=bufs)
+        if first is None:
+            first = one.copy()
+        assert np.array_equal(one.view(np.uint16), first.view(np.uint16))
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(first, ref, "single launch")
+    assert np.max(np.abs(first.astype(np.float64) - two.astype(np.float64))) <= 2e-3
 
 
 def test_non_default_stream_and_two_streams():
