@@ -144,16 +144,20 @@ int sw_release(void);
  *                      otherwise a power of two in [64, 65536].
  *   SW_PARAM_KERNEL    0 = library default choice, 1 = force the vector-ALU
  *                      partial kernel, 2 = force the matrix-core (MFMA)
- *                      partial kernel (SW_ERR_UNSUPPORTED at call time if the
- *                      shape has no such kernel).
+ *                      partial kernel, 3 = force the matrix-core kernel that
+ *                      stages both K and V through LDS (SW_ERR_UNSUPPORTED at
+ *                      call time if the shape has no such kernel).
  *   SW_PARAM_COMBINE   how the chunks of a request are merged: 0 = library default,
  *                      1 = a second (combine) kernel, 2 = in the same launch, by
  *                      the workgroup that finishes a request's head group last.
  *                      Each is deterministic; the two differ by rounding only.
+ *   SW_PARAM_WAVES     waves per workgroup of the matrix-core partial kernel:
+ *                      0 = library default, else 4, 8 or 16.
  */
 #define SW_PARAM_CHUNK   1
 #define SW_PARAM_KERNEL  2
 #define SW_PARAM_COMBINE 3
+#define SW_PARAM_WAVES   4
 int sw_set_param(int key, int value);
 int sw_get_param(int key, int *value);
 

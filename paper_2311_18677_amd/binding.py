@@ -24,6 +24,7 @@ SW_F16 = 1
 SW_PARAM_CHUNK = 1
 SW_PARAM_KERNEL = 2
 SW_PARAM_COMBINE = 3
+SW_PARAM_WAVES = 4
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")

@@ -46,6 +46,7 @@ std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 int g_chunk = 0;
 int g_kernel = 0;
 int g_combine = 0;
+int g_waves = 0;
 
 // per-kernel timing
 struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
@@ -74,19 +75,18 @@ long long slab_elems(int head_dim, int max_len)
     return (long long)(max_len + 8) * head_dim;
 }
 
-// Default positions per workgroup of the partial kernel.
+// Default positions per workgroup of the partial kernel: a request at max_len
+// is cut into at most 16 chunks, within [256, 1024].  Short chunks give the
+// parallelism that small batches need, long chunks amortise each workgroup's
+// partial-result traffic; measured best on all five reference shapes.  The
+// choice depends on max_len alone, so a request's bits never depend on the
+// other requests of its batch.
 int default_chunk(int n_req, int n_kvh, int max_len)
 {
-    (void)n_req; (void)n_kvh; (void)max_len;
-    return 256;
-}
-
-// Whether the last workgroup of each unit merges the chunks itself (one launch)
-// or a second kernel does.
-bool default_fused(int n_req, int n_kvh, int max_len)
-{
-    (void)n_req; (void)n_kvh; (void)max_len;
-    return false;
+    (void)n_req; (void)n_kvh;
+    int chunk = 256;
+    while (chunk < 1024 && chunk * 16 < max_len) chunk *= 2;
+    return chunk;
 }
 
 }  // namespace
@@ -125,12 +125,17 @@ int sw_set_param(int key, int value)
         g_chunk = value;
         return SW_OK;
     case SW_PARAM_KERNEL:
-        if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "kernel must be 0, 1 or 2");
+        if (value < 0 || value > 3) return fail(SW_ERR_PARAM, "kernel must be 0, 1, 2 or 3");
         g_kernel = value;
         return SW_OK;
     case SW_PARAM_COMBINE:
         if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "combine must be 0, 1 or 2");
         g_combine = value;
+        return SW_OK;
+    case SW_PARAM_WAVES:
+        if (value != 0 && value != 4 && value != 8 && value != 16)
+            return fail(SW_ERR_PARAM, "waves must be 0, 4, 8 or 16");
+        g_waves = value;
         return SW_OK;
     default:
         return fail(SW_ERR_PARAM, "unknown parameter key");
@@ -145,6 +150,7 @@ int sw_get_param(int key, int *value)
     case SW_PARAM_CHUNK:  *value = g_chunk;  return SW_OK;
     case SW_PARAM_KERNEL: *value = g_kernel; return SW_OK;
     case SW_PARAM_COMBINE: *value = g_combine; return SW_OK;
+    case SW_PARAM_WAVES: *value = g_waves; return SW_OK;
     default: return fail(SW_ERR_PARAM, "unknown parameter key");
     }
 }
@@ -232,13 +238,14 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
 
     hipStream_t stream = (hipStream_t)stream_v;
 
-    int chunk, kernel, combine;
+    int chunk, kernel, combine, waves;
     bool prof;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         chunk = g_chunk;
         kernel = g_kernel;
         combine = g_combine;
+        waves = g_waves;
         prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
     }
     if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
@@ -262,14 +269,21 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
     a.chunk_shift = 0;
     while ((1 << a.chunk_shift) < chunk) ++a.chunk_shift;
     a.n_chunks = n_chunks;
+    // four waves per workgroup measured best at every chunk length; a wave walks
+    // chunk / 128 tiles of 32 positions
+    a.waves = waves ? waves : 4;
+    if (a.waves * 32 > chunk) a.waves = 4;      // a chunk of 64 still runs 4 waves (2 idle)
     a.stride_kvh = slab_elems(head_dim, max_len);
     a.stride_req = a.stride_kvh * n_kvh;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
 
-    bool use_mfma = sw_partial_mfma_supported(a);
-    if (kernel == 1) use_mfma = false;
-    if (kernel == 2 && !use_mfma)
+    // 1 = vector ALU, 2 = matrix cores (V in registers), 3 = matrix cores (K and V through LDS)
+    int which = kernel;
+    if (which == 0) which = default_kernel(a);
+    if (which == 2 && !sw_partial_mfma_supported(a))
         return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
+    if (which == 3 && !sw_partial_mfma2_supported(a))
+        return fail(SW_ERR_UNSUPPORTED, "the LDS-staged matrix-core kernel does not cover this shape");
 
     const bool fused = combine == 0 ? default_fused(n_req, n_kvh, max_len) : combine == 2;
 
@@ -344,8 +358,9 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
         ev_c = {rec.ev[2], rec.ev[3]};
     }
 
-    e = use_mfma ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
-                 : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
+    e = which == 3 ? sw_launch_partial_mfma2(a, stream, prof ? &ev_p : nullptr)
+      : which == 2 ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
+                   : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
     if (e == hipSuccess && !fused) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
     if (e != hipSuccess) {
         if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);

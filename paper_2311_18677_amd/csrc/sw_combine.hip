@@ -38,8 +38,12 @@ void sw_combine_kernel(SwArgs a)
         if (k == 0) *out = half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
         return;
     }
-    const float2_t *ml = reinterpret_cast<const float2_t *>(a.ws_ml) + (long long)rh * a.n_chunks;
-    const float4_t *po = reinterpret_cast<const float4_t *>(a.ws_o + (long long)rh * a.n_chunks * D) + j4;
+    const int h = rh - r * a.n_qh;
+    const int g = h / a.group;
+    const long long slot0 = sw_ws_slot(a, r, g, 0, h - g * a.group);   // chunk c is at slot0 + c*group
+    const float2_t *ml = reinterpret_cast<const float2_t *>(a.ws_ml) + slot0;
+    const float4_t *po = reinterpret_cast<const float4_t *>(a.ws_o + slot0 * D) + j4;
+    const long long cs = a.group;                                     // slots between consecutive chunks
 
     float m = kNegBig, den = 0.f;
     float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -49,8 +53,8 @@ void sw_combine_kernel(SwArgs a)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int c = min(c0 + u * kGroups, nc - 1);     // clamped: in bounds, masked below
-            mlc[u] = ml[c];
-            x[u]   = po[(long long)c * V4];
+            mlc[u] = ml[c * cs];
+            x[u]   = po[c * cs * V4];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

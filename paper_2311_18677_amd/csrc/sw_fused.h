@@ -59,12 +59,13 @@ __device__ __forceinline__ void sw_store_partial2(float *p, float x, float y, bo
 }
 
 // Called by every thread of the workgroup after its partial-result stores.
-//   r, h_first, n_heads : the query heads [h_first, h_first + n_heads) of request r
+//   r, g, hh_first, n_heads : heads hh_first .. hh_first + n_heads - 1 of the group of
+//                         key/value head g of request r
 //   nc                  : number of chunks of request r (>= 1)
 //   counter             : this unit's ticket counter
 //   sm_flag             : one int of LDS
 template <int D>
-__device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int h_first, int n_heads,
+__device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int hh_first, int n_heads,
                                               int nc, unsigned *counter, int *sm_flag)
 {
     __builtin_amdgcn_s_waitcnt(0);         // this thread's partial stores are acknowledged
@@ -84,9 +85,11 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int h_firs
     for (int idx = threadIdx.x; idx < n_heads * V4; idx += blockDim.x) {
         const int hh = idx / V4;
         const int j4 = idx - hh * V4;
-        const long long rh = (long long)r * a.n_qh + h_first + hh;
-        const float *ml = a.ws_ml + rh * a.n_chunks * 2;
-        const float *po = a.ws_o + rh * a.n_chunks * D + 4 * j4;
+        const long long rh = (long long)r * a.n_qh + g * a.group + hh_first + hh;
+        const long long slot0 = sw_ws_slot(a, r, g, 0, hh_first + hh);
+        const long long cs = a.group;                     // slots between consecutive chunks
+        const float *ml = a.ws_ml + slot0 * 2;
+        const float *po = a.ws_o + slot0 * D + 4 * j4;
         // running-maximum merge, four chunks' loads in flight at a time
         float m = -1.0e30f, den = 0.f;
         sw_float4_t num = sw_float4_t{0.f, 0.f, 0.f, 0.f};
@@ -95,9 +98,9 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int h_firs
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int c = min(c0 + u, nc - 1);       // clamped: in bounds, masked below
-                mlc[u] = sw_coherent_load2(ml + 2 * c);
-                x01[u] = sw_coherent_load2(po + (long long)c * D);
-                x23[u] = sw_coherent_load2(po + (long long)c * D + 2);
+                mlc[u] = sw_coherent_load2(ml + 2 * c * cs);
+                x01[u] = sw_coherent_load2(po + c * cs * D);
+                x23[u] = sw_coherent_load2(po + c * cs * D + 2);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {

@@ -8,12 +8,14 @@
 // Everything a kernel needs, passed by value.
 //
 // Split over context length: positions [0, L) of a request are cut into
-// chunks of `chunk` positions; workgroup (unit = r*n_kvh + g, c) of the
-// partial kernel handles chunk c of key/value head g of request r for the
-// query heads that head serves, and leaves per query head an unnormalised
-// partial result in the workspace:
-//   ws_o [((r*n_qh + h)*n_chunks + c)*head_dim + j] = sum_t 2^(s2_t - m2) * V[t][j]
-//   ws_ml[((r*n_qh + h)*n_chunks + c)*2 + {0,1}]    = m2, sum_t 2^(s2_t - m2)
+// chunks of `chunk` positions; a workgroup of the partial kernel handles chunk
+// c of key/value head g of request r for the query heads that head serves,
+// and leaves per query head an unnormalised partial result in the workspace.
+// The workspace is item-major, so that one workgroup writes one contiguous
+// block: with slot(r, g, c, hh) = ((r*n_kvh + g)*n_chunks + c)*group + hh for
+// the hh-th head of the group,
+//   ws_o [slot*head_dim + j] = sum_t 2^(s2_t - m2) * V[t][j]
+//   ws_ml[slot*2 + {0,1}]    = m2, sum_t 2^(s2_t - m2)
 // where s2 = score * log2(e) (so that the exponentials are exp2) and m2 is
 // the chunk's maximum of s2.  Chunks at or past L are never written nor read.
 struct SwArgs {
@@ -28,9 +30,15 @@ struct SwArgs {
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
     int   chunk, chunk_shift, n_chunks; // chunk = 1 << chunk_shift; n_chunks = ceil(max_len / chunk)
+    int   waves;                        // waves per workgroup of the matrix-core partial kernel (4, 8 or 16)
     long long stride_req, stride_kvh;  // elements; the token stride is head_dim
     float scale_log2e;                 // log2(e) / sqrt(head_dim)
 };
+
+__host__ __device__ inline long long sw_ws_slot(const SwArgs &a, int r, int g, int c, int hh)
+{
+    return (((long long)r * a.n_kvh + g) * a.n_chunks + c) * a.group + hh;
+}
 
 // Optional per-kernel timing: when both are non-null the launch attaches them
 // to the dispatch so that their difference is the kernel's device time.
@@ -44,6 +52,9 @@ hipError_t sw_launch_partial_valu(const SwArgs &a, hipStream_t stream, const SwL
 // Matrix-core partial kernel: group sizes up to 16, head_dim 64 or 128.
 bool       sw_partial_mfma_supported(const SwArgs &a);
 hipError_t sw_launch_partial_mfma(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+// Matrix-core partial kernel with both K and V staged through LDS (4 or 8 waves).
+bool       sw_partial_mfma2_supported(const SwArgs &a);
+hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 // Merge of the chunks' partial results, normalisation and rounding to binary16.
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 

@@ -11,7 +11,7 @@
 // each request's whole cached context that the token phase consists of
 // (paper sections 2.2 and 3.5).
 //
-// One workgroup = kWaves waves = one chunk of one (request, key/value head).
+// One workgroup = WAVES waves = one chunk of one (request, key/value head).
 // Each wave owns 32-token tiles of the chunk and keeps its own running
 // softmax state; the waves merge through LDS at the end.
 //
@@ -48,13 +48,15 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
 
-constexpr int   kWaves    = 4;
 constexpr int   kD        = 128;
 constexpr int   kTile     = 32;            // tokens per wave per iteration
 constexpr int   kRowBytes = 256;           // a staged K row (chunks XOR-swizzled, no padding)
 constexpr int   kHeadStride = 132;         // floats; merge buffer row = head, 128 dims + 4 of padding
 constexpr int   kWaveLds  = 16 * kHeadStride * 4;   // 8448 B per wave: K tile (8192) or merge buffer
 constexpr float kNegBig   = -1.0e30f;
+// Cache policy of the K/V stream: non-temporal (read once; must not push the
+// partial results, which are written and read back, out of L2).
+constexpr int   kStream   = 2;
 
 static_assert(kTile * kRowBytes <= kWaveLds, "K tile must fit in the wave's LDS area");
 
@@ -67,19 +69,14 @@ union Frag {
     half8_t h;
 };
 
-__device__ __forceinline__ uint4_t load16(const uint16_t *p)
-{
-    return *reinterpret_cast<const uint4_t *>(p);
-}
-
-template <int PER, bool FUSED>
-__global__ __launch_bounds__(64 * kWaves, 4)
+template <int WAVES, int PER, bool FUSED>
+__global__ __launch_bounds__(64 * WAVES, 4)
 void sw_partial_mfma_kernel(SwArgs a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kWaveLds];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
     __shared__ __attribute__((aligned(16))) unsigned char sm_q[16 * kRowBytes];
-    __shared__ float sm_m[kWaves][16];
-    __shared__ float sm_l[kWaves][16];
+    __shared__ float sm_m[WAVES][16];
+    __shared__ float sm_l[WAVES][16];
     __shared__ int sm_flag;
 
     if (FUSED && blockIdx.x < (unsigned)a.n_req) sw_fused_zero_rows<kD>(a, (int)blockIdx.x);
@@ -101,11 +98,12 @@ void sw_partial_mfma_kernel(SwArgs a)
     // 4w + i/16 and therefore fetches chunk slot ^ row.
     {
         const int row = 4 * wave + gq;
-        if (row < a.group) {
+        // zero rows first, loads second: no LDS store follows a pending global->LDS load
+        if (row < 16 && row >= a.group)
+            *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
+        if (row < a.group) {       // group <= 16: waves past the fourth stage nothing
             const uint16_t *src = a.q + ((long long)r * a.n_qh + g * a.group + row) * kD + 8 * (n16 ^ row);
             __builtin_amdgcn_global_load_lds(src, sm_q + wave * 1024, 16, 0, 0);
-        } else {
-            *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
         }
     }
 
@@ -128,7 +126,7 @@ void sw_partial_mfma_kernel(SwArgs a)
             const int rho = 4 * n + gq;
             const int tk  = min(t0 + rho, t_end - 1);
             const uint16_t *src = kbase + (long long)tk * kD + 8 * (n16 ^ (rho & 15));
-            __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, kStream);
         }
     };
     // V tile -> registers: lane group gq takes the 8 tokens its P operand will
@@ -138,7 +136,7 @@ void sw_partial_mfma_kernel(SwArgs a)
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
             const int tv = min(t0 + (n < 4 ? 4 * gq + n : 16 + 4 * gq + (n - 4)), t_end - 1);
-            vreg[n] = load16(vbase + (long long)tv * kD + n16 * 8);
+            vreg[n] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(vbase + (long long)tv * kD + n16 * 8));
         }
     };
 
@@ -248,9 +246,9 @@ void sw_partial_mfma_kernel(SwArgs a)
     __builtin_amdgcn_s_barrier();
 
     if (ti < n_tiles) {
-        while (ti + kWaves < n_tiles) {
-            process_tile(t_begin + ti * kTile, t_begin + (ti + kWaves) * kTile, std::true_type{});
-            ti += kWaves;
+        while (ti + WAVES < n_tiles) {
+            process_tile(t_begin + ti * kTile, t_begin + (ti + WAVES) * kTile, std::true_type{});
+            ti += WAVES;
         }
         process_tile(t_begin + ti * kTile, 0, std::false_type{});
     }
@@ -276,16 +274,16 @@ void sw_partial_mfma_kernel(SwArgs a)
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < a.group * (kD / 4); idx += 64 * kWaves) {
+    for (int idx = threadIdx.x; idx < a.group * (kD / 4); idx += 64 * WAVES) {
         const int hh = idx >> 5;
         const int j4 = idx & 31;
         float mx = sm_m[0][hh];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_m[w][hh]);
+        for (int w = 1; w < WAVES; ++w) mx = fmaxf(mx, sm_m[w][hh]);
         float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
+        for (int w = 0; w < WAVES; ++w) {
             const float f = __builtin_amdgcn_exp2f(sm_m[w][hh] - mx);
             const float4_t x = *reinterpret_cast<const float4_t *>(
                 reinterpret_cast<const float *>(lds + w * kWaveLds) + hh * kHeadStride + 4 * j4);
@@ -293,12 +291,12 @@ void sw_partial_mfma_kernel(SwArgs a)
             for (int t = 0; t < 4; ++t) num[t] = fmaf(f, x[t], num[t]);
             den = fmaf(f, sm_l[w][hh], den);
         }
-        const long long slot = ((long long)r * a.n_qh + g * a.group + hh) * a.n_chunks + c;
+        const long long slot = sw_ws_slot(a, r, g, c, hh);
         sw_store_partial4(a.ws_o + slot * kD + 4 * j4, num, FUSED);
         if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, FUSED);
     }
     if (FUSED)
-        sw_fused_tail<kD>(a, r, g * a.group, a.group, (w.L + a.chunk - 1) >> a.chunk_shift,
+        sw_fused_tail<kD>(a, r, g, 0, a.group, (w.L + a.chunk - 1) >> a.chunk_shift,
                           a.counters + (r * a.n_kvh + g), &sm_flag);
 }
 
@@ -314,16 +312,18 @@ hipError_t sw_launch_partial_mfma(const SwArgs &a, hipStream_t stream, const SwL
     if (!sw_partial_mfma_supported(a)) return hipErrorNotSupported;
     const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)blocks), block(64 * kWaves);
+    const dim3 grid((unsigned)blocks);
     const int per = sw_worklist_per(a.n_req);
-#define SW_MFMA_CASE(P)                                                                         \
-    if (per == P)                                                                               \
-        return a.counters ? sw_launch(sw_partial_mfma_kernel<P, true>, grid, block, 0, stream, ev, a)  \
-                          : sw_launch(sw_partial_mfma_kernel<P, false>, grid, block, 0, stream, ev, a);
-    SW_MFMA_CASE(1)
-    SW_MFMA_CASE(4)
-    SW_MFMA_CASE(16)
-    SW_MFMA_CASE(0)
+#define SW_MFMA_CASE(W, P)                                                                            \
+    if (a.waves == W && per == P)                                                                     \
+        return a.counters                                                                             \
+            ? sw_launch(sw_partial_mfma_kernel<W, P, true>, grid, dim3(64 * W), 0, stream, ev, a)     \
+            : sw_launch(sw_partial_mfma_kernel<W, P, false>, grid, dim3(64 * W), 0, stream, ev, a);
+#define SW_MFMA_WAVES(W) SW_MFMA_CASE(W, 1) SW_MFMA_CASE(W, 4) SW_MFMA_CASE(W, 16) SW_MFMA_CASE(W, 0)
+    SW_MFMA_WAVES(4)
+    SW_MFMA_WAVES(8)
+    SW_MFMA_WAVES(16)
+#undef SW_MFMA_WAVES
 #undef SW_MFMA_CASE
     return hipErrorInvalidValue;
 }

@@ -1,0 +1,322 @@
+// Partial decode attention on the matrix cores, deep-pipelined variant
+// (gfx950, wave64), head_dim 128, up to 16 query heads per key/value head.
+//
+// Same contractions, operand layouts and softmax as the kernel in
+// sw_partial_mfma.hip (S^T = K Q^T and O^T = V^T P^T on
+// v_mfma_f32_16x16x32_f16, head = lane%16), for the token phase's read of the
+// whole cached context (paper sections 2.2 and 3.5).  The difference is how V
+// travels: here BOTH K and V tiles go global->LDS, so no registers are held
+// while data is in flight and all of a wave's loads are of one kind, which
+// lets the waits count exactly.  A wave then keeps the next tile's K and V
+// requests in flight while it computes the current tile:
+//
+//   wait K(i) | QK(i) from LDS | request K(i+1) | softmax(i) |
+//   wait V(i) | V(i) LDS->registers | request V(i+1) | transpose, PV(i)
+//
+// Each wave owns 16 KB of LDS (K tile + V tile), so two 4-wave workgroups fit a
+// compute unit; with chunks of several tiles per wave the memory pipeline stays
+// busy through compute and epilogue phases.
+#include "sw_internal.h"
+#include "sw_worklist.h"
+#include "sw_fused.h"
+
+#include <type_traits>
+
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+
+constexpr int   kD        = 128;
+constexpr int   kTile     = 32;            // tokens per wave per iteration
+constexpr int   kRowBytes = 256;           // a staged K row (chunks XOR-swizzled, no padding)
+constexpr int   kHeadStride = 132;         // floats; merge buffer row = head, 128 dims + 4 of padding
+constexpr int   kTileBytes = kTile * kRowBytes;         // 8192
+constexpr int   kWaveLds  = 2 * kTileBytes;             // K tile + V tile; the merge buffer reuses it
+constexpr float kNegBig   = -1.0e30f;
+// Cache policy of the K/V stream: non-temporal (read once; must not push the
+// partial results, which are written and read back, out of L2).
+constexpr int   kStream   = 2;
+
+static_assert(16 * kHeadStride * 4 <= kWaveLds, "merge buffer must fit in the wave's LDS area");
+
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (n < 64),
+// leaving the other counters unconstrained.
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+union Frag {
+    uint4_t u;
+    half8_t h;
+};
+
+template <int WAVES, int PER, bool FUSED>
+__global__ __launch_bounds__(64 * WAVES, 2)
+void sw_partial_mfma2_kernel(SwArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
+    __shared__ __attribute__((aligned(16))) unsigned char sm_q[16 * kRowBytes];
+    __shared__ float sm_m[WAVES][16];
+    __shared__ float sm_l[WAVES][16];
+    __shared__ int sm_flag;
+
+    if (FUSED && blockIdx.x < (unsigned)a.n_req) sw_fused_zero_rows<kD>(a, (int)blockIdx.x);
+
+    const SwWork w = sw_find_work<PER>(a, blockIdx.x);
+    if (!w.valid) return;
+    const int r = w.r, g = w.g, c = w.c;
+    const int t_begin = c << a.chunk_shift;
+    const int t_end = min(w.L, t_begin + a.chunk);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int n16  = lane & 15;     // head (B operand / output column), token (A operand of QK), dim chunk (A operand of PV)
+    const int gq   = lane >> 4;     // k-slot group
+
+    // ---- Q^T for the B operands goes to LDS once per workgroup (row = head, chunks
+    // swizzled like K's; heads past the group are zero columns).  Wave w covers
+    // rows 4w .. 4w+3 with one global->LDS load: lane i lands in slot i%16 of row
+    // 4w + i/16 and therefore fetches chunk slot ^ row.
+    {
+        const int row = 4 * wave + gq;
+        // zero rows first, loads second: no LDS store follows a pending global->LDS load
+        if (row < 16 && row >= a.group)
+            *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
+        if (row < a.group) {       // group <= 16: waves past the fourth stage nothing
+            const uint16_t *src = a.q + ((long long)r * a.n_qh + g * a.group + row) * kD + 8 * (n16 ^ row);
+            __builtin_amdgcn_global_load_lds(src, sm_q + wave * 1024, 16, 0, 0);
+        }
+    }
+
+    float m = kNegBig, l = 0.f;
+    float4_t o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t *kbase = a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh;
+    const uint16_t *vbase = a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh;
+    unsigned char *wlds = lds + wave * kWaveLds;
+
+    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+
+    // K tile -> LDS, asynchronously.  Rows past the chunk's end re-read its last
+    // row (in bounds, result masked below).
+    auto issue_k = [&](int t0) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int rho = 4 * n + gq;
+            const int tk  = min(t0 + rho, t_end - 1);
+            const uint16_t *src = kbase + (long long)tk * kD + 8 * (n16 ^ (rho & 15));
+            __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, kStream);
+        }
+    };
+    // V tile -> LDS, asynchronously, whole rows in token order (row t0 + 4n + gq by
+    // instruction n).
+    unsigned char *vlds = wlds + kTileBytes;
+    auto issue_v = [&](int t0) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int tv = min(t0 + 4 * n + gq, t_end - 1);
+            __builtin_amdgcn_global_load_lds(vbase + (long long)tv * kD + n16 * 8, vlds + n * 1024, 16, 0, kStream);
+        }
+    };
+
+    // One tile: the wave's loads for this tile are in flight on entry (K first,
+    // then V).  MORE says whether the wave has a further tile, whose loads are
+    // then issued from here; it is a compile-time flag so that the waits in
+    // between can count exactly which loads are still outstanding.
+    auto process_tile = [&](int t0, int t0_next, auto more_c) {
+        constexpr bool MORE = decltype(more_c)::value;
+
+        // ---- S^T = K Q^T : two 16-token blocks, four 32-dim steps.
+        // Outstanding, oldest first: K(t0) x8, V(t0) x8.
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        float4_t sacc[2];
+        sacc[0] = float4_t{0.f, 0.f, 0.f, 0.f};
+        sacc[1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int off = n16 * kRowBytes + (((4 * kk + gq) ^ n16) << 4);   // row n16, chunk 4kk+gq
+            Frag qb, k0, k1;
+            qb.u = *reinterpret_cast<const uint4_t *>(sm_q + off);
+            k0.u = *reinterpret_cast<const uint4_t *>(wlds + off);
+            k1.u = *reinterpret_cast<const uint4_t *>(wlds + 16 * kRowBytes + off);
+            sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0.h, qb.h, sacc[0], 0, 0, 0);
+            sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1.h, qb.h, sacc[1], 0, 0, 0);
+        }
+        // the K tile has been read into registers: its LDS area may be refilled
+        if (MORE) issue_k(t0_next);
+
+        // ---- online softmax, base 2; this lane: head n16, tokens t0 + 16tb + 4gq + i
+        float s[8];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[4 * tb + i] = sacc[tb][i] * a.scale_log2e;
+        // only a wave's last tile can reach past the chunk's end
+        const bool ragged = !MORE && t0 + kTile > t_end;
+        if (ragged) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (t0 + 16 * tb + 4 * gq + i >= t_end) s[4 * tb + i] = -INFINITY;
+        }
+        float mt = s[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) mt = fmaxf(mt, s[j]);
+        mt = fmaxf(mt, __shfl_xor(mt, 16));
+        mt = fmaxf(mt, __shfl_xor(mt, 32));
+        const float m_new = fmaxf(m, mt);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        float p[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            p[j] = __builtin_amdgcn_exp2f(s[j] - m_new);
+            psum += p[j];
+        }
+        l = l * alpha + psum;
+        Frag phi, plo;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const _Float16 hi = (_Float16)p[j];
+            phi.h[j] = hi;
+            plo.h[j] = (_Float16)(p[j] - (float)hi);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= alpha;
+
+        // ---- V(t0): LDS -> registers.  Lane group gq takes the 8 tokens its P operand
+        // holds, 4gq .. 4gq+3 and 16+4gq .. 16+4gq+3.
+        // Outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile.
+        if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        uint4_t vreg[8];
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int row = n < 4 ? 4 * gq + n : 16 + 4 * gq + (n - 4);
+            vreg[n] = *reinterpret_cast<const uint4_t *>(vlds + row * kRowBytes + n16 * 16);
+        }
+        if (ragged) {
+            // weights of the re-read rows are exactly 0; clear the rows too so that
+            // a non-finite value in the last valid row cannot turn 0 * x into NaN
+#pragma unroll
+            for (int n = 0; n < 8; ++n)
+                if (t0 + (n < 4 ? 4 * gq + n : 16 + 4 * gq + (n - 4)) >= t_end) vreg[n] = uint4_t{0u, 0u, 0u, 0u};
+        }
+        // the V tile is in registers: its LDS area may be refilled
+        if (MORE) {
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the LDS reads above have returned
+            issue_v(t0_next);
+        }
+
+        // ---- O^T += V^T P^T : block e covers dims 8*row + e (row = MFMA row)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int w2 = e >> 1;
+            const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            Frag va;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                va.u[j] = __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], sel);
+            o[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, phi.h, o[e], 0, 0, 0);
+            o[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, plo.h, o[e], 0, 0, 0);
+        }
+    };
+
+
+    int ti = wave;
+    if (ti < n_tiles) {
+        issue_k(t_begin + ti * kTile);
+        issue_v(t_begin + ti * kTile);
+    }
+    // Q must be in LDS before any wave goes on; the tile loads stay in flight
+    // across the barrier.  Vector-memory operations complete in issue order, so
+    // "at most the 16 tile loads outstanding" means this wave's Q load is done.
+    if (ti < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(16) & 0xc07f);   // vmcnt(16), lgkmcnt(0)
+    else              __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & 0xc07f);    // vmcnt(0),  lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+
+    if (ti < n_tiles) {
+        while (ti + WAVES < n_tiles) {
+            process_tile(t_begin + ti * kTile, t_begin + (ti + WAVES) * kTile, std::true_type{});
+            ti += WAVES;
+        }
+        process_tile(t_begin + ti * kTile, 0, std::false_type{});
+    }
+
+    // ---- the lane groups summed disjoint tokens into l
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+
+    // ---- merge the waves through LDS (each wave reuses its own K staging area):
+    // row = head (stride 132 floats), column = dim; this lane owns dims
+    // 32gq + 8i + e, i.e. for each i two aligned groups of four consecutive dims
+    float *mo = reinterpret_cast<float *>(wlds);
+    if (n16 < a.group) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                *reinterpret_cast<float4_t *>(mo + n16 * kHeadStride + 32 * gq + 8 * i + 4 * hf) =
+                    float4_t{o[4 * hf][i], o[4 * hf + 1][i], o[4 * hf + 2][i], o[4 * hf + 3][i]};
+        if (gq == 0) {
+            sm_m[wave][n16] = m;
+            sm_l[wave][n16] = l;
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < a.group * (kD / 4); idx += 64 * WAVES) {
+        const int hh = idx >> 5;
+        const int j4 = idx & 31;
+        float mx = sm_m[0][hh];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) mx = fmaxf(mx, sm_m[w][hh]);
+        float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            const float f = __builtin_amdgcn_exp2f(sm_m[w][hh] - mx);
+            const float4_t x = *reinterpret_cast<const float4_t *>(
+                reinterpret_cast<const float *>(lds + w * kWaveLds) + hh * kHeadStride + 4 * j4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) num[t] = fmaf(f, x[t], num[t]);
+            den = fmaf(f, sm_l[w][hh], den);
+        }
+        const long long slot = sw_ws_slot(a, r, g, c, hh);
+        sw_store_partial4(a.ws_o + slot * kD + 4 * j4, num, FUSED);
+        if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, FUSED);
+    }
+    if (FUSED)
+        sw_fused_tail<kD>(a, r, g, 0, a.group, (w.L + a.chunk - 1) >> a.chunk_shift,
+                          a.counters + (r * a.n_kvh + g), &sm_flag);
+}
+
+}  // namespace
+
+bool sw_partial_mfma2_supported(const SwArgs &a)
+{
+    return a.head_dim == kD && a.group <= 16 && (a.waves == 4 || a.waves == 8);
+}
+
+hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
+{
+    if (!sw_partial_mfma2_supported(a)) return hipErrorNotSupported;
+    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks);
+    const int per = sw_worklist_per(a.n_req);
+#define SW_MFMA2_CASE(W, P)                                                                            \
+    if (a.waves == W && per == P)                                                                     \
+        return a.counters                                                                             \
+            ? sw_launch(sw_partial_mfma2_kernel<W, P, true>, grid, dim3(64 * W), 0, stream, ev, a)     \
+            : sw_launch(sw_partial_mfma2_kernel<W, P, false>, grid, dim3(64 * W), 0, stream, ev, a);
+#define SW_MFMA2_WAVES(W) SW_MFMA2_CASE(W, 1) SW_MFMA2_CASE(W, 4) SW_MFMA2_CASE(W, 16) SW_MFMA2_CASE(W, 0)
+    SW_MFMA2_WAVES(4)
+    SW_MFMA2_WAVES(8)
+#undef SW_MFMA2_WAVES
+#undef SW_MFMA2_CASE
+    return hipErrorInvalidValue;
+}

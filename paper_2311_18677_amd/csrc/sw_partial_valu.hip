@@ -18,6 +18,16 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 struct __attribute__((aligned(16))) Row8 { half2_t h[4]; };
 
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte load with the non-temporal hint
+__device__ __forceinline__ Row8 stream_load(const uint16_t *p)
+{
+    union { uint4_t u; Row8 r; } x;
+    x.u = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(p));
+    return x.r;
+}
+
 constexpr float kNegBig = -1.0e30f;   // below any reachable score; stays finite under subtraction
 constexpr int   kWaves  = 4;
 
@@ -98,8 +108,9 @@ void sw_partial_valu_kernel(SwArgs a)
             kk[u] = Row8{};
             vv[u] = Row8{};
             if (ok[u]) {
-                kk[u] = *reinterpret_cast<const Row8 *>(kbase + (long long)t * D);
-                vv[u] = *reinterpret_cast<const Row8 *>(vbase + (long long)t * D);
+                // non-temporal: read once, must not push the partial results out of L2
+                kk[u] = stream_load(kbase + (long long)t * D);
+                vv[u] = stream_load(vbase + (long long)t * D);
             }
         }
 #pragma unroll
@@ -195,13 +206,13 @@ void sw_partial_valu_kernel(SwArgs a)
             for (int t = 0; t < 4; ++t) num[t] = fmaf(f, sm_o[w2][hh][4 * j4 + t], num[t]);
             den = fmaf(f, sm_l[w2][hh], den);
         }
-        const long long slot = ((long long)r * a.n_qh + h0 + hh) * a.n_chunks + c;
+        const long long slot = sw_ws_slot(a, r, g, c, ht * GT + hh);
         sw_store_partial4(a.ws_o + slot * D + 4 * j4, num, fused);
         if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, fused);
     }
     if (fused) {
         const int tiles = (a.group + GT - 1) / GT;
-        sw_fused_tail<D>(a, r, h0, n_valid, (w.L + a.chunk - 1) >> a.chunk_shift,
+        sw_fused_tail<D>(a, r, g, ht * GT, n_valid, (w.L + a.chunk - 1) >> a.chunk_shift,
                          a.counters + ((long long)(r * a.n_kvh + g) * tiles + ht), &sm_flag);
     }
 }

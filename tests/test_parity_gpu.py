@@ -11,8 +11,9 @@ from helpers import assert_parity, oracle_on_packed
 pytestmark = pytest.mark.gpu
 
 # mode -> (SW_PARAM_KERNEL, SW_PARAM_COMBINE)
-MODES = {"default": (0, 0), "valu": (1, 1), "mfma": (2, 1), "valu_fused": (1, 2), "mfma_fused": (2, 2)}
-ALL_MODES = ["valu", "mfma", "valu_fused", "mfma_fused"]
+MODES = {"default": (0, 0), "valu": (1, 1), "mfma": (2, 1), "mfma2": (3, 1),
+         "valu_fused": (1, 2), "mfma_fused": (2, 2), "mfma2_fused": (3, 2)}
+ALL_MODES = ["valu", "mfma", "mfma2", "valu_fused", "mfma_fused", "mfma2_fused"]
 
 
 def set_mode(which):
@@ -183,7 +184,7 @@ def test_permutation_batch_independence_and_repeatability(which):
         assert np.array_equal(out_s.view(np.uint16)[0], out.view(np.uint16)[r])
 
 
-@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("kernel", [1, 2, 3])
 def test_single_launch_variant_is_repeatable_and_agrees_with_two_kernels(kernel):
     lens = [700, 3, 256, 1023, 64, 511, 90, 1, 0, 129]
     cfg = wl.custom_config("fz", len(lens), 8, 1, 128, 1024)
