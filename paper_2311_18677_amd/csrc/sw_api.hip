@@ -89,6 +89,21 @@ int default_chunk(int n_req, int n_kvh, int max_len)
     return chunk;
 }
 
+// Which partial kernel serves a shape when the caller has not forced one.
+int default_kernel(const SwArgs &a)
+{
+    if (sw_partial_mfma2_supported(a)) return 3;
+    return sw_partial_mfma_supported(a) ? 2 : 1;
+}
+
+// Whether the last workgroup of each unit merges the chunks itself (one launch)
+// or a second kernel does.  The second kernel measured faster on every shape.
+bool default_fused(int n_req, int n_kvh, int max_len)
+{
+    (void)n_req; (void)n_kvh; (void)max_len;
+    return false;
+}
+
 }  // namespace
 
 extern "C" {
