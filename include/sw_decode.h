@@ -95,7 +95,7 @@ int sw_kv_layout(int n_req, int n_kvh, int head_dim, int max_len, sw_kv_layout_t
  *   out       DEVICE, binary16, dense [n_req][n_qh][head_dim].  Fully
  *             overwritten (rows of requests with length 0 become +0).
  *   n_req >= 0; n_qh, n_kvh > 0 with n_qh % n_kvh == 0 and n_qh / n_kvh <= 64;
- *   head_dim in {64, 128}; 0 < max_len <= 2^24; n_req * n_qh and
+ *   head_dim in {64, 128}; 0 < max_len <= 2^23; n_req * n_qh and
  *   n_req * n_kvh at most 2^20.
  *   stream    a hipStream_t passed as void*; NULL is the default stream.
  *

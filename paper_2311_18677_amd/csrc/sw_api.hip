@@ -60,8 +60,8 @@ int check_shape(int n_req, int n_kvh, int head_dim, int max_len)
         return fail(SW_ERR_SHAPE, "n_req must be >= 0, n_kvh and max_len > 0");
     if (head_dim != 64 && head_dim != 128)
         return fail(SW_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
-    if (max_len > (1 << 24))
-        return fail(SW_ERR_SHAPE, "max_len above 2^24");
+    if (max_len > (1 << 23))
+        return fail(SW_ERR_SHAPE, "max_len above 2^23");
     if ((long long)n_req * n_kvh > (1LL << 20))
         return fail(SW_ERR_SHAPE, "n_req * n_kvh above 2^20");
     return SW_OK;

@@ -69,7 +69,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
     const int t_end = min(w.L, t_begin + a.chunk);
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
     const int n16  = lane & 15;     // head (B operand / output column), token (A operand of QK), dim chunk (A operand of PV)
     const int gq   = lane >> 4;     // k-slot group
 
@@ -93,8 +93,10 @@ void sw_partial_mfma2_kernel(SwArgs a)
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    const uint16_t *kbase = a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh;
-    const uint16_t *vbase = a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh;
+    // slab bases are wave-uniform; rows are addressed with 32-bit byte offsets from
+    // them (a slab is below 4 GiB: max_len <= 2^23 rows of 256 bytes)
+    const char *kbase = reinterpret_cast<const char *>(a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    const char *vbase = reinterpret_cast<const char *>(a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh);
     unsigned char *wlds = lds + wave * kWaveLds;
 
     const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
@@ -106,7 +108,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
         for (int n = 0; n < 8; ++n) {
             const int rho = 4 * n + gq;
             const int tk  = min(t0 + rho, t_end - 1);
-            const uint16_t *src = kbase + (long long)tk * kD + 8 * (n16 ^ (rho & 15));
+            const char *src = kbase + (((unsigned)tk << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
             __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, kStream);
         }
     };
@@ -117,7 +119,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
             const int tv = min(t0 + 4 * n + gq, t_end - 1);
-            __builtin_amdgcn_global_load_lds(vbase + (long long)tv * kD + n16 * 8, vlds + n * 1024, 16, 0, kStream);
+            __builtin_amdgcn_global_load_lds(vbase + (((unsigned)tv << 8) | (unsigned)(n16 << 4)), vlds + n * 1024, 16, 0, kStream);
         }
     };
 

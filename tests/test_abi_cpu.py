@@ -71,7 +71,7 @@ def test_decode_attn_rejects_bad_arguments_without_touching_the_device():
     assert call(n_kvh=0) == sw.SW_ERR_SHAPE
     assert call(n_qh=8, n_kvh=3) == sw.SW_ERR_SHAPE
     assert call(max_len=0) == sw.SW_ERR_SHAPE
-    assert call(max_len=(1 << 24) + 1) == sw.SW_ERR_SHAPE
+    assert call(max_len=(1 << 23) + 1) == sw.SW_ERR_SHAPE
     assert call(d=96) == sw.SW_ERR_UNSUPPORTED
     assert call(d=256) == sw.SW_ERR_UNSUPPORTED
     assert call(n_qh=130, n_kvh=2) == sw.SW_ERR_UNSUPPORTED
