@@ -30,6 +30,24 @@ void sw_combine_kernel(SwArgs a)
     const int r  = rh / a.n_qh;
     const int k  = threadIdx.x / V4;             // chunk group
     const int j4 = threadIdx.x - k * V4;
+    const int h = rh - r * a.n_qh;
+    const int g = h / a.group;
+    const long long slot0 = sw_ws_slot(a, r, g, 0, h - g * a.group);   // chunk c is at slot0 + c*group
+    const float2_t *ml = reinterpret_cast<const float2_t *>(a.ws_ml) + slot0;
+    const float4_t *po = reinterpret_cast<const float4_t *>(a.ws_o + slot0 * D) + j4;
+    const long long cs = a.group;                                     // slots between consecutive chunks
+
+    // The first round of partial results is requested together with the length:
+    // slots up to n_chunks exist whether or not they were written, so the loads are
+    // in bounds, and what lies at or past the request's chunk count is never used.
+    float2_t mlc[4];
+    float4_t x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = min(k + u * kGroups, a.n_chunks - 1);
+        mlc[u] = ml[c * cs];
+        x[u]   = po[c * cs * V4];
+    }
     int L = a.seq_lens[r];
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
     const int nc = (L + a.chunk - 1) >> a.chunk_shift;
@@ -38,23 +56,17 @@ void sw_combine_kernel(SwArgs a)
         if (k == 0) *out = half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
         return;
     }
-    const int h = rh - r * a.n_qh;
-    const int g = h / a.group;
-    const long long slot0 = sw_ws_slot(a, r, g, 0, h - g * a.group);   // chunk c is at slot0 + c*group
-    const float2_t *ml = reinterpret_cast<const float2_t *>(a.ws_ml) + slot0;
-    const float4_t *po = reinterpret_cast<const float4_t *>(a.ws_o + slot0 * D) + j4;
-    const long long cs = a.group;                                     // slots between consecutive chunks
 
     float m = kNegBig, den = 0.f;
     float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
     for (int c0 = k; c0 < nc; c0 += 4 * kGroups) {
-        float2_t mlc[4];
-        float4_t x[4];
+        if (c0 != k) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = min(c0 + u * kGroups, nc - 1);     // clamped: in bounds, masked below
-            mlc[u] = ml[c * cs];
-            x[u]   = po[c * cs * V4];
+            for (int u = 0; u < 4; ++u) {
+                const int c = min(c0 + u * kGroups, nc - 1);     // clamped: in bounds, masked below
+                mlc[u] = ml[c * cs];
+                x[u]   = po[c * cs * V4];
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

@@ -99,6 +99,10 @@ def test_params_roundtrip_and_validation():
     assert sw.sw_set_param(sw.SW_PARAM_KERNEL, 4, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(sw.SW_PARAM_COMBINE, 3, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_get_param(sw.SW_PARAM_COMBINE) == 0
+    assert sw.sw_set_param(sw.SW_PARAM_WAVES, 5, check=False) == sw.SW_ERR_PARAM
+    sw.sw_set_param(sw.SW_PARAM_WAVES, 8)
+    assert sw.sw_get_param(sw.SW_PARAM_WAVES) == 8
+    sw.sw_set_param(sw.SW_PARAM_WAVES, 0)
     assert sw.sw_set_param(99, 1, check=False) == sw.SW_ERR_PARAM
     with pytest.raises(sw.SwError):
         sw.sw_set_param(99, 1)

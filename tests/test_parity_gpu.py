@@ -28,6 +28,7 @@ def _defaults():
         sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
         sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
         sw.sw_set_param(sw.SW_PARAM_COMBINE, 0)
+        sw.sw_set_param(sw.SW_PARAM_WAVES, 0)
     reset()
     yield
     reset()
@@ -204,6 +205,43 @@ def test_single_launch_variant_is_repeatable_and_agrees_with_two_kernels(kernel)
     ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
     assert_parity(first, ref, "single launch")
     assert np.max(np.abs(first.astype(np.float64) - two.astype(np.float64))) <= 2e-3
+
+
+@pytest.mark.parametrize("which", ["valu", "mfma", "mfma2"])
+@pytest.mark.parametrize("n_req", [65, 300, 1100])
+def test_many_requests_exercise_every_work_map(n_req, which):
+    # 65 / 300 / 1100 requests select the 4-per-lane scan, the 16-per-lane scan and
+    # the direct block -> (request, chunk) mapping of the partial kernels
+    rng = np.random.Generator(np.random.Philox(6000 + n_req))
+    lens = rng.integers(0, 200, size=n_req).astype(np.int32)
+    lens[::17] = 0
+    lens[5] = 192
+    cfg = wl.custom_config("many%d" % n_req, n_req, 8, 2, 128, 192)
+    batch = wl.make_batch(cfg, seed=6000 + n_req, seq_lens=lens)
+    set_mode(which)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 64)
+    out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, cfg.name)
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("kernel", [2, 3])
+def test_waves_per_workgroup(kernel, waves):
+    lens = [1000, 37, 512, 513, 0, 256]
+    cfg = wl.custom_config("w%d" % waves, len(lens), 8, 1, 128, 1024)
+    batch = wl.make_batch(cfg, seed=7000 + waves, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    sw.sw_set_param(sw.SW_PARAM_WAVES, waves)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 512)
+    try:
+        out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    except sw.SwError as e:
+        if e.code == sw.SW_ERR_UNSUPPORTED and kernel == 3 and waves == 16:
+            pytest.skip("the LDS-staged kernel runs 4 or 8 waves")
+        raise
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, cfg.name)
 
 
 def test_non_default_stream_and_two_streams():
