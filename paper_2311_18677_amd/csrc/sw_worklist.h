@@ -2,12 +2,12 @@
 //
 // A work item is one chunk of one (request, key/value head).  How many items a
 // request has depends on its length, which only the device knows, so the grid
-// is sized for max_len and each workgroup finds its own item: the items are
-// numbered request by request (request r owns n_kvh * ceil(L_r / chunk)
-// consecutive numbers, key/value head major, chunk minor), and workgroup b
-// takes item b.  Workgroups past the last item exit.  Compared with mapping
-// blockIdx straight onto (request, head, chunk) this puts every real item at
-// the front of the dispatch order, so no item waits behind empty workgroups.
+// workgroups find their items themselves: the items are numbered request by
+// request (request r owns n_kvh * ceil(L_r / chunk) consecutive numbers,
+// key/value head major, chunk minor), and workgroup b takes items b,
+// b + gridDim.x, ... up to the last one.  Compared with mapping blockIdx
+// straight onto (request, head, chunk) no launched workgroup is empty once the
+// grid is no larger than what the device holds at a time.
 //
 // Every wave computes the mapping on its own (no LDS, no barrier): a lane
 // holds up to kMaxPerLane consecutive requests, the per-lane counts are
@@ -47,11 +47,49 @@ __device__ __forceinline__ int sw_wave_inclusive_scan(int x)
 }
 
 // PER = requests held per lane (1, 4 or 16; 0 selects the direct mapping).
-// Must be called by all 64 lanes of a wave (uses cross-lane operations).  The
-// chunk length is a power of two, and the host keeps n_req * n_kvh * n_chunks
-// below 2^31, so item numbers fit 32 bits.
+// The chunk length is a power of two, and the host keeps
+// n_req * n_kvh * n_chunks below 2^31, so item numbers fit 32 bits.
+//
+// The lookup is split in two so that a workgroup that walks several items
+// (item b, b + gridDim.x, ...) reads the lengths only once: sw_scan_lens leaves
+// each lane with its requests' lengths and chunk counts and the wave-wide prefix
+// sum, sw_lookup finds an item from that state with a ballot and lane reads.
+// Both must be called by all 64 lanes of a wave.
 template <int PER>
-__device__ __forceinline__ SwWork sw_find_work(const SwArgs &a, unsigned b)
+struct SwScan {
+    int len[PER > 0 ? PER : 1];
+    int cnt[PER > 0 ? PER : 1];
+    int mine;          // chunks of this lane's requests
+    int incl;          // chunks of all requests up to this lane's last
+    unsigned total;    // number of item slots to walk (for PER > 0: exactly the real items)
+};
+
+template <int PER>
+__device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
+{
+    SwScan<PER> s;
+    if constexpr (PER == 0) {
+        s.len[0] = s.cnt[0] = s.mine = s.incl = 0;
+        s.total = (unsigned)a.n_req * (unsigned)a.n_kvh * (unsigned)a.n_chunks;
+    } else {
+        const int lane = threadIdx.x & 63;
+        s.mine = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int r = lane * PER + j;
+            s.len[j] = 0;
+            if (r < a.n_req) s.len[j] = sw_clamp_len(a.seq_lens[r], a.max_len);
+            s.cnt[j] = (s.len[j] + a.chunk - 1) >> a.chunk_shift;
+            s.mine += s.cnt[j];
+        }
+        s.incl = sw_wave_inclusive_scan(s.mine);
+        s.total = (unsigned)__builtin_amdgcn_readlane(s.incl, 63) * (unsigned)a.n_kvh;
+    }
+    return s;
+}
+
+template <int PER>
+__device__ __forceinline__ SwWork sw_lookup(const SwArgs &a, const SwScan<PER> &s, unsigned b)
 {
     SwWork w;
     w.valid = false;
@@ -67,27 +105,15 @@ __device__ __forceinline__ SwWork sw_find_work(const SwArgs &a, unsigned b)
         w.valid = ((long long)w.c << a.chunk_shift) < w.L;
         return w;
     } else {
-        const int lane = threadIdx.x & 63;
-        int len[PER], cnt[PER];
-        int mine = 0;
-#pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            const int r = lane * PER + j;
-            len[j] = 0;
-            if (r < a.n_req) len[j] = sw_clamp_len(a.seq_lens[r], a.max_len);
-            cnt[j] = (len[j] + a.chunk - 1) >> a.chunk_shift;
-            mine += cnt[j];
-        }
-        const int incl = sw_wave_inclusive_scan(mine);   // chunks of all requests up to this lane's last
-        const unsigned long long hit = __ballot((unsigned)incl * (unsigned)a.n_kvh > b);
+        const unsigned long long hit = __ballot((unsigned)s.incl * (unsigned)a.n_kvh > b);
         if (hit == 0) return w;                          // past the last item
         const int owner = __builtin_ctzll(hit);          // first lane whose range reaches item b
-        unsigned before = (unsigned)__builtin_amdgcn_readlane(incl - mine, owner);   // chunks before the owner's requests
+        unsigned before = (unsigned)__builtin_amdgcn_readlane(s.incl - s.mine, owner);   // chunks before the owner's requests
         bool found = false;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            const unsigned cj = (unsigned)__builtin_amdgcn_readlane(cnt[j], owner);
-            const int lj = __builtin_amdgcn_readlane(len[j], owner);
+            const unsigned cj = (unsigned)__builtin_amdgcn_readlane(s.cnt[j], owner);
+            const int lj = __builtin_amdgcn_readlane(s.len[j], owner);
             if (!found && (before + cj) * (unsigned)a.n_kvh > b) {
                 const unsigned rem = b - before * (unsigned)a.n_kvh;   // < cj * n_kvh
                 // the clamps below change nothing when the scan is right; they keep
@@ -104,6 +130,14 @@ __device__ __forceinline__ SwWork sw_find_work(const SwArgs &a, unsigned b)
         }
         return w;
     }
+}
+
+// One-item form: workgroup b handles item b only.
+template <int PER>
+__device__ __forceinline__ SwWork sw_find_work(const SwArgs &a, unsigned b)
+{
+    const SwScan<PER> s = sw_scan_lens<PER>(a);
+    return sw_lookup<PER>(a, s, b);
 }
 
 // Which mapping the host picks for a batch size.
