@@ -5,10 +5,6 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
-#include <map>
-#include <mutex>
-#include <utility>
-
 // Everything a kernel needs, passed by value.
 //
 // Split over context length: positions [0, L) of a request are cut into
@@ -75,25 +71,4 @@ static inline hipError_t sw_launch(void (*kernel)(KArgs...), dim3 grid, dim3 blo
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, args...);
     }
     return hipGetLastError();
-}
-
-// How many workgroups of `kernel` the current device holds at a time (cached).
-template <typename... KArgs>
-static inline int sw_resident_blocks(void (*kernel)(KArgs...), int block_threads)
-{
-    static std::mutex mu;
-    static std::map<std::pair<const void *, int>, int> cache;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    std::lock_guard<std::mutex> lk(mu);
-    auto key = std::make_pair(reinterpret_cast<const void *>(kernel), dev);
-    auto it = cache.find(key);
-    if (it != cache.end()) return it->second;
-    int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block_threads, 0) != hipSuccess || per_cu < 1)
-        per_cu = 1;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-        cus = 256;
-    (void)hipGetLastError();
-    return cache[key] = per_cu * cus;
 }
