@@ -82,6 +82,7 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int
     if (!*sm_flag) return;
 
     constexpr int V4 = D / 4;
+    constexpr int kBatch = 8;
     for (int idx = threadIdx.x; idx < n_heads * V4; idx += blockDim.x) {
         const int hh = idx / V4;
         const int j4 = idx - hh * V4;
@@ -90,20 +91,20 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int
         const long long cs = a.group;                     // slots between consecutive chunks
         const float *ml = a.ws_ml + slot0 * 2;
         const float *po = a.ws_o + slot0 * D + 4 * j4;
-        // running-maximum merge, four chunks' loads in flight at a time
+        // running-maximum merge, kBatch chunks' loads in flight at a time
         float m = -1.0e30f, den = 0.f;
         sw_float4_t num = sw_float4_t{0.f, 0.f, 0.f, 0.f};
-        for (int c0 = 0; c0 < nc; c0 += 4) {
-            sw_float2_t mlc[4], x01[4], x23[4];
+        for (int c0 = 0; c0 < nc; c0 += kBatch) {
+            sw_float2_t mlc[kBatch], x01[kBatch], x23[kBatch];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kBatch; ++u) {
                 const int c = min(c0 + u, nc - 1);       // clamped: in bounds, masked below
                 mlc[u] = sw_coherent_load2(ml + 2 * c * cs);
                 x01[u] = sw_coherent_load2(po + c * cs * D);
                 x23[u] = sw_coherent_load2(po + c * cs * D + 2);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kBatch; ++u) {
                 if (c0 + u < nc) {
                     const float m_new = fmaxf(m, mlc[u][0]);
                     const float f_old = __builtin_amdgcn_exp2f(m - m_new);
