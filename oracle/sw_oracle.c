@@ -27,6 +27,10 @@
  * that is double.  Each (r, h) unit is computed sequentially by one thread, so
  * the result does not depend on the thread count.
  *
+ * sw_oracle_decode_attn_paged is the same step over a block-table cache
+ * (pinned against the dense routine: identity and shuffled block tables must
+ * give bit-equal results).
+ *
  * Pins: closed forms (one token, identical keys, a dominant key), brute force
  * against a dense matrix formulation, shift / permutation invariance,
  * convexity, the chunk-merge identity, GQA-as-replicated-MHA and a one-hot-V
@@ -169,6 +173,83 @@ int sw_oracle_decode_attn(const uint16_t *q, const uint16_t *k, const uint16_t *
                        m_out ? m_out + u : NULL, l_out ? l_out + u : NULL);
         }
         free(scores);
+    }
+    return failed ? -4 : used;
+}
+
+/*
+ * Block-table ("paged") variant.  The paper's prototype keeps the KV cache in
+ * fixed-size blocks (section 5.1: the cache is shipped block by block); the
+ * step is the same attention, only the addressing differs: positions
+ * [i*block_size, (i+1)*block_size) of request r live in pool block
+ * block_table[r*max_blocks + i], and element (b, g, t, j) of a pool -- block
+ * b, key/value head g, position t inside the block, dimension j -- is at
+ *     b*stride_block + g*stride_kvh + t*stride_tok + j.
+ * Lengths are clamped to [0, max_blocks*block_size]; block ids are clamped to
+ * [0, n_blocks-1].  Each (request, head) unit gathers its rows into a dense
+ * temporary and runs the same two-pass routine as above.
+ */
+int sw_oracle_decode_attn_paged(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
+                                const int32_t *block_table, const int32_t *seq_lens, double *ref,
+                                int n_req, int n_qh, int n_kvh, int head_dim,
+                                int block_size, int max_blocks, int n_blocks,
+                                int64_t stride_block, int64_t stride_kvh, int64_t stride_tok,
+                                int n_threads)
+{
+    if (n_req < 0 || n_qh <= 0 || n_kvh <= 0 || head_dim <= 0 || block_size <= 0 ||
+        max_blocks <= 0 || n_blocks <= 0) return -1;
+    if (n_qh % n_kvh != 0) return -2;
+    if (n_req == 0) return 1;
+    if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !ref) return -3;
+
+    const int group = n_qh / n_kvh;
+    const int64_t max_len = (int64_t)max_blocks * block_size;
+    const int64_t units = (int64_t)n_req * n_qh;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    if ((int64_t)n_threads > units) n_threads = (int)units;
+    used = n_threads;
+#else
+    (void)n_threads;
+#endif
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(n_threads)
+#endif
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)max_len);
+        uint16_t *kd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
+        uint16_t *vd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
+        if (!scores || !kd || !vd) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t u = 0; u < units; ++u) {
+            if (!scores || !kd || !vd) continue;
+            int r = (int)(u / n_qh);
+            int h = (int)(u % n_qh);
+            int g = h / group;
+            int64_t L64 = seq_lens[r];
+            int L = (int)(L64 < 0 ? 0 : (L64 > max_len ? max_len : L64));
+            for (int t = 0; t < L; ++t) {
+                int b = clampi(block_table[(int64_t)r * max_blocks + t / block_size], 0, n_blocks - 1);
+                int64_t off = (int64_t)b * stride_block + (int64_t)g * stride_kvh +
+                              (int64_t)(t % block_size) * stride_tok;
+                memcpy(kd + (size_t)t * head_dim, k_pool + off, sizeof(uint16_t) * (size_t)head_dim);
+                memcpy(vd + (size_t)t * head_dim, v_pool + off, sizeof(uint16_t) * (size_t)head_dim);
+            }
+            attend_one(q + ((int64_t)r * n_qh + h) * head_dim, kd, vd, L, head_dim, head_dim, scores,
+                       ref + u * head_dim, NULL, NULL);
+        }
+        free(scores);
+        free(kd);
+        free(vd);
     }
     return failed ? -4 : used;
 }

@@ -162,3 +162,51 @@ def dense_layout(cfg):
     sg = cfg.max_len * d
     sr = cfg.n_kvh * sg
     return sr, sg, st, cfg.n_req * sr
+
+
+def pack_paged(k_rows, v_rows, cfg, block_size, stride_block, stride_kvh, stride_tok, n_blocks,
+               seed=0, pad_bits=0, spare_bits=None):
+    """Scatter compact valid rows into K and V block pools with a shuffled block table.
+
+    Request r gets ceil(L_r / block_size) pool blocks drawn without replacement from
+    a seeded permutation of all n_blocks, so neighbouring positions land in
+    unrelated blocks; blocks that no request owns, the unused tail of a request's
+    last block and stride padding hold pad_bits.  Table entries past a request's
+    last block hold spare_bits (default: an id far out of range), which the
+    library must never follow.
+    Returns (k_pool, v_pool, block_table) as flat uint16 / uint16 / int32 [n_req, max_blocks].
+    """
+    d = cfg.head_dim
+    max_blocks = -(-cfg.max_len // block_size)
+    need = sum(-(-blk.shape[1] // block_size) for blk in k_rows)
+    if need > n_blocks:
+        raise ValueError("pool of %d blocks cannot hold %d" % (n_blocks, need))
+    total = int(n_blocks) * int(stride_block)
+    k_pool = np.full(total, np.uint16(pad_bits), dtype=np.uint16)
+    v_pool = np.full(total, np.uint16(pad_bits), dtype=np.uint16)
+    shape = (n_blocks, cfg.n_kvh, block_size, d)
+    strides = (2 * stride_block, 2 * stride_kvh, 2 * stride_tok, 2)
+    kv = np.lib.stride_tricks.as_strided(k_pool, shape=shape, strides=strides, writeable=True)
+    vv = np.lib.stride_tricks.as_strided(v_pool, shape=shape, strides=strides, writeable=True)
+    order = np.random.Generator(np.random.Philox(int(seed) + 77)).permutation(n_blocks)
+    table = np.full((cfg.n_req, max_blocks), 0x3FFFFFF0 if spare_bits is None else spare_bits,
+                    dtype=np.int32)
+    nxt = 0
+    for r, (kb, vb) in enumerate(zip(k_rows, v_rows)):
+        L = kb.shape[1]
+        for i in range(-(-L // block_size)):
+            b = int(order[nxt])
+            nxt += 1
+            table[r, i] = b
+            n = min(block_size, L - i * block_size)
+            kv[b, :, :n, :] = kb[:, i * block_size:i * block_size + n, :].view(np.uint16)
+            vv[b, :, :n, :] = vb[:, i * block_size:i * block_size + n, :].view(np.uint16)
+    return k_pool, v_pool, table
+
+
+def dense_paged_layout(cfg, block_size):
+    """Plain dense pool strides (for CPU-only tests that have no library to ask)."""
+    st = cfg.head_dim
+    sg = block_size * st
+    sb = cfg.n_kvh * sg
+    return sb, sg, st

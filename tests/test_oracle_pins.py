@@ -279,3 +279,44 @@ def test_tiny_config_matches_brute_force():
         kd[r, :, :L] = b.k_rows[r]
         vd[r, :, :L] = b.v_rows[r]
     assert np.allclose(ref, brute(b.q, kd, vd, b.seq_lens), rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("block_size", [4, 16, 32])
+def test_paged_oracle_equals_dense_oracle(block_size):
+    # the block-table routine is pinned to the dense one: whatever the block size
+    # and however the blocks are scattered, the result has the same bits
+    cfg = wl.custom_config("pg", 5, 6, 2, 64, 96)
+    b = wl.make_batch(cfg, seed=91, seq_lens=[96, 1, 0, 33, 64])
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    kb = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0x7E00)
+    vb = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0x7E00)
+    dense = oracle.decode_attn(b.q, kb, vb, b.seq_lens, 5, 6, 2, 64, 96, sr, sg, st)
+    sb, sgp, stp = wl.dense_paged_layout(cfg, block_size)
+    sb += 64                                     # padded block stride
+    n_blocks = 5 * (96 // block_size) + 3
+    for seed in (0, 1):
+        kp, vp, table = wl.pack_paged(b.k_rows, b.v_rows, cfg, block_size, sb, sgp, stp, n_blocks,
+                                      seed=seed, pad_bits=0x7E00)
+        paged = oracle.decode_attn_paged(b.q, kp, vp, table, b.seq_lens, 5, 6, 2, 64, block_size,
+                                         96 // block_size, n_blocks, sb, sgp, stp)
+        assert np.array_equal(paged, dense)
+    assert np.all(np.isfinite(dense))
+
+
+def test_paged_oracle_matches_brute_force_and_clamps():
+    cfg = wl.custom_config("pg2", 3, 4, 4, 64, 32)
+    b = wl.make_batch(cfg, seed=92, seq_lens=[7, 32, 19])
+    sb, sg, st = wl.dense_paged_layout(cfg, 8)
+    kp, vp, table = wl.pack_paged(b.k_rows, b.v_rows, cfg, 8, sb, sg, st, 12, seed=3)
+    kd = np.zeros((3, 4, 32, 64), np.float16)
+    vd = np.zeros((3, 4, 32, 64), np.float16)
+    for r in range(3):
+        L = b.seq_lens[r]
+        kd[r, :, :L] = b.k_rows[r]
+        vd[r, :, :L] = b.v_rows[r]
+    got = oracle.decode_attn_paged(b.q, kp, vp, table, b.seq_lens, 3, 4, 4, 64, 8, 4, 12, sb, sg, st)
+    assert np.allclose(got, brute(b.q, kd, vd, b.seq_lens), rtol=1e-12, atol=1e-14)
+    # lengths above max_blocks*block_size clamp; length <= 0 gives zeros
+    lens2 = np.array([-1, 99, 19], np.int32)
+    got2 = oracle.decode_attn_paged(b.q, kp, vp, table, lens2, 3, 4, 4, 64, 8, 4, 12, sb, sg, st)
+    assert np.array_equal(got2[0], np.zeros((4, 64))) and np.array_equal(got2[1], got[1])
