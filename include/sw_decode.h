@@ -119,6 +119,59 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
                    void *stream);
 
 /*
+ * Block-table ("paged") variant of the same step.  The paper's prototype keeps
+ * the KV cache in fixed-size blocks and ships it block by block (section 5.1,
+ * "KV-cache transfer" implementation), which is also what lets a token machine
+ * batch until its memory is nearly full (section 4.2) instead of reserving
+ * max_len positions per request.  Same attention, different addressing:
+ * positions [i*block_size, (i+1)*block_size) of request r live in pool block
+ * block_table[r*max_blocks + i], and element (b, g, t, j) of a pool -- block
+ * b, key/value head g, position t inside the block, dimension j -- is at
+ *     base + b*stride_block + g*stride_kvh + t*stride_tok + j*stride_dim
+ * with the strides sw_kv_paged_layout returns (in elements).
+ */
+typedef struct sw_kv_paged_layout_t {
+    int32_t dtype;         /* SW_F16                                              */
+    int32_t elem_bytes;    /* 2                                                   */
+    int64_t stride_block;  /* elements between consecutive pool blocks            */
+    int64_t stride_kvh;    /* elements between key/value heads inside a block     */
+    int64_t stride_tok;    /* elements between positions inside a block (= head_dim) */
+    int64_t stride_dim;    /* 1                                                   */
+    int64_t total_elems;   /* elements to allocate for ONE pool (K or V)          */
+    int32_t base_align;    /* required alignment of each pool's base, bytes       */
+    int32_t block_size;    /* positions per block, as passed in                   */
+} sw_kv_paged_layout_t;
+
+/*
+ * sw_kv_paged_layout -- layout query for block pools.  Pure host arithmetic.
+ * block_size must be a power of two in [4, 4096].  Errors: SW_ERR_NULL (out),
+ * SW_ERR_SHAPE (n_blocks/n_kvh <= 0), SW_ERR_UNSUPPORTED (head_dim, block_size).
+ */
+int sw_kv_paged_layout(int n_blocks, int n_kvh, int head_dim, int block_size,
+                       sw_kv_paged_layout_t *out);
+
+/*
+ * sw_decode_attn_paged -- sw_decode_attn over block pools.
+ *   q, seq_lens, out, n_req, n_qh, n_kvh, head_dim, stream: as in sw_decode_attn.
+ *   k_pool, v_pool  DEVICE, binary16, laid out as sw_kv_paged_layout(n_blocks,
+ *                   n_kvh, head_dim, block_size) says; separate buffers.  Read only.
+ *   block_table     DEVICE, int32 [n_req][max_blocks].  Only the first
+ *                   ceil(L_r / block_size) entries of row r are read; ids outside
+ *                   [0, n_blocks-1] are clamped into that range on the device.
+ *   block_size      positions per block: a power of two in [4, 4096].
+ *   max_blocks      table entries per request; lengths are clamped to
+ *                   [0, max_blocks*block_size], which must not exceed 2^23.
+ *   n_blocks        blocks in each pool (> 0).
+ * Asynchrony, workspace, ownership and errors as for sw_decode_attn; in
+ * addition block_table must be non-NULL and 4-byte aligned.  For the same
+ * cached values the result has the same bits as sw_decode_attn's.
+ */
+int sw_decode_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                         const int32_t *block_table, const int32_t *seq_lens, void *out,
+                         int n_req, int n_qh, int n_kvh, int head_dim,
+                         int block_size, int max_blocks, int n_blocks, void *stream);
+
+/*
  * sw_last_error -- text of the calling thread's most recent failure
  * (a static or thread-local string; never NULL; valid until the thread's next
  * failing call).  Support call, not part of the step.

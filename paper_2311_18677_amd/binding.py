@@ -26,7 +26,7 @@ SW_PARAM_KERNEL = 2
 SW_PARAM_COMBINE = 3
 SW_PARAM_WAVES = 4
 
-EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_last_error", "sw_version", "sw_release",
+EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged", "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
 
 
@@ -36,6 +36,14 @@ class sw_kv_layout_t(ctypes.Structure):
                 ("stride_tok", ctypes.c_int64), ("stride_dim", ctypes.c_int64),
                 ("total_elems", ctypes.c_int64),
                 ("base_align", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class sw_kv_paged_layout_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("elem_bytes", ctypes.c_int32),
+                ("stride_block", ctypes.c_int64), ("stride_kvh", ctypes.c_int64),
+                ("stride_tok", ctypes.c_int64), ("stride_dim", ctypes.c_int64),
+                ("total_elems", ctypes.c_int64),
+                ("base_align", ctypes.c_int32), ("block_size", ctypes.c_int32)]
 
 
 class SwError(RuntimeError):
@@ -67,6 +75,10 @@ def load():
     lib.sw_kv_layout.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sw_kv_layout_t)]
     lib.sw_decode_attn.restype = ci
     lib.sw_decode_attn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.sw_kv_paged_layout.restype = ci
+    lib.sw_kv_paged_layout.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sw_kv_paged_layout_t)]
+    lib.sw_decode_attn_paged.restype = ci
+    lib.sw_decode_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.sw_last_error.restype = ctypes.c_char_p
     lib.sw_last_error.argtypes = []
     lib.sw_version.restype = ci
@@ -131,6 +143,25 @@ def sw_decode_attn(q, k_cache, v_cache, seq_lens, out, n_req, n_qh, n_kvh, head_
     """One decode step's attention; enqueues on `stream` and returns without waiting."""
     rc = load().sw_decode_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out),
                                n_req, n_qh, n_kvh, head_dim, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_kv_paged_layout(n_blocks, n_kvh, head_dim, block_size, check=True):
+    """Returns the sw_kv_paged_layout_t the library fills in (or (code, layout) if check=False)."""
+    lay = sw_kv_paged_layout_t()
+    rc = load().sw_kv_paged_layout(n_blocks, n_kvh, head_dim, block_size, ctypes.byref(lay))
+    if check:
+        _check(rc)
+        return lay
+    return rc, lay
+
+
+def sw_decode_attn_paged(q, k_pool, v_pool, block_table, seq_lens, out, n_req, n_qh, n_kvh,
+                         head_dim, block_size, max_blocks, n_blocks, stream=None, check=True):
+    """One decode step's attention over block pools; enqueues on `stream`."""
+    rc = load().sw_decode_attn_paged(_ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                     _ptr(seq_lens), _ptr(out), n_req, n_qh, n_kvh, head_dim,
+                                     block_size, max_blocks, n_blocks, _stream(stream))
     return _check(rc) if check else rc
 
 
@@ -201,3 +232,41 @@ def run_batch(bufs, cfg, stream=None):
     return sw_decode_attn(bufs["q"], bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"],
                           bufs["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len,
                           stream)
+
+
+def upload_paged_batch(batch, block_size, spare_blocks=3, seed=0, device="cuda:0", pad_bits=0,
+                       table=None):
+    """Like upload_batch, for the block-table layout: shuffled pool blocks plus spares."""
+    import numpy as np
+    import torch
+    from . import workloads as wl
+
+    cfg = batch.cfg
+    max_blocks = -(-cfg.max_len // block_size)
+    n_blocks = sum(-(-int(L) // block_size) for L in batch.valid_lens) + spare_blocks
+    lay = sw_kv_paged_layout(n_blocks, cfg.n_kvh, cfg.head_dim, block_size)
+    k_host, v_host, tab = wl.pack_paged(batch.k_rows, batch.v_rows, cfg, block_size, lay.stride_block,
+                                        lay.stride_kvh, lay.stride_tok, n_blocks, seed=seed,
+                                        pad_bits=pad_bits)
+    if table is not None:
+        tab = table(tab)
+    dev = torch.device(device)
+    as_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
+    return {
+        "layout": lay, "k_host": k_host, "v_host": v_host, "table_host": tab,
+        "block_size": block_size, "max_blocks": max_blocks, "n_blocks": n_blocks,
+        "q": as_dev(np.ascontiguousarray(batch.q).view(np.uint16).reshape(-1)),
+        "k_pool": as_dev(k_host), "v_pool": as_dev(v_host),
+        "block_table": torch.from_numpy(np.ascontiguousarray(tab, dtype=np.int32)).to(dev),
+        "seq_lens": torch.from_numpy(np.ascontiguousarray(batch.seq_lens, dtype=np.int32)).to(dev),
+        "out": torch.full((cfg.n_req, cfg.n_qh, cfg.head_dim), float("nan"),
+                          dtype=torch.float16, device=dev),
+    }
+
+
+def run_paged_batch(bufs, cfg, stream=None):
+    """sw_decode_attn_paged on buffers made by upload_paged_batch."""
+    return sw_decode_attn_paged(bufs["q"], bufs["k_pool"], bufs["v_pool"], bufs["block_table"],
+                                bufs["seq_lens"], bufs["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh,
+                                cfg.head_dim, bufs["block_size"], bufs["max_blocks"],
+                                bufs["n_blocks"], stream)

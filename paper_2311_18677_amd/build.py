@@ -48,6 +48,12 @@ def build(verbose=False):
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
+    # every symbol must resolve: load the result once, in a process of its own
+    chk = subprocess.run([sys.executable, "-c", "import ctypes, sys; ctypes.CDLL(sys.argv[1], mode=2)", tmp],
+                         capture_output=True, text=True)
+    if chk.returncode != 0:
+        os.unlink(tmp)
+        raise RuntimeError("the built library does not load:\n" + chk.stderr)
     os.replace(tmp, LIB)
     if verbose:
         print("built", LIB)

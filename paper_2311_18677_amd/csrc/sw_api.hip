@@ -104,6 +104,178 @@ bool default_fused(int n_req, int n_kvh, int max_len)
     return false;
 }
 
+// Everything one step needs, dense or block-table.
+struct StepIn {
+    const void *q, *k, *v;
+    const int32_t *seq_lens;
+    void *out;
+    int n_req, n_qh, n_kvh, head_dim, max_len;
+    const int32_t *block_table;     // null for the dense layout
+    int block_size, max_blocks, n_blocks;
+    hipStream_t stream;
+};
+
+// Policy, workspace and launches; the arguments have been validated.
+int run_step(const StepIn &in)
+{
+    const void *q = in.q, *k_cache = in.k, *v_cache = in.v;
+    const int32_t *seq_lens = in.seq_lens;
+    void *out = in.out;
+    const int n_req = in.n_req, n_qh = in.n_qh, n_kvh = in.n_kvh, head_dim = in.head_dim, max_len = in.max_len;
+    const int group = n_qh / n_kvh;
+    hipStream_t stream = in.stream;
+
+    int chunk, kernel, combine, waves;
+    bool prof;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        chunk = g_chunk;
+        kernel = g_kernel;
+        combine = g_combine;
+        waves = g_waves;
+        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
+    }
+    if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
+    // keep the partial kernel's grid below 2^31 workgroups
+    while (((long long)(max_len + chunk - 1) / chunk) * n_req * n_kvh > 0x7fffffffLL) chunk *= 2;
+    const int n_chunks = (max_len + chunk - 1) / chunk;
+
+    SwArgs a;
+    a.q = (const uint16_t *)q;
+    a.k = (const uint16_t *)k_cache;
+    a.v = (const uint16_t *)v_cache;
+    a.seq_lens = seq_lens;
+    a.out = (uint16_t *)out;
+    a.n_req = n_req;
+    a.n_qh = n_qh;
+    a.n_kvh = n_kvh;
+    a.group = group;
+    a.head_dim = head_dim;
+    a.max_len = max_len;
+    a.chunk = chunk;
+    a.chunk_shift = 0;
+    while ((1 << a.chunk_shift) < chunk) ++a.chunk_shift;
+    a.n_chunks = n_chunks;
+    // four waves per workgroup measured best at every chunk length; a wave walks
+    // chunk / 128 tiles of 32 positions
+    a.waves = waves ? waves : 4;
+    if (a.waves * 32 > chunk) a.waves = 4;      // a chunk of 64 still runs 4 waves (2 idle)
+    a.block_table = in.block_table;
+    if (in.block_table) {
+        a.block_shift = 0;
+        while ((1 << a.block_shift) < in.block_size) ++a.block_shift;
+        a.max_blocks = in.max_blocks;
+        a.n_blocks = in.n_blocks;
+        a.stride_kvh = (long long)in.block_size * head_dim;
+        a.stride_block = a.stride_kvh * n_kvh;
+        a.stride_req = 0;
+    } else {
+        a.block_shift = a.max_blocks = a.n_blocks = 0;
+        a.stride_block = 0;
+        a.stride_kvh = slab_elems(head_dim, max_len);
+        a.stride_req = a.stride_kvh * n_kvh;
+    }
+    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
+
+    // 1 = vector ALU, 2 = matrix cores (V in registers), 3 = matrix cores (K and V through LDS)
+    int which = kernel;
+    if (which == 0) which = default_kernel(a);
+    if (which == 2 && !sw_partial_mfma_supported(a))
+        return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
+    if (which == 3 && !sw_partial_mfma2_supported(a))
+        return fail(SW_ERR_UNSUPPORTED, "the LDS-staged matrix-core kernel does not cover this shape");
+    if (which == 2 && in.block_table)
+        return fail(SW_ERR_UNSUPPORTED, "the register-staged matrix-core kernel has no block-table form");
+
+    const bool fused = combine == 0 ? default_fused(n_req, n_kvh, max_len) : combine == 2;
+
+    // ---- workspace: slots of (head_dim + 2) floats per (request, query head, chunk) ----
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    const size_t slots = (size_t)n_req * n_qh * n_chunks;
+    const size_t o_bytes = slots * head_dim * sizeof(float);
+    const size_t need = o_bytes + slots * 2 * sizeof(float);
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        Workspace &ws = g_ws[std::make_pair(dev, stream)];
+        if (ws.bytes < need) {
+            if (ws.base) {
+                e = hipStreamSynchronize(stream);   // earlier calls on this stream may still use it
+                if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+                e = hipFree(ws.base);
+                ws.base = nullptr;
+                ws.bytes = 0;
+                if (e != hipSuccess) return fail_hip(e, "hipFree");
+            }
+            const size_t grow = need + need / 4;
+            e = hipMalloc((void **)&ws.base, grow);
+            if (e != hipSuccess) {
+                ws.base = nullptr;
+                return fail_hip(e, "hipMalloc(workspace)");
+            }
+            ws.bytes = grow;
+        }
+        a.ws_o = ws.base;
+        a.ws_ml = ws.base + slots * head_dim;
+        a.counters = nullptr;
+        if (fused) {
+            // one counter per (request, key/value head, head tile); n_req * n_qh covers it
+            const size_t n_cnt = (size_t)n_req * n_qh;
+            if (ws.n_counters < n_cnt) {
+                if (ws.counters) {
+                    e = hipStreamSynchronize(stream);
+                    if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+                    e = hipFree(ws.counters);
+                    ws.counters = nullptr;
+                    ws.n_counters = 0;
+                    if (e != hipSuccess) return fail_hip(e, "hipFree");
+                }
+                const size_t grow = n_cnt + n_cnt / 4 + 64;
+                e = hipMalloc((void **)&ws.counters, grow * sizeof(unsigned));
+                if (e == hipSuccess) e = hipMemset(ws.counters, 0, grow * sizeof(unsigned));
+                if (e != hipSuccess) {
+                    if (ws.counters) (void)hipFree(ws.counters);
+                    ws.counters = nullptr;
+                    return fail_hip(e, "hipMalloc(counters)");
+                }
+                ws.n_counters = grow;
+            }
+            a.counters = ws.counters;
+        }
+    }
+
+    SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
+    ProfRec rec;
+    rec.has_combine = !fused;
+    if (prof) {
+        for (int i = 0; i < 4; ++i) {
+            e = hipEventCreate(&rec.ev[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
+                return fail_hip(e, "hipEventCreate");
+            }
+        }
+        ev_p = {rec.ev[0], rec.ev[1]};
+        ev_c = {rec.ev[2], rec.ev[3]};
+    }
+
+    e = which == 3 ? sw_launch_partial_mfma2(a, stream, prof ? &ev_p : nullptr)
+      : which == 2 ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
+                   : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
+    if (e == hipSuccess && !fused) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
+    if (e != hipSuccess) {
+        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        return fail_hip(e, "kernel launch");
+    }
+    if (prof) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
+        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+    }
+    return SW_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -251,142 +423,67 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
         return fail(SW_ERR_ALIGN, "q, k_cache, v_cache and out must be 16-byte aligned");
     if ((uintptr_t)seq_lens & 3u) return fail(SW_ERR_ALIGN, "seq_lens must be 4-byte aligned");
 
-    hipStream_t stream = (hipStream_t)stream_v;
+    StepIn in;
+    in.q = q; in.k = k_cache; in.v = v_cache; in.seq_lens = seq_lens; in.out = out;
+    in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
+    in.block_table = nullptr; in.block_size = in.max_blocks = in.n_blocks = 0;
+    in.stream = (hipStream_t)stream_v;
+    return run_step(in);
+}
 
-    int chunk, kernel, combine, waves;
-    bool prof;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        chunk = g_chunk;
-        kernel = g_kernel;
-        combine = g_combine;
-        waves = g_waves;
-        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
-    }
-    if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
-    // keep the partial kernel's grid below 2^31 workgroups
-    while (((long long)(max_len + chunk - 1) / chunk) * n_req * n_kvh > 0x7fffffffLL) chunk *= 2;
-    const int n_chunks = (max_len + chunk - 1) / chunk;
-
-    SwArgs a;
-    a.q = (const uint16_t *)q;
-    a.k = (const uint16_t *)k_cache;
-    a.v = (const uint16_t *)v_cache;
-    a.seq_lens = seq_lens;
-    a.out = (uint16_t *)out;
-    a.n_req = n_req;
-    a.n_qh = n_qh;
-    a.n_kvh = n_kvh;
-    a.group = group;
-    a.head_dim = head_dim;
-    a.max_len = max_len;
-    a.chunk = chunk;
-    a.chunk_shift = 0;
-    while ((1 << a.chunk_shift) < chunk) ++a.chunk_shift;
-    a.n_chunks = n_chunks;
-    // four waves per workgroup measured best at every chunk length; a wave walks
-    // chunk / 128 tiles of 32 positions
-    a.waves = waves ? waves : 4;
-    if (a.waves * 32 > chunk) a.waves = 4;      // a chunk of 64 still runs 4 waves (2 idle)
-    a.stride_kvh = slab_elems(head_dim, max_len);
-    a.stride_req = a.stride_kvh * n_kvh;
-    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
-
-    // 1 = vector ALU, 2 = matrix cores (V in registers), 3 = matrix cores (K and V through LDS)
-    int which = kernel;
-    if (which == 0) which = default_kernel(a);
-    if (which == 2 && !sw_partial_mfma_supported(a))
-        return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
-    if (which == 3 && !sw_partial_mfma2_supported(a))
-        return fail(SW_ERR_UNSUPPORTED, "the LDS-staged matrix-core kernel does not cover this shape");
-
-    const bool fused = combine == 0 ? default_fused(n_req, n_kvh, max_len) : combine == 2;
-
-    // ---- workspace: slots of (head_dim + 2) floats per (request, query head, chunk) ----
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
-    const size_t slots = (size_t)n_req * n_qh * n_chunks;
-    const size_t o_bytes = slots * head_dim * sizeof(float);
-    const size_t need = o_bytes + slots * 2 * sizeof(float);
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        Workspace &ws = g_ws[std::make_pair(dev, stream)];
-        if (ws.bytes < need) {
-            if (ws.base) {
-                e = hipStreamSynchronize(stream);   // earlier calls on this stream may still use it
-                if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
-                e = hipFree(ws.base);
-                ws.base = nullptr;
-                ws.bytes = 0;
-                if (e != hipSuccess) return fail_hip(e, "hipFree");
-            }
-            const size_t grow = need + need / 4;
-            e = hipMalloc((void **)&ws.base, grow);
-            if (e != hipSuccess) {
-                ws.base = nullptr;
-                return fail_hip(e, "hipMalloc(workspace)");
-            }
-            ws.bytes = grow;
-        }
-        a.ws_o = ws.base;
-        a.ws_ml = ws.base + slots * head_dim;
-        a.counters = nullptr;
-        if (fused) {
-            // one counter per (request, key/value head, head tile); n_req * n_qh covers it
-            const size_t n_cnt = (size_t)n_req * n_qh;
-            if (ws.n_counters < n_cnt) {
-                if (ws.counters) {
-                    e = hipStreamSynchronize(stream);
-                    if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
-                    e = hipFree(ws.counters);
-                    ws.counters = nullptr;
-                    ws.n_counters = 0;
-                    if (e != hipSuccess) return fail_hip(e, "hipFree");
-                }
-                const size_t grow = n_cnt + n_cnt / 4 + 64;
-                e = hipMalloc((void **)&ws.counters, grow * sizeof(unsigned));
-                if (e == hipSuccess) e = hipMemset(ws.counters, 0, grow * sizeof(unsigned));
-                if (e != hipSuccess) {
-                    if (ws.counters) (void)hipFree(ws.counters);
-                    ws.counters = nullptr;
-                    return fail_hip(e, "hipMalloc(counters)");
-                }
-                ws.n_counters = grow;
-            }
-            a.counters = ws.counters;
-        }
-    }
-
-    SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
-    ProfRec rec;
-    rec.has_combine = !fused;
-    if (prof) {
-        for (int i = 0; i < 4; ++i) {
-            e = hipEventCreate(&rec.ev[i]);
-            if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
-                return fail_hip(e, "hipEventCreate");
-            }
-        }
-        ev_p = {rec.ev[0], rec.ev[1]};
-        ev_c = {rec.ev[2], rec.ev[3]};
-    }
-
-    e = which == 3 ? sw_launch_partial_mfma2(a, stream, prof ? &ev_p : nullptr)
-      : which == 2 ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
-                   : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
-    if (e == hipSuccess && !fused) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
-    if (e != hipSuccess) {
-        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
-        return fail_hip(e, "kernel launch");
-    }
-    if (prof) {
-        std::lock_guard<std::mutex> lk(g_mu);
-        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
-        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
-    }
+int sw_kv_paged_layout(int n_blocks, int n_kvh, int head_dim, int block_size,
+                       sw_kv_paged_layout_t *out)
+{
+    if (!out) return fail(SW_ERR_NULL, "out is NULL");
+    if (n_blocks <= 0 || n_kvh <= 0) return fail(SW_ERR_SHAPE, "n_blocks and n_kvh must be > 0");
+    if (head_dim != 64 && head_dim != 128) return fail(SW_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (block_size < 4 || block_size > 4096 || (block_size & (block_size - 1)))
+        return fail(SW_ERR_UNSUPPORTED, "block_size must be a power of two in [4, 4096]");
+    out->dtype = SW_F16;
+    out->elem_bytes = 2;
+    out->stride_dim = 1;
+    out->stride_tok = head_dim;
+    out->stride_kvh = (long long)block_size * head_dim;
+    out->stride_block = out->stride_kvh * n_kvh;
+    out->total_elems = out->stride_block * (long long)n_blocks;
+    out->base_align = 256;
+    out->block_size = block_size;
     return SW_OK;
+}
+
+int sw_decode_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                         const int32_t *block_table, const int32_t *seq_lens, void *out,
+                         int n_req, int n_qh, int n_kvh, int head_dim,
+                         int block_size, int max_blocks, int n_blocks, void *stream_v)
+{
+    // ---- validation, before any HIP call ----
+    if (n_qh <= 0) return fail(SW_ERR_SHAPE, "n_qh must be > 0");
+    if (n_kvh <= 0 || n_qh % n_kvh != 0)
+        return fail(SW_ERR_SHAPE, "n_kvh must be > 0 and divide n_qh");
+    if (block_size < 4 || block_size > 4096 || (block_size & (block_size - 1)))
+        return fail(SW_ERR_UNSUPPORTED, "block_size must be a power of two in [4, 4096]");
+    if (max_blocks <= 0 || n_blocks <= 0) return fail(SW_ERR_SHAPE, "max_blocks and n_blocks must be > 0");
+    if ((long long)max_blocks * block_size > (1 << 23))
+        return fail(SW_ERR_SHAPE, "max_blocks * block_size above 2^23");
+    const int max_len = max_blocks * block_size;
+    int rc = check_shape(n_req, n_kvh, head_dim, max_len);
+    if (rc != SW_OK) return rc;
+    if (n_qh / n_kvh > 64) return fail(SW_ERR_UNSUPPORTED, "more than 64 query heads per key/value head");
+    if ((long long)n_req * n_qh > (1LL << 20)) return fail(SW_ERR_SHAPE, "n_req * n_qh above 2^20");
+    if (n_req == 0) return SW_OK;
+    if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !out)
+        return fail(SW_ERR_NULL, "q, k_pool, v_pool, block_table, seq_lens and out must be non-NULL");
+    if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out) & 15u)
+        return fail(SW_ERR_ALIGN, "q, k_pool, v_pool and out must be 16-byte aligned");
+    if (((uintptr_t)seq_lens | (uintptr_t)block_table) & 3u)
+        return fail(SW_ERR_ALIGN, "seq_lens and block_table must be 4-byte aligned");
+
+    StepIn in;
+    in.q = q; in.k = k_pool; in.v = v_pool; in.seq_lens = seq_lens; in.out = out;
+    in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
+    in.block_table = block_table; in.block_size = block_size; in.max_blocks = max_blocks; in.n_blocks = n_blocks;
+    in.stream = (hipStream_t)stream_v;
+    return run_step(in);
 }
 
 }  // extern "C"

@@ -27,11 +27,16 @@ struct SwArgs {
     float          *ws_o;
     float          *ws_ml;
     unsigned       *counters;           // single-launch variant: one ticket counter per unit, else null
+    const int32_t  *block_table;        // block-table variant: [n_req][max_blocks] pool block ids, else null
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
     int   chunk, chunk_shift, n_chunks; // chunk = 1 << chunk_shift; n_chunks = ceil(max_len / chunk)
     int   waves;                        // waves per workgroup of the matrix-core partial kernel (4, 8 or 16)
     long long stride_req, stride_kvh;  // elements; the token stride is head_dim
+    // block-table variant: k, v are pools; row t of request r is row t % block_size of pool
+    // block block_table[r*max_blocks + t / block_size]; stride_req is unused
+    long long stride_block;
+    int   block_shift, max_blocks, n_blocks;   // block_size = 1 << block_shift
     float scale_log2e;                 // log2(e) / sqrt(head_dim)
 };
 

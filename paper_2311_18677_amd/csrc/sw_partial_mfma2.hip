@@ -45,12 +45,19 @@ static_assert(16 * kHeadStride * 4 <= kWaveLds, "merge buffer must fit in the wa
 // leaving the other counters unconstrained.
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
+// Block-table variant: byte offset of the pool block behind each of a tile's 8 load instructions.
+struct TileBlocks { long long off[8]; };
+
+// The block table is read-only for the whole launch; reading it through the constant
+// address space lets wave-uniform entries come in over the scalar path.
+typedef const __attribute__((address_space(4))) int32_t *const_table_t;
+
 union Frag {
     uint4_t u;
     half8_t h;
 };
 
-template <int WAVES, int PER, bool FUSED>
+template <int WAVES, int PER, bool FUSED, bool PAGED>
 __global__ __launch_bounds__(64 * WAVES, 2)
 void sw_partial_mfma2_kernel(SwArgs a)
 {
@@ -93,33 +100,59 @@ void sw_partial_mfma2_kernel(SwArgs a)
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    // slab bases are wave-uniform; rows are addressed with 32-bit byte offsets from
-    // them (a slab is below 4 GiB: max_len <= 2^23 rows of 256 bytes)
-    const char *kbase = reinterpret_cast<const char *>(a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh);
-    const char *vbase = reinterpret_cast<const char *>(a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    // Row addressing: a wave-uniform 64-bit base plus a 32-bit byte offset per lane.
+    // Dense layout: the base is the (request, head) slab (below 4 GiB: max_len <= 2^23
+    // rows of 256 bytes).  Block-table layout: the base is the pool block of the
+    // instruction's four rows -- they always share one block (blocks hold a multiple of
+    // four positions and tiles start at multiples of 32), so the block id is one scalar
+    // table read per instruction; ids are clamped into the pool.
+    const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    // the table is read-only for the whole launch: read it through the constant address
+    // space so that wave-uniform entries come in over the scalar path
+    const_table_t table = PAGED ? (const_table_t)(a.block_table + (long long)r * a.max_blocks) : nullptr;
+    const int in_block = PAGED ? (1 << a.block_shift) - 1 : ~0;
     unsigned char *wlds = lds + wave * kWaveLds;
 
     const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
 
+    // byte offset, from the block-table base, of the block that holds row 4n of tile t0
+    // (clamped like the rows themselves); unused in the dense layout
+    auto find_blocks = [&](int t0) {
+        TileBlocks tb;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            tb.off[n] = 0;
+            if (PAGED) {
+                const int tu = min(t0 + 4 * n, t_end - 1);            // wave-uniform
+                int id = table[tu >> a.block_shift];
+                id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
+                tb.off[n] = 2 * (long long)id * a.stride_block;
+            }
+        }
+        return tb;
+    };
+
     // K tile -> LDS, asynchronously.  Rows past the chunk's end re-read its last
     // row (in bounds, result masked below).
-    auto issue_k = [&](int t0) {
+    auto issue_k = [&](int t0, const TileBlocks &tb) {
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
             const int rho = 4 * n + gq;
             const int tk  = min(t0 + rho, t_end - 1);
-            const char *src = kbase + (((unsigned)tk << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
+            const char *src = kslab + tb.off[n] + ((((unsigned)tk & (unsigned)in_block) << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
             __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, kStream);
         }
     };
     // V tile -> LDS, asynchronously, whole rows in token order (row t0 + 4n + gq by
     // instruction n).
     unsigned char *vlds = wlds + kTileBytes;
-    auto issue_v = [&](int t0) {
+    auto issue_v = [&](int t0, const TileBlocks &tb) {
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
             const int tv = min(t0 + 4 * n + gq, t_end - 1);
-            __builtin_amdgcn_global_load_lds(vbase + (((unsigned)tv << 8) | (unsigned)(n16 << 4)), vlds + n * 1024, 16, 0, kStream);
+            __builtin_amdgcn_global_load_lds(vslab + tb.off[n] + ((((unsigned)tv & (unsigned)in_block) << 8) | (unsigned)(n16 << 4)),
+                                             vlds + n * 1024, 16, 0, kStream);
         }
     };
 
@@ -129,6 +162,9 @@ void sw_partial_mfma2_kernel(SwArgs a)
     // between can count exactly which loads are still outstanding.
     auto process_tile = [&](int t0, int t0_next, auto more_c) {
         constexpr bool MORE = decltype(more_c)::value;
+        // block ids of the next tile: requested first, needed only after QK
+        TileBlocks nb;
+        if (MORE) nb = find_blocks(t0_next);
 
         // ---- S^T = K Q^T : two 16-token blocks, four 32-dim steps.
         // Outstanding, oldest first: K(t0) x8, V(t0) x8.
@@ -147,7 +183,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
             sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1.h, qb.h, sacc[1], 0, 0, 0);
         }
         // the K tile has been read into registers: its LDS area may be refilled
-        if (MORE) issue_k(t0_next);
+        if (MORE) issue_k(t0_next, nb);
 
         // ---- online softmax, base 2; this lane: head n16, tokens t0 + 16tb + 4gq + i
         float s[8];
@@ -211,7 +247,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
         // the V tile is in registers: its LDS area may be refilled
         if (MORE) {
             __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the LDS reads above have returned
-            issue_v(t0_next);
+            issue_v(t0_next, nb);
         }
 
         // ---- O^T += V^T P^T : block e covers dims 8*row + e (row = MFMA row)
@@ -231,8 +267,9 @@ void sw_partial_mfma2_kernel(SwArgs a)
 
     int ti = wave;
     if (ti < n_tiles) {
-        issue_k(t_begin + ti * kTile);
-        issue_v(t_begin + ti * kTile);
+        const TileBlocks fb = find_blocks(t_begin + ti * kTile);
+        issue_k(t_begin + ti * kTile, fb);
+        issue_v(t_begin + ti * kTile, fb);
     }
     // Q must be in LDS before any wave goes on; the tile loads stay in flight
     // across the barrier.  Vector-memory operations complete in issue order, so
@@ -310,12 +347,15 @@ hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const Sw
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks);
     const int per = sw_worklist_per(a.n_req);
-#define SW_MFMA2_CASE(W, P)                                                                            \
-    if (a.waves == W && per == P)                                                                     \
+    const bool paged = a.block_table != nullptr;
+#define SW_MFMA2_CASE(W, P, B)                                                                           \
+    if (a.waves == W && per == P && paged == B)                                                                   \
         return a.counters                                                                             \
-            ? sw_launch(sw_partial_mfma2_kernel<W, P, true>, grid, dim3(64 * W), 0, stream, ev, a)     \
-            : sw_launch(sw_partial_mfma2_kernel<W, P, false>, grid, dim3(64 * W), 0, stream, ev, a);
-#define SW_MFMA2_WAVES(W) SW_MFMA2_CASE(W, 1) SW_MFMA2_CASE(W, 4) SW_MFMA2_CASE(W, 16) SW_MFMA2_CASE(W, 0)
+            ? sw_launch(sw_partial_mfma2_kernel<W, P, true, B>, grid, dim3(64 * W), 0, stream, ev, a)     \
+            : sw_launch(sw_partial_mfma2_kernel<W, P, false, B>, grid, dim3(64 * W), 0, stream, ev, a);
+#define SW_MFMA2_WAVES(W)                                                                             \
+    SW_MFMA2_CASE(W, 1, false) SW_MFMA2_CASE(W, 4, false) SW_MFMA2_CASE(W, 16, false) SW_MFMA2_CASE(W, 0, false) \
+    SW_MFMA2_CASE(W, 1, true) SW_MFMA2_CASE(W, 4, true) SW_MFMA2_CASE(W, 16, true) SW_MFMA2_CASE(W, 0, true)
     SW_MFMA2_WAVES(4)
     SW_MFMA2_WAVES(8)
 #undef SW_MFMA2_WAVES

@@ -95,6 +95,7 @@ void sw_partial_valu_kernel(SwArgs a)
         for (int j = 0; j < 8; ++j) o[hh][j] = 0.f;
     }
 
+    const bool paged = a.block_table != nullptr;     // then stride_req is 0 and k, v are block pools
     const uint16_t *kbase = a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh + sub * 8;
     const uint16_t *vbase = a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh + sub * 8;
 
@@ -109,8 +110,15 @@ void sw_partial_valu_kernel(SwArgs a)
             vv[u] = Row8{};
             if (ok[u]) {
                 // non-temporal: read once, must not push the partial results out of L2
-                kk[u] = stream_load(kbase + (long long)t * D);
-                vv[u] = stream_load(vbase + (long long)t * D);
+                long long row = (long long)t * D;            // dense: row t of the slab
+                if (paged) {
+                    // block-table layout: row t % block_size of the pool block the table names
+                    int id = a.block_table[(long long)r * a.max_blocks + (t >> a.block_shift)];
+                    id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
+                    row = (long long)id * a.stride_block + (long long)(t & ((1 << a.block_shift) - 1)) * D;
+                }
+                kk[u] = stream_load(kbase + row);
+                vv[u] = stream_load(vbase + row);
             }
         }
 #pragma unroll

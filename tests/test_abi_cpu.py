@@ -116,3 +116,32 @@ def test_prof_state_errors():
     assert lib.sw_prof_start(4) == sw.SW_ERR_STATE
     p, c, n = sw.sw_prof_stop()
     assert (p, c, n) == (0.0, 0.0, 0)
+
+
+def test_paged_layout_and_validation():
+    lay = sw.sw_kv_paged_layout(100, 2, 128, 16)
+    assert lay.dtype == sw.SW_F16 and lay.block_size == 16
+    assert lay.stride_dim == 1 and lay.stride_tok == 128 and lay.stride_kvh == 16 * 128
+    assert lay.stride_block == 2 * lay.stride_kvh and lay.total_elems == 100 * lay.stride_block
+    assert sw.sw_kv_paged_layout(10, 1, 128, 24, check=False)[0] == sw.SW_ERR_UNSUPPORTED
+    assert sw.sw_kv_paged_layout(10, 1, 128, 2, check=False)[0] == sw.SW_ERR_UNSUPPORTED
+    assert sw.sw_kv_paged_layout(10, 1, 96, 16, check=False)[0] == sw.SW_ERR_UNSUPPORTED
+    assert sw.sw_kv_paged_layout(0, 1, 128, 16, check=False)[0] == sw.SW_ERR_SHAPE
+
+    def pcall(q=0x1000, k=0x2000, v=0x3000, tab=0x4000, lens=0x5000, out=0x6000, n_req=2, n_qh=8,
+              n_kvh=2, d=128, bs=16, mb=8, nb=32):
+        return sw.sw_decode_attn_paged(q, k, v, tab, lens, out, n_req, n_qh, n_kvh, d, bs, mb, nb,
+                                       None, check=False)
+    # every call fails validation (or is empty), so none reaches a HIP call
+    assert pcall(tab=None) == sw.SW_ERR_NULL
+    assert pcall(k=None) == sw.SW_ERR_NULL
+    assert pcall(tab=0x4002) == sw.SW_ERR_ALIGN
+    assert pcall(v=0x3008) == sw.SW_ERR_ALIGN
+    assert pcall(bs=24) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(bs=8192) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(d=32) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(mb=0) == sw.SW_ERR_SHAPE
+    assert pcall(nb=0) == sw.SW_ERR_SHAPE
+    assert pcall(bs=4096, mb=4096) == sw.SW_ERR_SHAPE
+    assert pcall(n_qh=8, n_kvh=3) == sw.SW_ERR_SHAPE
+    assert pcall(n_req=0) == sw.SW_OK
