@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
+    ap.add_argument("--paged", type=int, default=0, metavar="BLOCK",
+                    help="run the block-table variant with this block size (0 = dense layout)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch plain device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings); 0 = none")
@@ -63,6 +65,44 @@ def make_device_set(cfg, lay, seed, torch, np, wl, dev):
     bufs["seq_lens"] = torch.from_numpy(lens).to(dev)
     bufs["out"] = torch.zeros((cfg.n_req, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
     valid = np.clip(lens, 0, cfg.max_len).astype(np.int64)
+    bufs["kv_bytes"] = int(valid.sum()) * cfg.n_kvh * cfg.head_dim * 4
+    return bufs
+
+
+def make_paged_set(cfg, block_size, seed, torch, np, wl, sw, dev):
+    """A block-table cache set generated on the device: pools of exactly the blocks the
+    lengths need (plus 3), values N(0,1), a seeded random block assignment."""
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence(int(seed))))
+    lens = wl.draw_seq_lens(cfg, rng)
+    valid = np.clip(lens, 0, cfg.max_len).astype(np.int64)
+    per_req = -(-valid // block_size)
+    n_blocks = int(per_req.sum()) + 3
+    max_blocks = -(-cfg.max_len // block_size)
+    lay = sw.sw_kv_paged_layout(n_blocks, cfg.n_kvh, cfg.head_dim, block_size)
+    g = torch.Generator(device=dev)
+    g.manual_seed(int(seed))
+    bufs = {"block_size": block_size, "max_blocks": max_blocks, "n_blocks": n_blocks}
+    for name in ("k_pool", "v_pool"):
+        t = torch.empty(lay.total_elems, dtype=torch.float16, device=dev)
+        t.normal_(0.0, 1.0, generator=g)
+        bufs[name] = t
+    if cfg.k_row_scale:
+        prob, factor = cfg.k_row_scale
+        rows = bufs["k_pool"].view(-1, cfg.head_dim)
+        hit = torch.rand(rows.shape[0], device=dev, generator=g) < prob
+        rows[hit] *= factor
+    order = rng.permutation(n_blocks)
+    table = np.full((cfg.n_req, max_blocks), 0x3FFFFFF0, dtype=np.int32)
+    nxt = 0
+    for r in range(cfg.n_req):
+        table[r, :per_req[r]] = order[nxt:nxt + per_req[r]]
+        nxt += int(per_req[r])
+    q = torch.empty(cfg.n_req * cfg.n_qh * cfg.head_dim, dtype=torch.float16, device=dev)
+    q.normal_(0.0, 1.0, generator=g)
+    bufs["q"] = q
+    bufs["block_table"] = torch.from_numpy(table).to(dev)
+    bufs["seq_lens"] = torch.from_numpy(lens).to(dev)
+    bufs["out"] = torch.zeros((cfg.n_req, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
     bufs["kv_bytes"] = int(valid.sum()) * cfg.n_kvh * cfg.head_dim * 4
     return bufs
 
@@ -105,13 +145,19 @@ def main():
 
     # ---- inputs: set 0 from the host recipe (also the oracle's input), the rest on device
     batch0 = wl.make_batch(cfg)
-    set0 = sw.upload_batch(batch0, device="cuda:0", pad_bits=0)
+    if args.paged:
+        set0 = sw.upload_paged_batch(batch0, args.paged, device="cuda:0", pad_bits=0)
+    else:
+        set0 = sw.upload_batch(batch0, device="cuda:0", pad_bits=0)
     set0["kv_bytes"] = batch0.kv_bytes
     n_sets = args.sets or max(2, -(-4 * LLC_BYTES // max(batch0.kv_bytes, 1)))
     sets = [set0]
     for i in range(1, n_sets):
-        sets.append(make_device_set(cfg, lay, wl.BASE_SEED + 1000 * cfg.seed_index + i,
-                                    torch, np, wl, dev))
+        seed_i = wl.BASE_SEED + 1000 * cfg.seed_index + i
+        if args.paged:
+            sets.append(make_paged_set(cfg, args.paged, seed_i, torch, np, wl, sw, dev))
+        else:
+            sets.append(make_device_set(cfg, lay, seed_i, torch, np, wl, dev))
     torch.cuda.synchronize()
 
     if args.copy_calibration:
@@ -127,8 +173,13 @@ def main():
     stream = torch.cuda.Stream(device=dev)
 
     def call(s, st):
-        sw.sw_decode_attn(s["q"], s["k_cache"], s["v_cache"], s["seq_lens"], s["out"],
-                          cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
+        if args.paged:
+            sw.sw_decode_attn_paged(s["q"], s["k_pool"], s["v_pool"], s["block_table"], s["seq_lens"],
+                                    s["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                                    s["block_size"], s["max_blocks"], s["n_blocks"], st)
+        else:
+            sw.sw_decode_attn(s["q"], s["k_cache"], s["v_cache"], s["seq_lens"], s["out"],
+                              cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
 
     # first call on the stream sizes the workspace (allocates); keep it out of everything timed
     call(sets[0], stream)
@@ -197,10 +248,18 @@ def main():
         reps, t_cpu, ref, used = 0, 0.0, None, 0
         while t_cpu < 10.0 and reps < 500:
             c0 = time.perf_counter()
-            ref, _, _, used = oracle.decode_attn(
-                batch0.q, set0["k_host"], set0["v_host"], batch0.seq_lens, cfg.n_req, cfg.n_qh,
-                cfg.n_kvh, cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh,
-                lay.stride_tok, return_stats=True)
+            if args.paged:
+                pl = set0["layout"]
+                ref = oracle.decode_attn_paged(
+                    batch0.q, set0["k_host"], set0["v_host"], set0["table_host"], batch0.seq_lens,
+                    cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, set0["block_size"],
+                    set0["max_blocks"], set0["n_blocks"], pl.stride_block, pl.stride_kvh, pl.stride_tok)
+                used = oracle.max_threads()
+            else:
+                ref, _, _, used = oracle.decode_attn(
+                    batch0.q, set0["k_host"], set0["v_host"], batch0.seq_lens, cfg.n_req, cfg.n_qh,
+                    cfg.n_kvh, cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh,
+                    lay.stride_tok, return_stats=True)
             t_cpu += time.perf_counter() - c0
             reps += 1
         cpu_gbps = batch0.kv_bytes * reps / t_cpu / 1e9
@@ -232,10 +291,13 @@ def main():
         "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_qh": cfg.n_qh, "n_kvh": cfg.n_kvh,
                    "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
                    "kv_bytes_per_step": mean_bytes, "cache_sets": n_sets, "launch": mode,
+                   "kv_layout": ("block table, %d positions per block" % args.paged) if args.paged
+                   else "dense, padded to max_len",
                    "chunk": sw.sw_get_param(sw.SW_PARAM_CHUNK),
                    "kernel": sw.sw_get_param(sw.SW_PARAM_KERNEL)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(cfg.name),
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None if args.paged else read_traffic(cfg.name),
                      "kernel": "partial (dominant)", "kernel_us": partial_us,
                      "combine_us": combine_us, "bytes_per_launch": prof_bytes,
                      "launches_timed": n_rec},
