@@ -170,7 +170,12 @@ void sw_partial_mfma_kernel(SwArgs a)
             sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1.h, qb.h, sacc[1], 0, 0, 0);
         }
         // the K tile has been read into registers: its LDS area may be refilled
-        if (MORE) issue_k(t0_next);
+        if (MORE) {
+            // every read of the K tile must have RETURNED before its area is refilled:
+            // global->LDS writes arrive outside the LDS instruction queue
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+            issue_k(t0_next);
+        }
 
         // ---- online softmax, base 2; this lane: head n16, tokens t0 + 16tb + 4gq + i
         float s[8];

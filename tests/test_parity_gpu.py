@@ -285,3 +285,27 @@ def test_sampled_outputs_at_full_size_in_bench_configuration():
     for r in range(batch.cfg.n_req):
         v = batch.v_rows[r][0].astype(np.float64)
         assert np.all(o[r] <= v.max(axis=0) + 2e-3) and np.all(o[r] >= v.min(axis=0) - 2e-3)
+
+
+@pytest.mark.parametrize("n_qh,n_kvh", [(14, 14), (8, 1)])
+def test_repeated_calls_on_cache_resident_data_are_stable(n_qh, n_kvh):
+    """A small batch stays in the on-chip caches across calls, so a tile's rows come back
+    fast; every call must still give the first call's bits (a wave refills its staging
+    area only after its reads of the previous tile have returned)."""
+    import torch
+    lens = [129, 255, 256, 400, 511, 512, 700, 766, 767, 768] * 2
+    cfg = wl.custom_config("hot%d" % n_kvh, len(lens), n_qh, n_kvh, 128, 768)
+    batch = wl.make_batch(cfg, seed=7700 + n_kvh, seq_lens=lens)
+    bufs = sw.upload_batch(batch, pad_bits=0x7E00)
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    first = None
+    for rep in range(40):
+        out = torch.full_like(bufs["out"], float("nan"))
+        sw.sw_decode_attn(bufs["q"], bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], out,
+                          cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        if first is None:
+            first = got
+            assert_parity(got, ref, cfg.name)
+        assert np.array_equal(got.view(np.uint16), first.view(np.uint16)), rep
