@@ -172,6 +172,56 @@ int sw_decode_attn_paged(const void *q, const void *k_pool, const void *v_pool,
                          int block_size, int max_blocks, int n_blocks, void *stream);
 
 /*
+ * Append-then-attend variants: one layer's attention inside a running decode
+ * loop.  Every token-phase iteration takes the last generated token and the KV
+ * cache as inputs (section 2.2, "token phase"): the token's own key and value
+ * rows join the cache of every layer, and the token attends over the cache
+ * including itself.  These calls do both in one pass over the cache, so a
+ * model step is n_layers such calls (one per layer cache, all sharing one
+ * seq_lens array) followed by one sw_advance_lens.
+ *
+ *   k_new, v_new   DEVICE, binary16, dense [n_req][n_kvh][head_dim]: the newest
+ *                  token's K and V rows for this layer.  Read only, 16-byte aligned.
+ *   k_cache, v_cache (k_pool, v_pool)  as in sw_decode_attn (_paged), but
+ *                  WRITTEN: with L0 = clamp(seq_lens[r], 0, max_len) the number
+ *                  of positions cached BEFORE this token, a request with
+ *                  L0 < max_len gets k_new[r] / v_new[r] stored, bit for bit, at
+ *                  position L0 of every key/value head and attends over
+ *                  positions [0, L0]; a request whose cache is full (L0 ==
+ *                  max_len) stores nothing and attends over the max_len cached
+ *                  positions without the new token.  Nothing else in the
+ *                  caches is written.
+ *   block_table    (paged) the entry for position L0, i.e. entry
+ *                  L0 / block_size of row r, must name the block the caller
+ *                  has allotted to it; an id outside the pool is clamped into
+ *                  it like any other.  Two requests must not share the block
+ *                  either of them appends to.
+ *   seq_lens       read only here; every layer of a step sees the same values.
+ * Everything else (arguments, asynchrony, workspace, errors) as in
+ * sw_decode_attn / sw_decode_attn_paged.  `out` has the bits sw_decode_attn
+ * gives on the cache after the append with lengths L0 + 1 (L0 when full).
+ */
+int sw_decode_attn_append(const void *q, const void *k_new, const void *v_new,
+                          void *k_cache, void *v_cache,
+                          const int32_t *seq_lens, void *out,
+                          int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                          void *stream);
+int sw_decode_attn_paged_append(const void *q, const void *k_new, const void *v_new,
+                                void *k_pool, void *v_pool,
+                                const int32_t *block_table, const int32_t *seq_lens, void *out,
+                                int n_req, int n_qh, int n_kvh, int head_dim,
+                                int block_size, int max_blocks, int n_blocks, void *stream);
+
+/*
+ * sw_advance_lens -- end of a model step: seq_lens[r] = min(clamp(seq_lens[r],
+ * 0, max_len) + 1, max_len) for every request, on the device, enqueued on
+ * `stream` after the step's layer calls.  seq_lens: DEVICE, int32 [n_req],
+ * 4-byte aligned.  Errors: SW_ERR_NULL, SW_ERR_SHAPE (n_req < 0, max_len <= 0),
+ * SW_ERR_ALIGN, SW_ERR_HIP.  n_req == 0 returns SW_OK.
+ */
+int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream);
+
+/*
  * sw_last_error -- text of the calling thread's most recent failure
  * (a static or thread-local string; never NULL; valid until the thread's next
  * failing call).  Support call, not part of the step.

@@ -50,6 +50,17 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+        lib.sw_oracle_kv_append.restype = ctypes.c_int
+        lib.sw_oracle_kv_append.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+        lib.sw_oracle_kv_append_paged.restype = ctypes.c_int
+        lib.sw_oracle_kv_append_paged.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
         lib.sw_oracle_half_to_double.restype = ctypes.c_double
         lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
         lib.sw_oracle_max_threads.restype = ctypes.c_int
@@ -141,3 +152,65 @@ def decode_attn_paged(q, k_pool, v_pool, block_table, seq_lens, n_req, n_qh, n_k
     if rc < 0:
         raise ValueError("sw_oracle_decode_attn_paged rejected its arguments (code %d)" % rc)
     return ref
+
+
+def _writable_u16(a, name):
+    if not isinstance(a, np.ndarray) or a.dtype != np.uint16 or not a.flags["C_CONTIGUOUS"] \
+            or not a.flags["WRITEABLE"]:
+        raise TypeError("%s must be a writable C-contiguous uint16 array (it is updated in place)" % name)
+    return a
+
+
+def kv_append(k_new, v_new, k, v, seq_lens, n_req, n_kvh, head_dim, max_len,
+              stride_req, stride_kvh, stride_tok):
+    """Store the newest token's rows at each request's next position, IN PLACE in k and v.
+
+    Returns the lengths after the append (int32 [n_req]); full caches are left alone.
+    """
+    lib = _load()
+    k_new = _as_u16(k_new, "k_new")
+    v_new = _as_u16(v_new, "v_new")
+    k = _writable_u16(k, "k")
+    v = _writable_u16(v, "v")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    if lens.size != n_req or k_new.size != n_req * n_kvh * head_dim or v_new.size != k_new.size:
+        raise ValueError("seq_lens / k_new / v_new have the wrong number of entries")
+    need = 0
+    if n_req > 0:
+        need = ((n_req - 1) * stride_req + (n_kvh - 1) * stride_kvh
+                + (max_len - 1) * stride_tok + head_dim)
+    if k.size < need or v.size < need:
+        raise ValueError("k/v buffers are smaller than the strides address")
+    out = np.zeros(n_req, dtype=np.int32)
+    rc = lib.sw_oracle_kv_append(k_new.ctypes.data, v_new.ctypes.data, k.ctypes.data, v.ctypes.data,
+                                 lens.ctypes.data, out.ctypes.data, n_req, n_kvh, head_dim, max_len,
+                                 stride_req, stride_kvh, stride_tok)
+    if rc < 0:
+        raise ValueError("sw_oracle_kv_append rejected its arguments (code %d)" % rc)
+    return out
+
+
+def kv_append_paged(k_new, v_new, k_pool, v_pool, block_table, seq_lens, n_req, n_kvh, head_dim,
+                    block_size, max_blocks, n_blocks, stride_block, stride_kvh, stride_tok):
+    """kv_append over block pools (updated in place).  Returns the lengths after the append."""
+    lib = _load()
+    k_new = _as_u16(k_new, "k_new")
+    v_new = _as_u16(v_new, "v_new")
+    k_pool = _writable_u16(k_pool, "k_pool")
+    v_pool = _writable_u16(v_pool, "v_pool")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    table = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    if lens.size != n_req or table.size != n_req * max_blocks \
+            or k_new.size != n_req * n_kvh * head_dim or v_new.size != k_new.size:
+        raise ValueError("seq_lens / block_table / k_new / v_new have the wrong number of entries")
+    need = (n_blocks - 1) * stride_block + (n_kvh - 1) * stride_kvh + (block_size - 1) * stride_tok + head_dim
+    if k_pool.size < need or v_pool.size < need:
+        raise ValueError("pools are smaller than the strides address")
+    out = np.zeros(n_req, dtype=np.int32)
+    rc = lib.sw_oracle_kv_append_paged(
+        k_new.ctypes.data, v_new.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data,
+        table.ctypes.data, lens.ctypes.data, out.ctypes.data, n_req, n_kvh, head_dim,
+        block_size, max_blocks, n_blocks, stride_block, stride_kvh, stride_tok)
+    if rc < 0:
+        raise ValueError("sw_oracle_kv_append_paged rejected its arguments (code %d)" % rc)
+    return out

@@ -254,6 +254,81 @@ int sw_oracle_decode_attn_paged(const uint16_t *q, const uint16_t *k_pool, const
     return failed ? -4 : used;
 }
 
+/*
+ * The cache side of one token-phase iteration (section 2.2: each iteration's
+ * inputs are the last generated token and the KV cache, so that token's key and
+ * value rows join the cache before it attends).  For every request r with
+ * L0 = clamp(seq_lens[r], 0, max_len) < max_len, rows k_new[r, g, :] and
+ * v_new[r, g, :] are copied, bit for bit, to position L0 of every key/value
+ * head g, and lens_out[r] = L0 + 1; a request whose cache is full keeps its
+ * cache and gets lens_out[r] = max_len.  k_new, v_new: dense
+ * [n_req][n_kvh][head_dim].  A step of the append-then-attend variant is this
+ * routine followed by sw_oracle_decode_attn with lens_out.
+ * Pinned by brute force against array slicing (tests/test_oracle_pins.py).
+ */
+int sw_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, uint16_t *k, uint16_t *v,
+                        const int32_t *seq_lens, int32_t *lens_out,
+                        int n_req, int n_kvh, int head_dim, int max_len,
+                        int64_t stride_req, int64_t stride_kvh, int64_t stride_tok)
+{
+    if (n_req < 0 || n_kvh <= 0 || head_dim <= 0 || max_len <= 0) return -1;
+    if (n_req == 0) return 0;
+    if (!k_new || !v_new || !k || !v || !seq_lens || !lens_out) return -3;
+    for (int r = 0; r < n_req; ++r) {
+        int L0 = clampi(seq_lens[r], 0, max_len);
+        if (L0 == max_len) {
+            lens_out[r] = max_len;
+            continue;
+        }
+        for (int g = 0; g < n_kvh; ++g) {
+            int64_t dst = (int64_t)r * stride_req + (int64_t)g * stride_kvh + (int64_t)L0 * stride_tok;
+            int64_t src = ((int64_t)r * n_kvh + g) * head_dim;
+            for (int j = 0; j < head_dim; ++j) {
+                k[dst + j] = k_new[src + j];
+                v[dst + j] = v_new[src + j];
+            }
+        }
+        lens_out[r] = L0 + 1;
+    }
+    return 0;
+}
+
+/* The same over block pools: position L0 of request r is row L0 % block_size of
+ * pool block clamp(block_table[r*max_blocks + L0 / block_size], 0, n_blocks-1). */
+int sw_oracle_kv_append_paged(const uint16_t *k_new, const uint16_t *v_new,
+                              uint16_t *k_pool, uint16_t *v_pool,
+                              const int32_t *block_table, const int32_t *seq_lens, int32_t *lens_out,
+                              int n_req, int n_kvh, int head_dim,
+                              int block_size, int max_blocks, int n_blocks,
+                              int64_t stride_block, int64_t stride_kvh, int64_t stride_tok)
+{
+    if (n_req < 0 || n_kvh <= 0 || head_dim <= 0 || block_size <= 0 || max_blocks <= 0 ||
+        n_blocks <= 0) return -1;
+    if (n_req == 0) return 0;
+    if (!k_new || !v_new || !k_pool || !v_pool || !block_table || !seq_lens || !lens_out) return -3;
+    const int64_t max_len = (int64_t)max_blocks * block_size;
+    for (int r = 0; r < n_req; ++r) {
+        int64_t L0 = seq_lens[r];
+        L0 = L0 < 0 ? 0 : (L0 > max_len ? max_len : L0);
+        if (L0 == max_len) {
+            lens_out[r] = (int32_t)max_len;
+            continue;
+        }
+        int b = clampi(block_table[(int64_t)r * max_blocks + L0 / block_size], 0, n_blocks - 1);
+        for (int g = 0; g < n_kvh; ++g) {
+            int64_t dst = (int64_t)b * stride_block + (int64_t)g * stride_kvh +
+                          (L0 % block_size) * stride_tok;
+            int64_t src = ((int64_t)r * n_kvh + g) * head_dim;
+            for (int j = 0; j < head_dim; ++j) {
+                k_pool[dst + j] = k_new[src + j];
+                v_pool[dst + j] = v_new[src + j];
+            }
+        }
+        lens_out[r] = (int32_t)(L0 + 1);
+    }
+    return 0;
+}
+
 int sw_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -26,7 +26,9 @@ SW_PARAM_KERNEL = 2
 SW_PARAM_COMBINE = 3
 SW_PARAM_WAVES = 4
 
-EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged", "sw_last_error", "sw_version", "sw_release",
+EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
+           "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
+           "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
 
 
@@ -79,6 +81,13 @@ def load():
     lib.sw_kv_paged_layout.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sw_kv_paged_layout_t)]
     lib.sw_decode_attn_paged.restype = ci
     lib.sw_decode_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.sw_decode_attn_append.restype = ci
+    lib.sw_decode_attn_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.sw_decode_attn_paged_append.restype = ci
+    lib.sw_decode_attn_paged_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
+                                                ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.sw_advance_lens.restype = ci
+    lib.sw_advance_lens.argtypes = [vp, ci, ci, vp]
     lib.sw_last_error.restype = ctypes.c_char_p
     lib.sw_last_error.argtypes = []
     lib.sw_version.restype = ci
@@ -165,6 +174,32 @@ def sw_decode_attn_paged(q, k_pool, v_pool, block_table, seq_lens, out, n_req, n
     return _check(rc) if check else rc
 
 
+def sw_decode_attn_append(q, k_new, v_new, k_cache, v_cache, seq_lens, out, n_req, n_qh, n_kvh,
+                          head_dim, max_len, stream=None, check=True):
+    """Store the newest token's K/V rows in the cache and attend over it, in one pass."""
+    rc = load().sw_decode_attn_append(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                      _ptr(v_cache), _ptr(seq_lens), _ptr(out),
+                                      n_req, n_qh, n_kvh, head_dim, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_decode_attn_paged_append(q, k_new, v_new, k_pool, v_pool, block_table, seq_lens, out,
+                                n_req, n_qh, n_kvh, head_dim, block_size, max_blocks, n_blocks,
+                                stream=None, check=True):
+    """sw_decode_attn_append over block pools."""
+    rc = load().sw_decode_attn_paged_append(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_pool),
+                                            _ptr(v_pool), _ptr(block_table), _ptr(seq_lens),
+                                            _ptr(out), n_req, n_qh, n_kvh, head_dim,
+                                            block_size, max_blocks, n_blocks, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_advance_lens(seq_lens, n_req, max_len, stream=None, check=True):
+    """End of a model step: every length grows by one, saturating at max_len (on the device)."""
+    rc = load().sw_advance_lens(_ptr(seq_lens), n_req, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
 def sw_release():
     return _check(load().sw_release())
 
@@ -235,19 +270,23 @@ def run_batch(bufs, cfg, stream=None):
 
 
 def upload_paged_batch(batch, block_size, spare_blocks=3, seed=0, device="cuda:0", pad_bits=0,
-                       table=None):
-    """Like upload_batch, for the block-table layout: shuffled pool blocks plus spares."""
+                       table=None, room=0):
+    """Like upload_batch, for the block-table layout: shuffled pool blocks plus spares.
+
+    room > 0 also allots blocks for each request's next `room` positions (append variant).
+    """
     import numpy as np
     import torch
     from . import workloads as wl
 
     cfg = batch.cfg
     max_blocks = -(-cfg.max_len // block_size)
-    n_blocks = sum(-(-int(L) // block_size) for L in batch.valid_lens) + spare_blocks
+    n_blocks = sum(-(-min(int(L) + room, cfg.max_len) // block_size)
+                   for L in batch.valid_lens) + spare_blocks
     lay = sw_kv_paged_layout(n_blocks, cfg.n_kvh, cfg.head_dim, block_size)
     k_host, v_host, tab = wl.pack_paged(batch.k_rows, batch.v_rows, cfg, block_size, lay.stride_block,
                                         lay.stride_kvh, lay.stride_tok, n_blocks, seed=seed,
-                                        pad_bits=pad_bits)
+                                        pad_bits=pad_bits, room=room)
     if table is not None:
         tab = table(tab)
     dev = torch.device(device)

@@ -93,7 +93,7 @@ int default_chunk(int n_req, int n_kvh, int max_len)
 int default_kernel(const SwArgs &a)
 {
     if (sw_partial_mfma2_supported(a)) return 3;
-    return sw_partial_mfma_supported(a) ? 2 : 1;
+    return sw_partial_mfma_supported(a) && !a.block_table && !a.k_new ? 2 : 1;
 }
 
 // Whether the last workgroup of each unit merges the chunks itself (one launch)
@@ -107,6 +107,7 @@ bool default_fused(int n_req, int n_kvh, int max_len)
 // Everything one step needs, dense or block-table.
 struct StepIn {
     const void *q, *k, *v;
+    const void *k_new, *v_new;      // append variant: the newest token's rows (then k, v are written), else null
     const int32_t *seq_lens;
     void *out;
     int n_req, n_qh, n_kvh, head_dim, max_len;
@@ -144,6 +145,8 @@ int run_step(const StepIn &in)
     a.q = (const uint16_t *)q;
     a.k = (const uint16_t *)k_cache;
     a.v = (const uint16_t *)v_cache;
+    a.k_new = (const uint16_t *)in.k_new;
+    a.v_new = (const uint16_t *)in.v_new;
     a.seq_lens = seq_lens;
     a.out = (uint16_t *)out;
     a.n_req = n_req;
@@ -180,6 +183,8 @@ int run_step(const StepIn &in)
     // 1 = vector ALU, 2 = matrix cores (V in registers), 3 = matrix cores (K and V through LDS)
     int which = kernel;
     if (which == 0) which = default_kernel(a);
+    if (which == 2 && in.k_new)
+        return fail(SW_ERR_UNSUPPORTED, "the register-staged matrix-core kernel has no append form");
     if (which == 2 && !sw_partial_mfma_supported(a))
         return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
     if (which == 3 && !sw_partial_mfma2_supported(a))
@@ -401,10 +406,12 @@ int sw_release(void)
     return rc;
 }
 
-int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
-                   const int32_t *seq_lens, void *out,
-                   int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
-                   void *stream_v)
+// sw_decode_attn and sw_decode_attn_append; k_new == v_new == NULL selects the former.
+static int decode_dense(const void *q, const void *k_new, const void *v_new, bool append,
+                        const void *k_cache, const void *v_cache,
+                        const int32_t *seq_lens, void *out,
+                        int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                        void *stream_v)
 {
     // ---- validation: nothing below this block runs on bad arguments, and
     // nothing in it touches HIP ----
@@ -419,16 +426,49 @@ int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
     if (n_req == 0) return SW_OK;
     if (!q || !k_cache || !v_cache || !seq_lens || !out)
         return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens and out must be non-NULL");
-    if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u)
-        return fail(SW_ERR_ALIGN, "q, k_cache, v_cache and out must be 16-byte aligned");
+    if (append && (!k_new || !v_new)) return fail(SW_ERR_NULL, "k_new and v_new must be non-NULL");
+    if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out |
+         (uintptr_t)k_new | (uintptr_t)v_new) & 15u)
+        return fail(SW_ERR_ALIGN, "q, k_new, v_new, k_cache, v_cache and out must be 16-byte aligned");
     if ((uintptr_t)seq_lens & 3u) return fail(SW_ERR_ALIGN, "seq_lens must be 4-byte aligned");
 
     StepIn in;
     in.q = q; in.k = k_cache; in.v = v_cache; in.seq_lens = seq_lens; in.out = out;
+    in.k_new = k_new; in.v_new = v_new;
     in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
     in.block_table = nullptr; in.block_size = in.max_blocks = in.n_blocks = 0;
     in.stream = (hipStream_t)stream_v;
     return run_step(in);
+}
+
+int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *seq_lens, void *out,
+                   int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                   void *stream)
+{
+    return decode_dense(q, nullptr, nullptr, false, k_cache, v_cache, seq_lens, out,
+                        n_req, n_qh, n_kvh, head_dim, max_len, stream);
+}
+
+int sw_decode_attn_append(const void *q, const void *k_new, const void *v_new,
+                          void *k_cache, void *v_cache,
+                          const int32_t *seq_lens, void *out,
+                          int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                          void *stream)
+{
+    return decode_dense(q, k_new, v_new, true, k_cache, v_cache, seq_lens, out,
+                        n_req, n_qh, n_kvh, head_dim, max_len, stream);
+}
+
+int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream)
+{
+    if (n_req < 0 || max_len <= 0) return fail(SW_ERR_SHAPE, "n_req must be >= 0 and max_len > 0");
+    if (n_req == 0) return SW_OK;
+    if (!seq_lens) return fail(SW_ERR_NULL, "seq_lens is NULL");
+    if ((uintptr_t)seq_lens & 3u) return fail(SW_ERR_ALIGN, "seq_lens must be 4-byte aligned");
+    hipError_t e = sw_launch_advance_lens(seq_lens, n_req, max_len, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return SW_OK;
 }
 
 int sw_kv_paged_layout(int n_blocks, int n_kvh, int head_dim, int block_size,
@@ -451,10 +491,11 @@ int sw_kv_paged_layout(int n_blocks, int n_kvh, int head_dim, int block_size,
     return SW_OK;
 }
 
-int sw_decode_attn_paged(const void *q, const void *k_pool, const void *v_pool,
-                         const int32_t *block_table, const int32_t *seq_lens, void *out,
-                         int n_req, int n_qh, int n_kvh, int head_dim,
-                         int block_size, int max_blocks, int n_blocks, void *stream_v)
+static int decode_paged(const void *q, const void *k_new, const void *v_new, bool append,
+                        const void *k_pool, const void *v_pool,
+                        const int32_t *block_table, const int32_t *seq_lens, void *out,
+                        int n_req, int n_qh, int n_kvh, int head_dim,
+                        int block_size, int max_blocks, int n_blocks, void *stream_v)
 {
     // ---- validation, before any HIP call ----
     if (n_qh <= 0) return fail(SW_ERR_SHAPE, "n_qh must be > 0");
@@ -473,17 +514,39 @@ int sw_decode_attn_paged(const void *q, const void *k_pool, const void *v_pool,
     if (n_req == 0) return SW_OK;
     if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !out)
         return fail(SW_ERR_NULL, "q, k_pool, v_pool, block_table, seq_lens and out must be non-NULL");
-    if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out) & 15u)
-        return fail(SW_ERR_ALIGN, "q, k_pool, v_pool and out must be 16-byte aligned");
+    if (append && (!k_new || !v_new)) return fail(SW_ERR_NULL, "k_new and v_new must be non-NULL");
+    if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out |
+         (uintptr_t)k_new | (uintptr_t)v_new) & 15u)
+        return fail(SW_ERR_ALIGN, "q, k_new, v_new, k_pool, v_pool and out must be 16-byte aligned");
     if (((uintptr_t)seq_lens | (uintptr_t)block_table) & 3u)
         return fail(SW_ERR_ALIGN, "seq_lens and block_table must be 4-byte aligned");
 
     StepIn in;
     in.q = q; in.k = k_pool; in.v = v_pool; in.seq_lens = seq_lens; in.out = out;
+    in.k_new = k_new; in.v_new = v_new;
     in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
     in.block_table = block_table; in.block_size = block_size; in.max_blocks = max_blocks; in.n_blocks = n_blocks;
     in.stream = (hipStream_t)stream_v;
     return run_step(in);
+}
+
+int sw_decode_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                         const int32_t *block_table, const int32_t *seq_lens, void *out,
+                         int n_req, int n_qh, int n_kvh, int head_dim,
+                         int block_size, int max_blocks, int n_blocks, void *stream)
+{
+    return decode_paged(q, nullptr, nullptr, false, k_pool, v_pool, block_table, seq_lens, out,
+                        n_req, n_qh, n_kvh, head_dim, block_size, max_blocks, n_blocks, stream);
+}
+
+int sw_decode_attn_paged_append(const void *q, const void *k_new, const void *v_new,
+                                void *k_pool, void *v_pool,
+                                const int32_t *block_table, const int32_t *seq_lens, void *out,
+                                int n_req, int n_qh, int n_kvh, int head_dim,
+                                int block_size, int max_blocks, int n_blocks, void *stream)
+{
+    return decode_paged(q, k_new, v_new, true, k_pool, v_pool, block_table, seq_lens, out,
+                        n_req, n_qh, n_kvh, head_dim, block_size, max_blocks, n_blocks, stream);
 }
 
 }  // extern "C"

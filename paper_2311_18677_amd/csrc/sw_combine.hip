@@ -48,8 +48,7 @@ void sw_combine_kernel(SwArgs a)
         mlc[u] = ml[c * cs];
         x[u]   = po[c * cs * V4];
     }
-    int L = a.seq_lens[r];
-    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    const int L = sw_request_len(a, r);
     const int nc = (L + a.chunk - 1) >> a.chunk_shift;
     half4_t *out = reinterpret_cast<half4_t *>(reinterpret_cast<_Float16 *>(a.out) + (long long)rh * D) + j4;
     if (nc == 0) {

@@ -131,7 +131,7 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int
 template <int D>
 __device__ __forceinline__ void sw_fused_zero_rows(const SwArgs &a, int req)
 {
-    if (a.seq_lens[req] > 0) return;
+    if (sw_request_len(a, req) > 0) return;
     sw_half4_t z = sw_half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
     _Float16 *row = reinterpret_cast<_Float16 *>(a.out) + (long long)req * a.n_qh * D;
     for (int idx = threadIdx.x; idx < a.n_qh * (D / 4); idx += blockDim.x)

@@ -27,6 +27,8 @@ struct SwArgs {
     float          *ws_o;
     float          *ws_ml;
     unsigned       *counters;           // single-launch variant: one ticket counter per unit, else null
+    const uint16_t *k_new;              // append variant: the newest token's K rows [n_req][n_kvh][head_dim], else null
+    const uint16_t *v_new;              //                 and V rows
     const int32_t  *block_table;        // block-table variant: [n_req][max_blocks] pool block ids, else null
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
@@ -39,6 +41,28 @@ struct SwArgs {
     int   block_shift, max_blocks, n_blocks;   // block_size = 1 << block_shift
     float scale_log2e;                 // log2(e) / sqrt(head_dim)
 };
+
+// Number of cached positions request r attends over, with a flag.  seq_lens[r]
+// is clamped to [0, max_len]; in the append variant it counts the positions
+// cached BEFORE the newest token, whose K/V rows this call stores at that
+// position (and attends over) unless the cache is already full.  Bit
+// kSwAppendedBit of the result says that the rows are stored, i.e. that
+// position L - 1 is the new one; the bits below it hold L (max_len <= 2^23).
+constexpr int kSwAppendedBit = 30;
+constexpr int kSwLenMask     = (1 << kSwAppendedBit) - 1;
+
+__device__ inline int sw_request_len_flagged(const SwArgs &a, int r)
+{
+    int L = a.seq_lens[r];
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    if (a.k_new && L < a.max_len) L += 1 + (1 << kSwAppendedBit);
+    return L;
+}
+
+__device__ inline int sw_request_len(const SwArgs &a, int r)
+{
+    return sw_request_len_flagged(a, r) & kSwLenMask;
+}
 
 __host__ __device__ inline long long sw_ws_slot(const SwArgs &a, int r, int g, int c, int hh)
 {
@@ -62,6 +86,7 @@ bool       sw_partial_mfma2_supported(const SwArgs &a);
 hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 // Merge of the chunks' partial results, normalisation and rounding to binary16.
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+hipError_t sw_launch_advance_lens(int32_t *seq_lens, int n_req, int max_len, hipStream_t stream);
 
 // Granularity the chunk length must be a multiple of (all kernels).
 constexpr int SW_CHUNK_QUANTUM = 64;

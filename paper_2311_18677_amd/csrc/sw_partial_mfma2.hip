@@ -13,6 +13,12 @@
 //   wait K(i) | QK(i) from LDS | request K(i+1) | softmax(i) |
 //   wait V(i) | V(i) LDS->registers | request V(i+1) | transpose, PV(i)
 //
+// Append variant (the newest token's rows join the cache in the same pass,
+// paper section 2.2): the one wave whose tile holds the new position overwrites
+// that row of its staged K and V tiles with the new rows (brought into LDS once
+// per workgroup) and stores them to the cache in global memory; no other wave
+// or workgroup reads that position.
+//
 // Each wave owns 16 KB of LDS (K tile + V tile), so two 4-wave workgroups fit a
 // compute unit; with chunks of several tiles per wave the memory pipeline stays
 // busy through compute and epilogue phases.
@@ -62,7 +68,10 @@ __global__ __launch_bounds__(64 * WAVES, 2)
 void sw_partial_mfma2_kernel(SwArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
-    __shared__ __attribute__((aligned(16))) unsigned char sm_q[16 * kRowBytes];
+    // Q rows, then (append variant) the new K row and the new V row.  One array: the
+    // compiler sees no ordinary store into the new rows' part -- they arrive by
+    // global->LDS load only -- and must not take it for never written.
+    __shared__ __attribute__((aligned(16))) unsigned char sm_q[16 * kRowBytes + 1024];
     __shared__ float sm_m[WAVES][16];
     __shared__ float sm_l[WAVES][16];
     __shared__ int sm_flag;
@@ -93,6 +102,16 @@ void sw_partial_mfma2_kernel(SwArgs a)
             const uint16_t *src = a.q + ((long long)r * a.n_qh + g * a.group + row) * kD + 8 * (n16 ^ row);
             __builtin_amdgcn_global_load_lds(src, sm_q + wave * 1024, 16, 0, 0);
         }
+    }
+
+    // Append variant: position the new rows go to if it lies in this chunk, else -1
+    // (workgroup-uniform).  Wave 0 brings both rows into LDS with one load: lanes
+    // 0-15 the K row's 16-byte pieces, lanes 16-31 the V row's (lanes 32-63 repeat them).
+    unsigned char *sm_new = sm_q + 16 * kRowBytes;
+    const int new_pos = (w.new_pos >= t_begin && w.new_pos < t_end) ? w.new_pos : -1;
+    if (new_pos >= 0 && wave == 0) {
+        const uint16_t *src = ((gq & 1) ? a.v_new : a.k_new) + ((long long)r * a.n_kvh + g) * kD + 8 * n16;
+        __builtin_amdgcn_global_load_lds(src, sm_new, 16, 0, 0);
     }
 
     float m = kNegBig, l = 0.f;
@@ -169,6 +188,13 @@ void sw_partial_mfma2_kernel(SwArgs a)
         // ---- S^T = K Q^T : two 16-token blocks, four 32-dim steps.
         // Outstanding, oldest first: K(t0) x8, V(t0) x8.
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        // the new position lies in the chunk's last tile, which is some wave's last tile
+        const bool has_new = !MORE && new_pos >= t0 && new_pos < t0 + kTile;     // wave-uniform
+        if (has_new && gq == 0) {
+            const int rho = new_pos - t0;
+            *reinterpret_cast<uint4_t *>(wlds + rho * kRowBytes + ((n16 ^ (rho & 15)) << 4)) =
+                *reinterpret_cast<const uint4_t *>(sm_new + n16 * 16);
+        }
         float4_t sacc[2];
         sacc[0] = float4_t{0.f, 0.f, 0.f, 0.f};
         sacc[1] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -182,8 +208,14 @@ void sw_partial_mfma2_kernel(SwArgs a)
             sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0.h, qb.h, sacc[0], 0, 0, 0);
             sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1.h, qb.h, sacc[1], 0, 0, 0);
         }
-        // the K tile has been read into registers: its LDS area may be refilled
-        if (MORE) issue_k(t0_next, nb);
+        // The K tile's LDS area is refilled only once every read of it has RETURNED:
+        // the global->LDS writes arrive outside the LDS instruction queue, so a
+        // refill requested while reads are still queued can overtake them when the
+        // rows come back quickly (cache-resident data).
+        if (MORE) {
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+            issue_k(t0_next, nb);
+        }
 
         // ---- online softmax, base 2; this lane: head n16, tokens t0 + 16tb + 4gq + i
         float s[8];
@@ -231,6 +263,24 @@ void sw_partial_mfma2_kernel(SwArgs a)
         // Outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile.
         if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        if (has_new) {
+            // all of the wave's loads have landed: patch the staged V row, then store
+            // both rows to the cache (lanes 0-15 the K row, lanes 16-31 the V row)
+            if (gq == 0)
+                *reinterpret_cast<uint4_t *>(vlds + (new_pos - t0) * kRowBytes + n16 * 16) =
+                    *reinterpret_cast<const uint4_t *>(sm_new + 256 + n16 * 16);
+            if (gq < 2) {
+                long long boff = 0;
+                if (PAGED) {
+                    int id = table[new_pos >> a.block_shift];
+                    id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
+                    boff = 2 * (long long)id * a.stride_block;
+                }
+                char *dst = const_cast<char *>(gq ? vslab : kslab) + boff +
+                            ((((unsigned)new_pos & (unsigned)in_block) << 8) | (unsigned)(n16 << 4));
+                *reinterpret_cast<uint4_t *>(dst) = *reinterpret_cast<const uint4_t *>(sm_new + gq * 256 + n16 * 16);
+            }
+        }
         uint4_t vreg[8];
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
@@ -271,7 +321,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
         issue_k(t_begin + ti * kTile, fb);
         issue_v(t_begin + ti * kTile, fb);
     }
-    // Q must be in LDS before any wave goes on; the tile loads stay in flight
+    // Q (and the new rows) must be in LDS before any wave goes on; the tile loads stay in flight
     // across the barrier.  Vector-memory operations complete in issue order, so
     // "at most the 16 tile loads outstanding" means this wave's Q load is done.
     if (ti < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(16) & 0xc07f);   // vmcnt(16), lgkmcnt(0)

@@ -96,6 +96,11 @@ void sw_partial_valu_kernel(SwArgs a)
     }
 
     const bool paged = a.block_table != nullptr;     // then stride_req is 0 and k, v are block pools
+    // Append variant (paper section 2.2: the newest token's rows join the cache): the
+    // position the new rows go to if it lies in this chunk, else -1.  The lanes that
+    // would load that row take the new row instead, and the first head tile stores
+    // it to the cache.
+    const int new_pos = (w.new_pos >= t_begin && w.new_pos < t_end) ? w.new_pos : -1;
     const uint16_t *kbase = a.k + (long long)r * a.stride_req + (long long)g * a.stride_kvh + sub * 8;
     const uint16_t *vbase = a.v + (long long)r * a.stride_req + (long long)g * a.stride_kvh + sub * 8;
 
@@ -117,8 +122,18 @@ void sw_partial_valu_kernel(SwArgs a)
                     id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
                     row = (long long)id * a.stride_block + (long long)(t & ((1 << a.block_shift) - 1)) * D;
                 }
-                kk[u] = stream_load(kbase + row);
-                vv[u] = stream_load(vbase + row);
+                if (t == new_pos) {
+                    const long long src = ((long long)r * a.n_kvh + g) * D + sub * 8;
+                    kk[u] = *reinterpret_cast<const Row8 *>(a.k_new + src);
+                    vv[u] = *reinterpret_cast<const Row8 *>(a.v_new + src);
+                    if (ht == 0) {
+                        *reinterpret_cast<Row8 *>(const_cast<uint16_t *>(kbase + row)) = kk[u];
+                        *reinterpret_cast<Row8 *>(const_cast<uint16_t *>(vbase + row)) = vv[u];
+                    }
+                } else {
+                    kk[u] = stream_load(kbase + row);
+                    vv[u] = stream_load(vbase + row);
+                }
             }
         }
 #pragma unroll

@@ -20,17 +20,13 @@ struct SwWork {
     int  r;       // request
     int  g;       // key/value head
     int  c;       // chunk index
-    int  L;       // clamped length of request r
+    int  L;       // number of positions request r attends over
+    int  new_pos; // append variant: position this call stores the newest rows at, else -1
     bool valid;   // false: this workgroup has nothing to do
 };
 
 constexpr int kSwMaxPerLane   = 16;
 constexpr int kSwMaxScanReqs  = 64 * kSwMaxPerLane;
-
-__device__ __forceinline__ int sw_clamp_len(int L, int max_len)
-{
-    return L < 0 ? 0 : (L > max_len ? max_len : L);
-}
 
 // Inclusive prefix sum over the 64 lanes of a wave.
 __device__ __forceinline__ int sw_wave_inclusive_scan(int x)
@@ -78,8 +74,8 @@ __device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
         for (int j = 0; j < PER; ++j) {
             const int r = lane * PER + j;
             s.len[j] = 0;
-            if (r < a.n_req) s.len[j] = sw_clamp_len(a.seq_lens[r], a.max_len);
-            s.cnt[j] = (s.len[j] + a.chunk - 1) >> a.chunk_shift;
+            if (r < a.n_req) s.len[j] = sw_request_len_flagged(a, r);
+            s.cnt[j] = ((s.len[j] & kSwLenMask) + a.chunk - 1) >> a.chunk_shift;
             s.mine += s.cnt[j];
         }
         s.incl = sw_wave_inclusive_scan(s.mine);
@@ -94,6 +90,7 @@ __device__ __forceinline__ SwWork sw_lookup(const SwArgs &a, const SwScan<PER> &
     SwWork w;
     w.valid = false;
     w.r = w.g = w.c = w.L = 0;
+    w.new_pos = -1;
     if constexpr (PER == 0) {
         // direct mapping: b = c * n_units + unit
         const unsigned n_units = (unsigned)a.n_req * (unsigned)a.n_kvh;
@@ -101,7 +98,9 @@ __device__ __forceinline__ SwWork sw_lookup(const SwArgs &a, const SwScan<PER> &
         w.r = (int)(unit / (unsigned)a.n_kvh);
         w.g = (int)(unit - (unsigned)w.r * (unsigned)a.n_kvh);
         w.c = (int)c;
-        w.L = sw_clamp_len(a.seq_lens[w.r], a.max_len);
+        const int lf = sw_request_len_flagged(a, w.r);
+        w.L = lf & kSwLenMask;
+        if ((lf >> kSwAppendedBit) & 1) w.new_pos = w.L - 1;
         w.valid = ((long long)w.c << a.chunk_shift) < w.L;
         return w;
     } else {
@@ -122,7 +121,8 @@ __device__ __forceinline__ SwWork sw_lookup(const SwArgs &a, const SwScan<PER> &
                 w.r = max(0, min(owner * PER + j, a.n_req - 1));
                 w.g = (int)min(gg, (unsigned)(a.n_kvh - 1));
                 w.c = (int)(rem - (unsigned)w.g * cj) & 0x7fffffff;
-                w.L = min(max(lj, 0), a.max_len);
+                w.L = min(lj & kSwLenMask, a.max_len);
+                if (((lj >> kSwAppendedBit) & 1) && w.L > 0) w.new_pos = w.L - 1;
                 w.valid = ((long long)w.c << a.chunk_shift) < w.L;
                 found = true;
             }

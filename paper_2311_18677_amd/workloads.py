@@ -129,6 +129,19 @@ def make_batch(cfg, seed=None, seq_lens=None):
     return Batch(cfg, int(seed), lens, q, k_rows, v_rows)
 
 
+def make_new_rows(cfg, seed, step=0):
+    """K and V rows of the token each request generates next: float16 [n_req, n_kvh, head_dim] each.
+
+    Same value distribution as the cached rows; `step` selects an independent draw per
+    decode iteration (and per layer, if the caller folds the layer into it).
+    """
+    ss = np.random.SeedSequence([int(seed), 0x6E6577, int(step)]).spawn(2)
+    shape = (cfg.n_req, cfg.n_kvh, cfg.head_dim)
+    k = np.random.Generator(np.random.Philox(ss[0])).standard_normal(shape, dtype=np.float32)
+    v = np.random.Generator(np.random.Philox(ss[1])).standard_normal(shape, dtype=np.float32)
+    return k.astype(np.float16), v.astype(np.float16)
+
+
 def custom_config(name, n_req, n_qh, n_kvh, head_dim, max_len, n_layers=1):
     """A free-form shape for edge-case tests; pass seq_lens to make_batch."""
     return Config(name, n_req, n_qh, n_kvh, head_dim, max_len, ("fixed", (0,) * n_req),
@@ -165,7 +178,7 @@ def dense_layout(cfg):
 
 
 def pack_paged(k_rows, v_rows, cfg, block_size, stride_block, stride_kvh, stride_tok, n_blocks,
-               seed=0, pad_bits=0, spare_bits=None):
+               seed=0, pad_bits=0, spare_bits=None, room=0):
     """Scatter compact valid rows into K and V block pools with a shuffled block table.
 
     Request r gets ceil(L_r / block_size) pool blocks drawn without replacement from
@@ -174,11 +187,17 @@ def pack_paged(k_rows, v_rows, cfg, block_size, stride_block, stride_kvh, stride
     last block and stride padding hold pad_bits.  Table entries past a request's
     last block hold spare_bits (default: an id far out of range), which the
     library must never follow.
+    room > 0 also allots the blocks of the next `room` positions of every request
+    (up to max_len), for callers that go on to append tokens.
     Returns (k_pool, v_pool, block_table) as flat uint16 / uint16 / int32 [n_req, max_blocks].
     """
     d = cfg.head_dim
     max_blocks = -(-cfg.max_len // block_size)
-    need = sum(-(-blk.shape[1] // block_size) for blk in k_rows)
+
+    def owned(L):
+        return -(-min(L + room, cfg.max_len) // block_size)
+
+    need = sum(owned(blk.shape[1]) for blk in k_rows)
     if need > n_blocks:
         raise ValueError("pool of %d blocks cannot hold %d" % (n_blocks, need))
     total = int(n_blocks) * int(stride_block)
@@ -194,11 +213,13 @@ def pack_paged(k_rows, v_rows, cfg, block_size, stride_block, stride_kvh, stride
     nxt = 0
     for r, (kb, vb) in enumerate(zip(k_rows, v_rows)):
         L = kb.shape[1]
-        for i in range(-(-L // block_size)):
+        for i in range(owned(L)):
             b = int(order[nxt])
             nxt += 1
             table[r, i] = b
             n = min(block_size, L - i * block_size)
+            if n <= 0:
+                continue
             kv[b, :, :n, :] = kb[:, i * block_size:i * block_size + n, :].view(np.uint16)
             vv[b, :, :n, :] = vb[:, i * block_size:i * block_size + n, :].view(np.uint16)
     return k_pool, v_pool, table

@@ -145,3 +145,33 @@ def test_paged_layout_and_validation():
     assert pcall(bs=4096, mb=4096) == sw.SW_ERR_SHAPE
     assert pcall(n_qh=8, n_kvh=3) == sw.SW_ERR_SHAPE
     assert pcall(n_req=0) == sw.SW_OK
+
+
+def test_append_validation():
+    def acall(q=0x1000, kn=0x7000, vn=0x8000, k=0x2000, v=0x3000, lens=0x5000, out=0x6000,
+              n_req=2, n_qh=8, n_kvh=2, d=128, max_len=256):
+        return sw.sw_decode_attn_append(q, kn, vn, k, v, lens, out, n_req, n_qh, n_kvh, d, max_len,
+                                        None, check=False)
+    # every call fails validation (or is empty), so none reaches a HIP call
+    assert acall(kn=None) == sw.SW_ERR_NULL
+    assert acall(vn=None) == sw.SW_ERR_NULL
+    assert acall(k=None) == sw.SW_ERR_NULL
+    assert acall(kn=0x7008) == sw.SW_ERR_ALIGN
+    assert acall(vn=0x8002) == sw.SW_ERR_ALIGN
+    assert acall(d=96) == sw.SW_ERR_UNSUPPORTED
+    assert acall(max_len=0) == sw.SW_ERR_SHAPE
+    assert acall(n_req=0) == sw.SW_OK
+
+    def pcall(kn=0x7000, vn=0x8000, tab=0x4000, bs=16):
+        return sw.sw_decode_attn_paged_append(0x1000, kn, vn, 0x2000, 0x3000, tab, 0x5000, 0x6000,
+                                              2, 8, 2, 128, bs, 8, 32, None, check=False)
+    assert pcall(kn=None) == sw.SW_ERR_NULL
+    assert pcall(vn=0x8004) == sw.SW_ERR_ALIGN
+    assert pcall(tab=None) == sw.SW_ERR_NULL
+    assert pcall(bs=24) == sw.SW_ERR_UNSUPPORTED
+
+    assert sw.sw_advance_lens(None, 4, 128, check=False) == sw.SW_ERR_NULL
+    assert sw.sw_advance_lens(0x1002, 4, 128, check=False) == sw.SW_ERR_ALIGN
+    assert sw.sw_advance_lens(0x1000, -1, 128, check=False) == sw.SW_ERR_SHAPE
+    assert sw.sw_advance_lens(0x1000, 4, 0, check=False) == sw.SW_ERR_SHAPE
+    assert sw.sw_advance_lens(0x1000, 0, 128, check=False) == sw.SW_OK

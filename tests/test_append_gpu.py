@@ -1,0 +1,220 @@
+"""GPU parity of the append-then-attend variants: the cache after the call equals the
+oracle's cache bit for bit, the output matches the oracle on that cache, and it has
+the bits of the plain call on the updated cache."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_18677_amd import binding as sw
+from paper_2311_18677_amd import workloads as wl
+from helpers import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+NAN_BITS = 0x7E00
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    def reset():
+        for key in (sw.SW_PARAM_CHUNK, sw.SW_PARAM_KERNEL, sw.SW_PARAM_COMBINE, sw.SW_PARAM_WAVES):
+            sw.sw_set_param(key, 0)
+    reset()
+    yield
+    reset()
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16).reshape(-1)).to("cuda:0").view(torch.float16)
+
+
+def bits(t):
+    return t.cpu().numpy().view(np.uint16).reshape(-1)
+
+
+def dense_append_case(batch, seed, tag):
+    """Run one append call; return (out, plain-call out on the updated cache, ref, bufs)."""
+    import torch
+    cfg = batch.cfg
+    bufs = sw.upload_batch(batch, pad_bits=NAN_BITS)
+    lay = bufs["layout"]
+    kn, vn = wl.make_new_rows(cfg, seed)
+    k_host, v_host = bufs["k_host"].copy(), bufs["v_host"].copy()
+    new_lens = oracle.kv_append(kn, vn, k_host, v_host, batch.seq_lens, cfg.n_req, cfg.n_kvh,
+                                cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok)
+    ref = oracle.decode_attn(batch.q, k_host, v_host, new_lens, cfg.n_req, cfg.n_qh, cfg.n_kvh,
+                             cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok)
+    kn_d, vn_d = to_dev(kn), to_dev(vn)
+    print("append run", tag, cfg.name, "kernel", sw.sw_get_param(sw.SW_PARAM_KERNEL),
+          "combine", sw.sw_get_param(sw.SW_PARAM_COMBINE), flush=True)
+    sw.sw_decode_attn_append(bufs["q"], kn_d, vn_d, bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"],
+                             bufs["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+    torch.cuda.synchronize()
+    out = bufs["out"].cpu().numpy()
+    # the caches now hold exactly what the oracle's hold; the lengths were not touched
+    assert np.array_equal(bits(bufs["k_cache"]), k_host), "K cache differs after append"
+    assert np.array_equal(bits(bufs["v_cache"]), v_host), "V cache differs after append"
+    assert np.array_equal(bufs["seq_lens"].cpu().numpy(), batch.seq_lens)
+    # the plain call on the updated cache with the lengths after the append
+    lens_d = torch.from_numpy(new_lens).to("cuda:0")
+    out2 = torch.full_like(bufs["out"], float("nan"))
+    sw.sw_decode_attn(bufs["q"], bufs["k_cache"], bufs["v_cache"], lens_d, out2, cfg.n_req, cfg.n_qh,
+                      cfg.n_kvh, cfg.head_dim, cfg.max_len)
+    torch.cuda.synchronize()
+    return out, out2.cpu().numpy(), ref, new_lens
+
+
+EDGE_LENS = [0, 1, -3, 3, 30, 31, 32, 33, 63, 64, 127, 128, 255, 256, 257, 400, 511, 512, 700,
+             766, 767, 768, 900]           # max_len 768: 767 fills the last slot, 768 and 900 are full
+
+SHAPES = [  # n_qh, n_kvh, d, kernel (0 = default), combine
+    (8, 1, 128, 0, 0), (8, 1, 128, 1, 0), (14, 14, 128, 0, 0), (8, 8, 64, 0, 0), (24, 1, 128, 0, 0),
+    (16, 2, 128, 3, 0), (6, 2, 64, 1, 0), (8, 1, 128, 3, 2), (8, 2, 128, 1, 2),
+]
+
+
+@pytest.mark.parametrize("n_qh,n_kvh,d,kernel,combine", SHAPES)
+def test_append_matches_oracle_cache_and_plain_call_bits(n_qh, n_kvh, d, kernel, combine):
+    cfg = wl.custom_config("ap%d_%d_%d" % (n_qh, n_kvh, d), len(EDGE_LENS), n_qh, n_kvh, d, 768)
+    batch = wl.make_batch(cfg, seed=9000 + n_qh + d, seq_lens=EDGE_LENS)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, combine)
+    out, plain, ref, new_lens = dense_append_case(batch, 9000 + n_qh, "edge")
+    assert new_lens.tolist() == [min(max(L, 0) + 1, 768) for L in EDGE_LENS]
+    assert_parity(out, ref, cfg.name)
+    assert np.array_equal(out.view(np.uint16), plain.view(np.uint16))
+    # an empty cache attends over the new token alone: the output is v_new, exactly
+    _, vn = wl.make_new_rows(cfg, 9000 + n_qh)
+    g = np.repeat(np.arange(n_kvh), n_qh // n_kvh)
+    for r in (0, 2):
+        assert np.array_equal(out[r].view(np.uint16), vn[r][g].view(np.uint16))
+
+
+@pytest.mark.parametrize("chunk", [64, 256, 1024])
+@pytest.mark.parametrize("waves", [4, 8])
+def test_append_at_chunk_and_tile_boundaries(chunk, waves):
+    lens = [chunk - 1, chunk, chunk + 1, 2 * chunk - 1, 2 * chunk, 2 * chunk + 31, 2 * chunk + 32,
+            4 * chunk - 1, 0, 5]
+    cfg = wl.custom_config("apc%d" % chunk, len(lens), 8, 1, 128, 4 * chunk)
+    batch = wl.make_batch(cfg, seed=9100 + chunk, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, chunk)
+    sw.sw_set_param(sw.SW_PARAM_WAVES, waves)
+    out, plain, ref, _ = dense_append_case(batch, 9100 + chunk, "chunk%d waves%d" % (chunk, waves))
+    assert_parity(out, ref, cfg.name)
+    assert np.array_equal(out.view(np.uint16), plain.view(np.uint16))
+
+
+@pytest.mark.parametrize("n_req", [65, 300, 1100])
+@pytest.mark.parametrize("kernel", [0, 1])
+def test_append_many_requests(n_req, kernel):
+    rng = np.random.Generator(np.random.Philox(9200 + n_req))
+    lens = rng.integers(0, 130, size=n_req).astype(np.int32)
+    lens[::7] = 128                                   # full caches sprinkled in
+    cfg = wl.custom_config("apm%d" % n_req, n_req, 8, 1, 128, 128)
+    batch = wl.make_batch(cfg, seed=9200 + n_req, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    out, plain, ref, _ = dense_append_case(batch, 9200 + n_req, "many%d" % n_req)
+    assert_parity(out, ref, cfg.name)
+    assert np.array_equal(out.view(np.uint16), plain.view(np.uint16))
+
+
+@pytest.mark.parametrize("name", ["tiny_mha", "llama70b_tp8", "bloom176b_tp8", "longctx_8x32k"])
+def test_append_full_size_configs(name):
+    batch = wl.make_batch(name)
+    out, plain, ref, _ = dense_append_case(batch, 9300, name)
+    errs = assert_parity(out, ref, name)
+    print(name, "append max_abs %.3e row_rel_l2 %.3e whole_rel_l2 %.3e" % errs)
+    assert np.array_equal(out.view(np.uint16), plain.view(np.uint16))
+
+
+@pytest.mark.parametrize("block_size", [4, 16, 256])
+@pytest.mark.parametrize("n_qh,n_kvh,d,kernel", [(8, 1, 128, 0), (8, 1, 128, 1), (14, 14, 128, 0),
+                                                  (8, 8, 64, 0), (16, 2, 128, 3)])
+def test_paged_append_matches_oracle_pool_and_dense_bits(n_qh, n_kvh, d, kernel, block_size):
+    import torch
+    cfg = wl.custom_config("pap%d_%d_%d" % (n_qh, n_kvh, d), len(EDGE_LENS), n_qh, n_kvh, d, 768)
+    seed = 9400 + n_qh + d + block_size
+    batch = wl.make_batch(cfg, seed=seed, seq_lens=EDGE_LENS)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    bufs = sw.upload_paged_batch(batch, block_size, seed=seed, pad_bits=NAN_BITS, room=1)
+    lay = bufs["layout"]
+    kn, vn = wl.make_new_rows(cfg, seed)
+    kp, vp = bufs["k_host"].copy(), bufs["v_host"].copy()
+    geom = (bufs["block_size"], bufs["max_blocks"], bufs["n_blocks"],
+            lay.stride_block, lay.stride_kvh, lay.stride_tok)
+    new_lens = oracle.kv_append_paged(kn, vn, kp, vp, bufs["table_host"], batch.seq_lens, cfg.n_req,
+                                      cfg.n_kvh, d, *geom)
+    ref = oracle.decode_attn_paged(batch.q, kp, vp, bufs["table_host"], new_lens, cfg.n_req, n_qh,
+                                   n_kvh, d, *geom)
+    print("paged append run", cfg.name, "block", block_size, "kernel", kernel, flush=True)
+    sw.sw_decode_attn_paged_append(bufs["q"], to_dev(kn), to_dev(vn), bufs["k_pool"], bufs["v_pool"],
+                                   bufs["block_table"], bufs["seq_lens"], bufs["out"], cfg.n_req, n_qh,
+                                   n_kvh, d, block_size, bufs["max_blocks"], bufs["n_blocks"])
+    torch.cuda.synchronize()
+    out = bufs["out"].cpu().numpy()
+    assert np.array_equal(bits(bufs["k_pool"]), kp) and np.array_equal(bits(bufs["v_pool"]), vp)
+    assert_parity(out, ref, cfg.name)
+    # same bits as the dense append call on the same values
+    dense, _, _, _ = dense_append_case(batch, seed, "dense twin")
+    assert np.array_equal(out.view(np.uint16), dense.view(np.uint16))
+
+
+def test_advance_lens():
+    import torch
+    lens = np.array([0, 1, -7, 126, 127, 128, 4000, -2 ** 31, 2 ** 31 - 1] + list(range(300)), np.int32)
+    d = torch.from_numpy(lens).to("cuda:0")
+    sw.sw_advance_lens(d, lens.size, 128)
+    torch.cuda.synchronize()
+    want = np.minimum(np.clip(lens.astype(np.int64), 0, 128) + 1, 128).astype(np.int32)
+    assert np.array_equal(d.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("kernel", [0, 1])
+def test_decode_loop_over_layers_and_steps(kernel):
+    """Three layer caches, six model steps: append + attend per layer, lengths advanced on the
+    device once per step; requests cross a tile edge, a chunk edge and fill up on the way."""
+    import torch
+    n_layers, n_steps = 3, 6
+    lens0 = [0, 29, 254, 509, 510, 100]
+    cfg = wl.custom_config("loop", len(lens0), 8, 2, 128, 512)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 256)
+    layers = []
+    for layer in range(n_layers):
+        b = wl.make_batch(cfg, seed=9500 + layer, seq_lens=lens0)
+        bufs = sw.upload_batch(b, pad_bits=NAN_BITS)
+        layers.append((b, bufs, bufs["k_host"].copy(), bufs["v_host"].copy()))
+    lay = layers[0][1]["layout"]
+    lens_dev = layers[0][1]["seq_lens"]
+    lens_host = np.array(lens0, np.int32)
+    stream = torch.cuda.Stream()
+    for step in range(n_steps):
+        outs, refs = [], []
+        with torch.cuda.stream(stream):
+            for layer, (b, bufs, kh, vh) in enumerate(layers):
+                kn, vn = wl.make_new_rows(cfg, 9500, step * n_layers + layer)
+                q = wl.make_batch(cfg, seed=9600 + step * n_layers + layer, seq_lens=[0] * cfg.n_req).q
+                q_d, kn_d, vn_d = to_dev(q), to_dev(kn), to_dev(vn)
+                out = torch.full((cfg.n_req, cfg.n_qh, cfg.head_dim), float("nan"),
+                                 dtype=torch.float16, device="cuda:0")
+                print("loop step", step, "layer", layer, "kernel", kernel, flush=True)
+                sw.sw_decode_attn_append(q_d, kn_d, vn_d, bufs["k_cache"], bufs["v_cache"], lens_dev, out,
+                                         cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len,
+                                         stream=stream)
+                outs.append((out, q_d, kn_d, vn_d))
+                new_lens = oracle.kv_append(kn, vn, kh, vh, lens_host, cfg.n_req, cfg.n_kvh,
+                                            cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh,
+                                            lay.stride_tok)
+                refs.append(oracle.decode_attn(q, kh, vh, new_lens, cfg.n_req, cfg.n_qh, cfg.n_kvh,
+                                               cfg.head_dim, cfg.max_len, lay.stride_req,
+                                               lay.stride_kvh, lay.stride_tok))
+            sw.sw_advance_lens(lens_dev, cfg.n_req, cfg.max_len, stream=stream)
+        stream.synchronize()
+        lens_host = new_lens
+        assert np.array_equal(lens_dev.cpu().numpy(), lens_host), step
+        for layer in range(n_layers):
+            assert_parity(outs[layer][0].cpu().numpy(), refs[layer], "step %d layer %d" % (step, layer))
+    assert lens_host.tolist() == [6, 35, 260, 512, 512, 106]
+    for b, bufs, kh, vh in layers:
+        assert np.array_equal(bits(bufs["k_cache"]), kh) and np.array_equal(bits(bufs["v_cache"]), vh)

@@ -320,3 +320,87 @@ def test_paged_oracle_matches_brute_force_and_clamps():
     lens2 = np.array([-1, 99, 19], np.int32)
     got2 = oracle.decode_attn_paged(b.q, kp, vp, table, lens2, 3, 4, 4, 64, 8, 4, 12, sb, sg, st)
     assert np.array_equal(got2[0], np.zeros((4, 64))) and np.array_equal(got2[1], got[1])
+
+
+# ---- append-then-attend (the cache side of one decode iteration) ----
+
+def _dense_views(buf, cfg, sr, sg, st):
+    return np.lib.stride_tricks.as_strided(
+        buf, shape=(cfg.n_req, cfg.n_kvh, cfg.max_len, cfg.head_dim), strides=(2 * sr, 2 * sg, 2 * st, 2))
+
+
+def test_kv_append_matches_array_slicing_and_touches_nothing_else():
+    cfg = wl.custom_config("ap", 5, 6, 2, 64, 48)
+    lens = np.array([0, 47, 48, 13, -3], np.int32)       # empty, last free slot, full, middle, negative
+    b = wl.make_batch(cfg, seed=93, seq_lens=lens)
+    kn, vn = wl.make_new_rows(cfg, 93)
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    sg += 24; sr = 2 * sg + 40; tot = 5 * sr               # padded strides
+    k = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0x7E00)
+    v = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0x7E01)
+    ek, ev = k.copy(), v.copy()
+    ekv, evv = _dense_views(ek, cfg, sr, sg, st), _dense_views(ev, cfg, sr, sg, st)
+    for r, pos in enumerate([0, 47, None, 13, 0]):
+        if pos is not None:
+            ekv[r, :, pos, :] = kn[r].view(np.uint16)
+            evv[r, :, pos, :] = vn[r].view(np.uint16)
+    out = oracle.kv_append(kn, vn, k, v, lens, 5, 2, 64, 48, sr, sg, st)
+    assert out.tolist() == [1, 48, 48, 14, 1]
+    assert np.array_equal(k, ek) and np.array_equal(v, ev)
+    assert not np.array_equal(k, v)                       # K rows went to K, V rows to V
+
+
+def test_append_then_attend_equals_attending_over_the_longer_context():
+    # a step of the append variant = the plain step on a cache that already holds the token
+    cfg = wl.custom_config("ap2", 4, 4, 2, 64, 40)
+    lens = np.array([5, 39, 0, 40], np.int32)
+    b = wl.make_batch(cfg, seed=94, seq_lens=lens)
+    kn, vn = wl.make_new_rows(cfg, 94)
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    k = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0x7E00)
+    v = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0x7E00)
+    new_lens = oracle.kv_append(kn, vn, k, v, lens, 4, 2, 64, 40, sr, sg, st)
+    got = oracle.decode_attn(b.q, k, v, new_lens, 4, 4, 2, 64, 40, sr, sg, st)
+    kd = np.zeros((4, 2, 40, 64), np.float16)
+    vd = np.zeros((4, 2, 40, 64), np.float16)
+    longer = []
+    for r in range(4):
+        L = int(lens[r])
+        kr, vr = b.k_rows[r], b.v_rows[r]
+        if L < 40:
+            kr = np.concatenate([kr, kn[r][:, None, :]], axis=1)
+            vr = np.concatenate([vr, vn[r][:, None, :]], axis=1)
+        kd[r, :, :kr.shape[1]] = kr
+        vd[r, :, :vr.shape[1]] = vr
+        longer.append(kr.shape[1])
+    assert new_lens.tolist() == longer == [6, 40, 1, 40]
+    assert np.allclose(got, brute(b.q, kd, vd, np.array(longer, np.int32)), rtol=1e-12, atol=1e-14)
+    # the request with an empty cache attends over its own token only: the result is v_new
+    g = np.repeat(np.arange(2), 2)
+    assert np.array_equal(got[2], vn[2][g].astype(np.float64))
+
+
+@pytest.mark.parametrize("block_size", [4, 16])
+def test_paged_kv_append_equals_dense_kv_append(block_size):
+    cfg = wl.custom_config("ap3", 5, 4, 2, 64, 64)
+    lens = np.array([0, 16, 63, 64, 21], np.int32)        # new block needed, last slot, full
+    b = wl.make_batch(cfg, seed=95, seq_lens=lens)
+    kn, vn = wl.make_new_rows(cfg, 95)
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    k = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0)
+    v = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0)
+    new_lens = oracle.kv_append(kn, vn, k, v, lens, 5, 2, 64, 64, sr, sg, st)
+    dense = oracle.decode_attn(b.q, k, v, new_lens, 5, 4, 2, 64, 64, sr, sg, st)
+    sb, sgp, stp = wl.dense_paged_layout(cfg, block_size)
+    mb = 64 // block_size
+    n_blocks = 5 * mb + 2
+    kp, vp, table = wl.pack_paged(b.k_rows, b.v_rows, cfg, block_size, sb, sgp, stp, n_blocks,
+                                  seed=5, pad_bits=0x7E00, room=1)
+    kp0 = kp.copy()
+    lens_p = oracle.kv_append_paged(kn, vn, kp, vp, table, lens, 5, 2, 64, block_size, mb, n_blocks,
+                                    sb, sgp, stp)
+    assert np.array_equal(lens_p, new_lens)
+    assert int((kp != kp0).any(axis=None)) and np.count_nonzero(kp != kp0) <= 4 * 2 * 64
+    paged = oracle.decode_attn_paged(b.q, kp, vp, table, lens_p, 5, 4, 2, 64, block_size, mb, n_blocks,
+                                     sb, sgp, stp)
+    assert np.array_equal(paged, dense) and np.all(np.isfinite(paged))
