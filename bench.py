@@ -7,6 +7,11 @@ calls rotate over several distinct cache sets so that the K/V rows come from
 HBM, not from the last-level cache.  One JSON line is printed.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+--append times the append-then-attend entry point instead (same rotation, the
+newest rows rewritten in place every call).  --decode-loop runs whole model
+steps: one append-then-attend call per layer over that many per-layer caches
+sharing one length array, then sw_advance_lens; a "step" is still one layer call.
 """
 import argparse
 import json
@@ -36,17 +41,32 @@ def parse_args():
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--paged", type=int, default=0, metavar="BLOCK",
                     help="run the block-table variant with this block size (0 = dense layout)")
+    ap.add_argument("--append", action="store_true",
+                    help="time sw_decode_attn_append / sw_decode_attn_paged_append")
+    ap.add_argument("--decode-loop", action="store_true",
+                    help="whole model steps: the workload's layer count of per-layer caches, one "
+                         "append-then-attend call each, lengths advanced on the device per step")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch plain device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings); 0 = none")
     return ap.parse_args()
 
 
-def make_device_set(cfg, lay, seed, torch, np, wl, dev):
+def add_new_rows(bufs, cfg, g, torch, dev):
+    """The newest token's K and V rows for the append variants, N(0,1) like the cache."""
+    for name in ("k_new", "v_new"):
+        t = torch.empty(cfg.n_req * cfg.n_kvh * cfg.head_dim, dtype=torch.float16, device=dev)
+        t.normal_(0.0, 1.0, generator=g)
+        bufs[name] = t
+
+
+def make_device_set(cfg, lay, seed, torch, np, wl, dev, lens=None):
     """A cache set generated on the device: same shapes, lengths from the config's
-    recipe, values N(0,1) in binary16 (every position, so padding is arbitrary data)."""
+    recipe (or the ones given), values N(0,1) in binary16 (every position, so padding
+    is arbitrary data)."""
     rng = np.random.Generator(np.random.Philox(np.random.SeedSequence(int(seed))))
-    lens = wl.draw_seq_lens(cfg, rng)
+    if lens is None:
+        lens = wl.draw_seq_lens(cfg, rng)
     g = torch.Generator(device=dev)
     g.manual_seed(int(seed))
     bufs = {}
@@ -66,16 +86,19 @@ def make_device_set(cfg, lay, seed, torch, np, wl, dev):
     bufs["out"] = torch.zeros((cfg.n_req, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
     valid = np.clip(lens, 0, cfg.max_len).astype(np.int64)
     bufs["kv_bytes"] = int(valid.sum()) * cfg.n_kvh * cfg.head_dim * 4
+    add_new_rows(bufs, cfg, g, torch, dev)
     return bufs
 
 
-def make_paged_set(cfg, block_size, seed, torch, np, wl, sw, dev):
+def make_paged_set(cfg, block_size, seed, torch, np, wl, sw, dev, lens=None, room=0):
     """A block-table cache set generated on the device: pools of exactly the blocks the
-    lengths need (plus 3), values N(0,1), a seeded random block assignment."""
+    lengths (plus `room` further positions) need, plus 3, values N(0,1), a seeded random
+    block assignment."""
     rng = np.random.Generator(np.random.Philox(np.random.SeedSequence(int(seed))))
-    lens = wl.draw_seq_lens(cfg, rng)
+    if lens is None:
+        lens = wl.draw_seq_lens(cfg, rng)
     valid = np.clip(lens, 0, cfg.max_len).astype(np.int64)
-    per_req = -(-valid // block_size)
+    per_req = -(-np.minimum(valid + room, cfg.max_len) // block_size)
     n_blocks = int(per_req.sum()) + 3
     max_blocks = -(-cfg.max_len // block_size)
     lay = sw.sw_kv_paged_layout(n_blocks, cfg.n_kvh, cfg.head_dim, block_size)
@@ -104,6 +127,7 @@ def make_paged_set(cfg, block_size, seed, torch, np, wl, sw, dev):
     bufs["seq_lens"] = torch.from_numpy(lens).to(dev)
     bufs["out"] = torch.zeros((cfg.n_req, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
     bufs["kv_bytes"] = int(valid.sum()) * cfg.n_kvh * cfg.head_dim * 4
+    add_new_rows(bufs, cfg, g, torch, dev)
     return bufs
 
 
@@ -144,20 +168,33 @@ def main():
     lay = sw.sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)
 
     # ---- inputs: set 0 from the host recipe (also the oracle's input), the rest on device
+    append = args.append or args.decode_loop
+    loop = args.decode_loop
+    room = (args.steps + args.warmup) // cfg.n_layers + 60 if loop else (1 if append else 0)
     batch0 = wl.make_batch(cfg)
     if args.paged:
-        set0 = sw.upload_paged_batch(batch0, args.paged, device="cuda:0", pad_bits=0)
+        set0 = sw.upload_paged_batch(batch0, args.paged, device="cuda:0", pad_bits=0, room=room)
     else:
         set0 = sw.upload_batch(batch0, device="cuda:0", pad_bits=0)
     set0["kv_bytes"] = batch0.kv_bytes
-    n_sets = args.sets or max(2, -(-4 * LLC_BYTES // max(batch0.kv_bytes, 1)))
+    kn0, vn0 = wl.make_new_rows(cfg, batch0.seed)
+    for name, rows in (("k_new", kn0), ("v_new", vn0)):
+        set0[name] = torch.from_numpy(rows.view(np.int16).reshape(-1)).to(dev).view(torch.float16)
+    if loop:
+        n_sets = cfg.n_layers        # one cache per layer, all with the batch's lengths
+    else:
+        n_sets = args.sets or max(2, -(-4 * LLC_BYTES // max(batch0.kv_bytes, 1)))
     sets = [set0]
     for i in range(1, n_sets):
         seed_i = wl.BASE_SEED + 1000 * cfg.seed_index + i
+        lens_i = batch0.seq_lens if loop else None
         if args.paged:
-            sets.append(make_paged_set(cfg, args.paged, seed_i, torch, np, wl, sw, dev))
+            sets.append(make_paged_set(cfg, args.paged, seed_i, torch, np, wl, sw, dev, lens_i, room))
         else:
-            sets.append(make_device_set(cfg, lay, seed_i, torch, np, wl, dev))
+            sets.append(make_device_set(cfg, lay, seed_i, torch, np, wl, dev, lens_i))
+    if loop:
+        for s in sets[1:]:
+            s["seq_lens"] = set0["seq_lens"]      # the layers of a model share one length array
     torch.cuda.synchronize()
 
     if args.copy_calibration:
@@ -173,7 +210,16 @@ def main():
     stream = torch.cuda.Stream(device=dev)
 
     def call(s, st):
-        if args.paged:
+        if append and args.paged:
+            sw.sw_decode_attn_paged_append(s["q"], s["k_new"], s["v_new"], s["k_pool"], s["v_pool"],
+                                           s["block_table"], s["seq_lens"], s["out"], cfg.n_req,
+                                           cfg.n_qh, cfg.n_kvh, cfg.head_dim, s["block_size"],
+                                           s["max_blocks"], s["n_blocks"], st)
+        elif append:
+            sw.sw_decode_attn_append(s["q"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"],
+                                     s["seq_lens"], s["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh,
+                                     cfg.head_dim, cfg.max_len, st)
+        elif args.paged:
             sw.sw_decode_attn_paged(s["q"], s["k_pool"], s["v_pool"], s["block_table"], s["seq_lens"],
                                     s["out"], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
                                     s["block_size"], s["max_blocks"], s["n_blocks"], st)
@@ -181,9 +227,49 @@ def main():
             sw.sw_decode_attn(s["q"], s["k_cache"], s["v_cache"], s["seq_lens"], s["out"],
                               cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
 
+    def end_of_model_step(st):
+        if loop:
+            sw.sw_advance_lens(set0["seq_lens"], cfg.n_req, cfg.max_len, st)
+
+    def attended_bytes():
+        """K/V bytes one layer call reads at the lengths now on the device."""
+        lens_now = np.clip(set0["seq_lens"].cpu().numpy().astype(np.int64), 0, cfg.max_len)
+        if append:
+            lens_now = np.minimum(lens_now + 1, cfg.max_len)
+        return int(lens_now.sum()) * cfg.n_kvh * cfg.head_dim * 4
+
     # first call on the stream sizes the workspace (allocates); keep it out of everything timed
     call(sets[0], stream)
     stream.synchronize()
+
+    # ---- append variants: parity of set 0 now, while its lengths are the recipe's (the
+    # call above stored the new rows; storing them again changes nothing)
+    parity = None
+    host0 = None
+    if append and not args.no_cpu_baseline:
+        import oracle
+        k0, v0 = set0["k_host"].copy(), set0["v_host"].copy()
+        if args.paged:
+            pl = set0["layout"]
+            geom = (set0["block_size"], set0["max_blocks"], set0["n_blocks"],
+                    pl.stride_block, pl.stride_kvh, pl.stride_tok)
+            lens1 = oracle.kv_append_paged(kn0, vn0, k0, v0, set0["table_host"], batch0.seq_lens,
+                                           cfg.n_req, cfg.n_kvh, cfg.head_dim, *geom)
+            ref = oracle.decode_attn_paged(batch0.q, k0, v0, set0["table_host"], lens1, cfg.n_req,
+                                           cfg.n_qh, cfg.n_kvh, cfg.head_dim, *geom)
+        else:
+            lens1 = oracle.kv_append(kn0, vn0, k0, v0, batch0.seq_lens, cfg.n_req, cfg.n_kvh,
+                                     cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh,
+                                     lay.stride_tok)
+            ref = oracle.decode_attn(batch0.q, k0, v0, lens1, cfg.n_req, cfg.n_qh, cfg.n_kvh,
+                                     cfg.head_dim, cfg.max_len, lay.stride_req, lay.stride_kvh,
+                                     lay.stride_tok)
+        host0 = (k0, v0, lens1)
+        out = set0["out"].cpu().numpy().astype(np.float64)
+        diff = out - ref
+        den = np.sqrt((ref ** 2).sum(-1))
+        rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
+        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
 
     steps, warmup = args.steps, args.warmup
     mode = args.mode
@@ -195,6 +281,7 @@ def main():
             with torch.cuda.graph(graph, stream=stream):
                 for s in sets:
                     call(s, torch.cuda.current_stream())
+                end_of_model_step(torch.cuda.current_stream())
             torch.cuda.synchronize()
         except Exception as e:      # noqa: BLE001 -- report and fall back to eager launches
             print("bench.py: graph capture failed (%s); using eager launches" % e, file=sys.stderr)
@@ -213,15 +300,27 @@ def main():
             return
         for i in range(n):
             call(sets[i % n_sets], stream)
+            if i % n_sets == n_sets - 1:
+                end_of_model_step(stream)
 
     run_steps(warmup)
     torch.cuda.synchronize()
+    bytes_before = attended_bytes()
     t0 = time.perf_counter()
     run_steps(steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
-    bytes_done = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
+    if loop:
+        # every layer call of a model step reads the same lengths, which grow by one per
+        # model step: the mean of the first and the last step's bytes, times the calls
+        full_steps = steps // n_sets
+        bytes_last = attended_bytes() - (cfg.n_req * cfg.n_kvh * cfg.head_dim * 4 if full_steps else 0)
+        bytes_done = 0.5 * (bytes_before + bytes_last) * steps
+    elif append:
+        bytes_done = bytes_before / sets[0]["kv_bytes"] * sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
+    else:
+        bytes_done = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
     mean_bytes = bytes_done / steps
     gbps = bytes_done / elapsed / 1e9
     steps_per_s = steps / elapsed
@@ -232,23 +331,46 @@ def main():
     for i in range(prof_calls):
         call(sets[i % n_sets], stream)
     p_us, c_us, n_rec = sw.sw_prof_stop()
-    prof_bytes = sum(sets[i % n_sets]["kv_bytes"] for i in range(n_rec)) / max(n_rec, 1)
+    if loop:
+        prof_bytes = attended_bytes()
+    else:
+        prof_bytes = sum(sets[i % n_sets]["kv_bytes"] for i in range(n_rec)) / max(n_rec, 1)
+        if append:
+            prof_bytes *= bytes_before / sets[0]["kv_bytes"]
     partial_us = p_us / max(n_rec, 1)
     combine_us = c_us / max(n_rec, 1)
     achieved = prof_bytes / (partial_us * 1e-6) / 1e9 if partial_us > 0 else 0.0
 
     # ---- parity of set 0 and the CPU baseline (the oracle as it stands, on the host cores)
     cpu_baseline = None
-    parity = None
     if not args.no_cpu_baseline:
         import oracle
-        call(sets[0], stream)
-        stream.synchronize()
-        out = set0["out"].cpu().numpy().astype(np.float64)
+        if not append:
+            call(sets[0], stream)
+            stream.synchronize()
+            out = set0["out"].cpu().numpy().astype(np.float64)
         reps, t_cpu, ref, used = 0, 0.0, None, 0
         while t_cpu < 10.0 and reps < 500:
             c0 = time.perf_counter()
-            if args.paged:
+            if append:
+                # the oracle's step: store the rows (again: same rows, same place), then attend
+                k0, v0, _ = host0
+                if args.paged:
+                    lens1 = oracle.kv_append_paged(kn0, vn0, k0, v0, set0["table_host"],
+                                                   batch0.seq_lens, cfg.n_req, cfg.n_kvh,
+                                                   cfg.head_dim, *geom)
+                    oracle.decode_attn_paged(batch0.q, k0, v0, set0["table_host"], lens1, cfg.n_req,
+                                             cfg.n_qh, cfg.n_kvh, cfg.head_dim, *geom)
+                    used = oracle.max_threads()
+                else:
+                    lens1 = oracle.kv_append(kn0, vn0, k0, v0, batch0.seq_lens, cfg.n_req, cfg.n_kvh,
+                                             cfg.head_dim, cfg.max_len, lay.stride_req,
+                                             lay.stride_kvh, lay.stride_tok)
+                    _, _, _, used = oracle.decode_attn(
+                        batch0.q, k0, v0, lens1, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                        cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok,
+                        return_stats=True)
+            elif args.paged:
                 pl = set0["layout"]
                 ref = oracle.decode_attn_paged(
                     batch0.q, set0["k_host"], set0["v_host"], set0["table_host"], batch0.seq_lens,
@@ -267,10 +389,11 @@ def main():
                         "sample": "set 0 of %s (whole batch, %d K/V bytes), %d repetitions, %.1f s"
                                   % (cfg.name, batch0.kv_bytes, reps, t_cpu),
                         "decode_steps_per_s": reps / t_cpu}
-        diff = out - ref
-        den = np.sqrt((ref ** 2).sum(-1))
-        rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
-        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+        if not append:
+            diff = out - ref
+            den = np.sqrt((ref ** 2).sum(-1))
+            rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
+            parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
 
     line = {
         "metric": "achieved HBM GB/s on K/V reads (% of MI355X peak) + decode steps/sec",
@@ -293,11 +416,15 @@ def main():
                    "kv_bytes_per_step": mean_bytes, "cache_sets": n_sets, "launch": mode,
                    "kv_layout": ("block table, %d positions per block" % args.paged) if args.paged
                    else "dense, padded to max_len",
+                   "entry_point": ("sw_decode_attn" + ("_paged" if args.paged else "")
+                                   + ("_append" if append else "")),
+                   "decode_loop": ("%d layer caches, lengths advanced per model step" % n_sets)
+                   if loop else None,
                    "chunk": sw.sw_get_param(sw.SW_PARAM_CHUNK),
                    "kernel": sw.sw_get_param(sw.SW_PARAM_KERNEL)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None if args.paged else read_traffic(cfg.name),
+                     "traffic": None if (args.paged or append) else read_traffic(cfg.name),
                      "kernel": "partial (dominant)", "kernel_us": partial_us,
                      "combine_us": combine_us, "bytes_per_launch": prof_bytes,
                      "launches_timed": n_rec},
