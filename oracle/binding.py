@@ -61,6 +61,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+        lib.sw_oracle_prefill_attn.restype = ctypes.c_int
+        lib.sw_oracle_prefill_attn.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
         lib.sw_oracle_half_to_double.restype = ctypes.c_double
         lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
         lib.sw_oracle_max_threads.restype = ctypes.c_int
@@ -214,3 +220,34 @@ def kv_append_paged(k_new, v_new, k_pool, v_pool, block_table, seq_lens, n_req, 
     if rc < 0:
         raise ValueError("sw_oracle_kv_append_paged rejected its arguments (code %d)" % rc)
     return out
+
+
+def prefill_attn(q, k, v, seq_lens, q_starts, n_req, n_qh, n_kvh, head_dim, max_len,
+                 stride_req, stride_kvh, stride_tok, n_threads=0, return_threads=False):
+    """Causal (prompt-phase) attention.  q: [n_tokens, n_qh, head_dim]; request r's token i is row
+    q_starts[r] + i.  Returns ref float64 [n_tokens, n_qh, head_dim] (rows of no request are 0)."""
+    lib = _load()
+    q = _as_u16(q, "q")
+    k = _as_u16(k, "k")
+    v = _as_u16(v, "v")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    starts = np.ascontiguousarray(np.asarray(q_starts, dtype=np.int32))
+    if lens.size != n_req or starts.size != n_req:
+        raise ValueError("seq_lens / q_starts need n_req entries")
+    if q.size % (n_qh * head_dim):
+        raise ValueError("q is not a whole number of token rows")
+    n_tokens = q.size // (n_qh * head_dim)
+    need = 0
+    if n_req > 0:
+        need = ((n_req - 1) * stride_req + (n_kvh - 1) * stride_kvh
+                + (max_len - 1) * stride_tok + head_dim)
+    if k.size < need or v.size < need:
+        raise ValueError("k/v buffers are smaller than the strides address")
+    ref = np.zeros((n_tokens, n_qh, head_dim), dtype=np.float64)
+    rc = lib.sw_oracle_prefill_attn(q.ctypes.data, k.ctypes.data, v.ctypes.data, lens.ctypes.data,
+                                    starts.ctypes.data, ref.ctypes.data, n_req, n_qh, n_kvh,
+                                    head_dim, max_len, n_tokens, stride_req, stride_kvh, stride_tok,
+                                    int(n_threads))
+    if rc < 0:
+        raise ValueError("sw_oracle_prefill_attn rejected its arguments (code %d)" % rc)
+    return (ref, rc) if return_threads else ref

@@ -329,6 +329,80 @@ int sw_oracle_kv_append_paged(const uint16_t *k_new, const uint16_t *v_new,
     return 0;
 }
 
+/*
+ * Prompt phase (section 2.2: all tokens of the prompt are processed in parallel
+ * in one forward pass, which also produces the KV cache; section 3.5, Insight V:
+ * this phase is compute bound).  Its attention is the causal form of the same
+ * definition: prompt token i of request r sees cached positions 0..i, so row i is
+ * exactly the token-phase routine above run with length i + 1.  It is written
+ * that way: one attend_one per (request, head, token).
+ *   q         binary16 bits, [n_tokens][n_qh][head_dim]; token i of request r is
+ *             row q_starts[r] + i
+ *   q_starts  int32 [n_req]; rows q_starts[r] .. q_starts[r] + L_r - 1 must lie in
+ *             [0, n_tokens) (checked: a request that would leave it returns -5)
+ *   ref       double [n_tokens][n_qh][head_dim]; rows of no request are left as
+ *             they were
+ * Everything else as in sw_oracle_decode_attn.
+ * Pins: row i equals sw_oracle_decode_attn at length i + 1; brute force against a
+ * masked dense matrix formulation; rows do not depend on later positions
+ * (tests/test_oracle_pins.py).
+ */
+int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                           const int32_t *seq_lens, const int32_t *q_starts, double *ref,
+                           int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int64_t n_tokens,
+                           int64_t stride_req, int64_t stride_kvh, int64_t stride_tok,
+                           int n_threads)
+{
+    if (n_req < 0 || n_qh <= 0 || n_kvh <= 0 || head_dim <= 0 || max_len <= 0 || n_tokens < 0) return -1;
+    if (n_qh % n_kvh != 0) return -2;
+    if (n_req == 0) return 1;
+    if (!q || !k || !v || !seq_lens || !q_starts || !ref) return -3;
+    for (int r = 0; r < n_req; ++r) {
+        int L = clampi(seq_lens[r], 0, max_len);
+        if (L > 0 && (q_starts[r] < 0 || (int64_t)q_starts[r] + L > n_tokens)) return -5;
+    }
+    const int group = n_qh / n_kvh;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    used = n_threads;
+#else
+    (void)n_threads;
+#endif
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(n_threads)
+#endif
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)max_len);
+        if (!scores) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+        for (int r = 0; r < n_req; ++r) {
+            int L = clampi(seq_lens[r], 0, max_len);
+            for (int h = 0; h < n_qh; ++h) {
+                int g = h / group;
+                const uint16_t *kg = k + (int64_t)r * stride_req + (int64_t)g * stride_kvh;
+                const uint16_t *vg = v + (int64_t)r * stride_req + (int64_t)g * stride_kvh;
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 4) nowait
+#endif
+                for (int i = 0; i < L; ++i) {
+                    if (!scores) continue;
+                    int64_t row = ((int64_t)q_starts[r] + i) * n_qh + h;
+                    attend_one(q + row * head_dim, kg, vg, i + 1, head_dim, stride_tok, scores,
+                               ref + row * head_dim, NULL, NULL);
+                }
+            }
+        }
+        free(scores);
+    }
+    return failed ? -4 : used;
+}
+
 int sw_oracle_max_threads(void)
 {
 #ifdef _OPENMP

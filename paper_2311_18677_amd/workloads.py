@@ -142,6 +142,46 @@ def make_new_rows(cfg, seed, step=0):
     return k.astype(np.float16), v.astype(np.float16)
 
 
+# Prompt-phase batches (section 4.2: a prompt machine batches prompts up to 2048 tokens in
+# total; section 3.1: prompt medians 1500 tokens for coding, 1020 for conversation).
+PREFILL_CONFIGS = {
+    "prefill_tiny": Config("prefill_tiny", 3, 4, 2, 128, 160, ("fixed", (1, 37, 160)),
+                           n_layers=1, seed_index=11),
+    # Llama-2-70B share: one coding-median prompt plus a short one, 2048 tokens in all
+    "prefill_llama70b_tp8": Config("prefill_llama70b_tp8", 2, 8, 1, 128, 2048,
+                                   ("fixed", (1500, 548)), n_layers=80, seed_index=12),
+    # BLOOM-176B share: two conversation-median prompts
+    "prefill_bloom176b_tp8": Config("prefill_bloom176b_tp8", 2, 14, 14, 128, 2048,
+                                    ("fixed", (1020, 1020)), n_layers=70, seed_index=13),
+    # one long prompt, where the quadratic term dominates
+    "prefill_long_8k": Config("prefill_long_8k", 1, 8, 1, 128, 8192, ("fixed", (8192,)),
+                              n_layers=80, seed_index=14),
+}
+
+
+def make_prefill_queries(batch, seed=None):
+    """Queries of every prompt token of a Batch, packed request after request.
+
+    Returns (q_tokens float16 [n_tokens, n_qh, head_dim], q_starts int32 [n_req]): token i of
+    request r is row q_starts[r] + i; n_tokens is the sum of the valid lengths.
+    """
+    cfg = batch.cfg
+    lens = batch.valid_lens.astype(np.int64)
+    starts = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int32)
+    n_tokens = int(lens.sum())
+    ss = np.random.SeedSequence([int(batch.seed if seed is None else seed), 0x70726F6D])
+    rng = np.random.Generator(np.random.Philox(ss))
+    q = rng.standard_normal((n_tokens, cfg.n_qh, cfg.head_dim), dtype=np.float32).astype(np.float16)
+    return q, starts
+
+
+def prefill_flops(cfg, lens):
+    """Algorithmic flops of causal attention: 4*head_dim per (query, visible key) pair and head."""
+    lens = np.clip(np.asarray(lens, dtype=np.int64), 0, cfg.max_len)
+    pairs = int((lens * (lens + 1) // 2).sum())
+    return 4 * cfg.head_dim * pairs * cfg.n_qh
+
+
 def custom_config(name, n_req, n_qh, n_kvh, head_dim, max_len, n_layers=1):
     """A free-form shape for edge-case tests; pass seq_lens to make_batch."""
     return Config(name, n_req, n_qh, n_kvh, head_dim, max_len, ("fixed", (0,) * n_req),

@@ -404,3 +404,68 @@ def test_paged_kv_append_equals_dense_kv_append(block_size):
     paged = oracle.decode_attn_paged(b.q, kp, vp, table, lens_p, 5, 4, 2, 64, block_size, mb, n_blocks,
                                      sb, sgp, stp)
     assert np.array_equal(paged, dense) and np.all(np.isfinite(paged))
+
+
+# ---- prompt phase (causal) ----
+
+def _prefill_case(n_qh, n_kvh, d, max_len, lens, seed):
+    cfg = wl.custom_config("pf", len(lens), n_qh, n_kvh, d, max_len)
+    b = wl.make_batch(cfg, seed=seed, seq_lens=lens)
+    qt, starts = wl.make_prefill_queries(b)
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    k = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0x7E00)
+    v = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0x7E00)
+    ref = oracle.prefill_attn(qt, k, v, b.seq_lens, starts, cfg.n_req, n_qh, n_kvh, d, max_len, sr, sg, st)
+    return cfg, b, qt, starts, k, v, (sr, sg, st), ref
+
+
+def test_prefill_row_i_is_the_decode_step_at_length_i_plus_1():
+    cfg, b, qt, starts, k, v, (sr, sg, st), ref = _prefill_case(4, 2, 64, 24, [24, 1, 0, 9], 96)
+    assert ref.shape == (34, 4, 64)
+    for r, L in enumerate([24, 1, 0, 9]):
+        for i in range(L):
+            q1 = np.zeros((cfg.n_req, 4, 64), np.float16)
+            q1[r] = qt[starts[r] + i]
+            lens1 = np.zeros(cfg.n_req, np.int32)
+            lens1[r] = i + 1
+            dec = oracle.decode_attn(q1, k, v, lens1, cfg.n_req, 4, 2, 64, 24, sr, sg, st)
+            assert np.array_equal(ref[starts[r] + i], dec[r])
+    # the first token of a prompt sees itself only: its row is V[0] exactly
+    g = np.repeat(np.arange(2), 2)
+    assert np.array_equal(ref[starts[0]], b.v_rows[0][g, 0, :].astype(np.float64))
+
+
+def test_prefill_matches_masked_matrix_formulation():
+    cfg, b, qt, starts, k, v, _, ref = _prefill_case(6, 3, 64, 40, [40, 17, 3], 97)
+    for r, L in enumerate([40, 17, 3]):
+        for h in range(6):
+            g = h // 2
+            q = qt[starts[r]:starts[r] + L, h].astype(np.float64)
+            kk = b.k_rows[r][g].astype(np.float64)
+            vv = b.v_rows[r][g].astype(np.float64)
+            s = q @ kk.T / np.sqrt(64.0)
+            s[np.triu_indices(L, 1)] = -np.inf          # token i does not see positions > i
+            want = scipy.special.softmax(s, axis=1) @ vv
+            assert np.allclose(ref[starts[r]:starts[r] + L, h], want, rtol=1e-12, atol=1e-14)
+
+
+def test_prefill_rows_do_not_depend_on_later_positions_or_other_requests():
+    cfg, b, qt, starts, k, v, (sr, sg, st), ref = _prefill_case(4, 4, 64, 32, [32, 20], 98)
+    # scramble every cached position >= 12 of request 0: rows 0..11 keep their bits
+    k2, v2 = k.copy(), v.copy()
+    kv = np.lib.stride_tricks.as_strided(k2, shape=(2, 4, 32, 64), strides=(2 * sr, 2 * sg, 2 * st, 2))
+    vv = np.lib.stride_tricks.as_strided(v2, shape=(2, 4, 32, 64), strides=(2 * sr, 2 * sg, 2 * st, 2))
+    kv[0, :, 12:, :] = 0x7E00
+    vv[0, :, 12:, :] = 0x7E00
+    ref2 = oracle.prefill_attn(qt, k2, v2, b.seq_lens, starts, 2, 4, 4, 64, 32, sr, sg, st)
+    assert np.array_equal(ref2[:12], ref[:12]) and np.array_equal(ref2[32:], ref[32:])
+    assert not np.all(np.isfinite(ref2[12:32]))
+    # unpacked query rows (a gap between the requests, reversed order) give the same rows
+    qt3 = np.zeros((70, 4, 64), np.float16)
+    qt3[40:60] = qt[32:52]
+    qt3[3:35] = qt[0:32]
+    ref3 = oracle.prefill_attn(qt3, k, v, b.seq_lens, [3, 40], 2, 4, 4, 64, 32, sr, sg, st)
+    assert np.array_equal(ref3[3:35], ref[0:32]) and np.array_equal(ref3[40:60], ref[32:52])
+    assert not ref3[:3].any() and not ref3[35:40].any() and not ref3[60:].any()
+    with pytest.raises(ValueError):
+        oracle.prefill_attn(qt, k, v, b.seq_lens, [0, 40], 2, 4, 4, 64, 32, sr, sg, st)
