@@ -222,6 +222,32 @@ int sw_decode_attn_paged_append(const void *q, const void *k_new, const void *v_
 int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream);
 
 /*
+ * sw_prefill_attn -- the prompt phase's attention (section 2.2: all tokens of a
+ * prompt are processed in one pass, which produces the KV cache; section 3.5,
+ * Insight V: this phase is compute bound).  Prompt token i of request r attends
+ * to cached positions 0..i of that request:
+ *     out[s_r + i, h, :] = softmax_{t <= i}( q[s_r + i, h, :] . K[r, g, t, :] / sqrt(head_dim) ) . V[r, g, 0..i, :]
+ * for i < L_r = clamp(seq_lens[r], 0, max_len), s_r = q_starts[r], g = h / (n_qh / n_kvh).
+ *   q, out     DEVICE, binary16, [n_tokens][n_qh][head_dim]; 16-byte aligned.  Rows of
+ *              `out` that belong to no prompt token are not written.
+ *   k_cache, v_cache   as in sw_decode_attn: the prompt's K/V rows are already in place
+ *              (positions 0 .. L_r - 1); read only.
+ *   seq_lens   DEVICE int32 [n_req]: prompt lengths, clamped to [0, max_len].
+ *   q_starts   DEVICE int32 [n_req]: row of each request's first prompt token.  Rows
+ *              s_r .. s_r + L_r - 1 must lie in [0, n_tokens) and the requests' row
+ *              ranges must not overlap; row indices outside [0, n_tokens) are never
+ *              dereferenced (such rows are skipped).
+ *   n_tokens   rows of q and out (0 returns SW_OK without touching the device).
+ *   head_dim must be 128 and n_qh / n_kvh at most 8 (SW_ERR_UNSUPPORTED otherwise).
+ * One kernel, no workspace; asynchrony, ownership and the other errors as in
+ * sw_decode_attn.  Weights enter the second matrix product as binary16 and the
+ * normaliser sums those same rounded weights.
+ */
+int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,
+                    int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream);
+
+/*
  * sw_last_error -- text of the calling thread's most recent failure
  * (a static or thread-local string; never NULL; valid until the thread's next
  * failing call).  Support call, not part of the step.

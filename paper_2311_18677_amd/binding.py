@@ -28,6 +28,7 @@ SW_PARAM_WAVES = 4
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
+           "sw_prefill_attn",
            "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
 
@@ -88,6 +89,8 @@ def load():
                                                 ci, ci, ci, ci, ci, ci, ci, vp]
     lib.sw_advance_lens.restype = ci
     lib.sw_advance_lens.argtypes = [vp, ci, ci, vp]
+    lib.sw_prefill_attn.restype = ci
+    lib.sw_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_longlong, ci, ci, ci, ci, ci, vp]
     lib.sw_last_error.restype = ctypes.c_char_p
     lib.sw_last_error.argtypes = []
     lib.sw_version.restype = ci
@@ -197,6 +200,15 @@ def sw_decode_attn_paged_append(q, k_new, v_new, k_pool, v_pool, block_table, se
 def sw_advance_lens(seq_lens, n_req, max_len, stream=None, check=True):
     """End of a model step: every length grows by one, saturating at max_len (on the device)."""
     rc = load().sw_advance_lens(_ptr(seq_lens), n_req, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_prefill_attn(q, k_cache, v_cache, seq_lens, q_starts, out, n_tokens, n_req, n_qh, n_kvh,
+                    head_dim, max_len, stream=None, check=True):
+    """Prompt-phase (causal) attention of every prompt token over its request's cache."""
+    rc = load().sw_prefill_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens),
+                                _ptr(q_starts), _ptr(out), int(n_tokens), n_req, n_qh, n_kvh,
+                                head_dim, max_len, _stream(stream))
     return _check(rc) if check else rc
 
 

@@ -460,6 +460,81 @@ int sw_decode_attn_append(const void *q, const void *k_new, const void *v_new,
                         n_req, n_qh, n_kvh, head_dim, max_len, stream);
 }
 
+int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,
+                    int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream_v)
+{
+    // ---- validation, before any HIP call ----
+    if (n_qh <= 0) return fail(SW_ERR_SHAPE, "n_qh must be > 0");
+    if (n_kvh <= 0 || n_qh % n_kvh != 0)
+        return fail(SW_ERR_SHAPE, "n_kvh must be > 0 and divide n_qh");
+    int rc = check_shape(n_req, n_kvh, head_dim, max_len);
+    if (rc != SW_OK) return rc;
+    if (n_tokens < 0 || n_tokens > (1LL << 31)) return fail(SW_ERR_SHAPE, "n_tokens must be in [0, 2^31]");
+    if (head_dim != 128 || n_qh / n_kvh > 8)
+        return fail(SW_ERR_UNSUPPORTED, "the prompt-phase kernel needs head_dim 128 and at most 8 query heads per key/value head");
+    if (n_req == 0 || n_tokens == 0) return SW_OK;
+    if (!q || !k_cache || !v_cache || !seq_lens || !q_starts || !out)
+        return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens, q_starts and out must be non-NULL");
+    if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u)
+        return fail(SW_ERR_ALIGN, "q, k_cache, v_cache and out must be 16-byte aligned");
+    if (((uintptr_t)seq_lens | (uintptr_t)q_starts) & 3u)
+        return fail(SW_ERR_ALIGN, "seq_lens and q_starts must be 4-byte aligned");
+
+    SwPrefillArgs a;
+    a.q = (const uint16_t *)q;
+    a.k = (const uint16_t *)k_cache;
+    a.v = (const uint16_t *)v_cache;
+    a.seq_lens = seq_lens;
+    a.q_starts = q_starts;
+    a.out = (uint16_t *)out;
+    a.n_tokens = n_tokens;
+    a.n_req = n_req;
+    a.n_qh = n_qh;
+    a.n_kvh = n_kvh;
+    a.group = n_qh / n_kvh;
+    a.head_dim = head_dim;
+    a.max_len = max_len;
+    a.qw = sw_prefill_waves_per_head(a.group);
+    a.n_qblocks = (max_len + 32 * a.qw - 1) / (32 * a.qw);
+    a.stride_kvh = slab_elems(head_dim, max_len);
+    a.stride_req = a.stride_kvh * n_kvh;
+    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
+    if ((long long)n_req * n_kvh * a.n_qblocks > 0x7fffffffLL)
+        return fail(SW_ERR_SHAPE, "too many workgroups");
+
+    bool prof;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
+    }
+    SwLaunchEvents ev = {nullptr, nullptr};
+    ProfRec rec;
+    rec.has_combine = false;
+    hipError_t e;
+    if (prof) {
+        for (int i = 0; i < 4; ++i) {
+            e = hipEventCreate(&rec.ev[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
+                return fail_hip(e, "hipEventCreate");
+            }
+        }
+        ev = {rec.ev[0], rec.ev[1]};
+    }
+    e = sw_launch_prefill_mfma(a, (hipStream_t)stream_v, prof ? &ev : nullptr);
+    if (e != hipSuccess) {
+        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        return fail_hip(e, "kernel launch");
+    }
+    if (prof) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
+        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+    }
+    return SW_OK;
+}
+
 int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream)
 {
     if (n_req < 0 || max_len <= 0) return fail(SW_ERR_SHAPE, "n_req must be >= 0 and max_len > 0");

@@ -42,6 +42,23 @@ struct SwArgs {
     float scale_log2e;                 // log2(e) / sqrt(head_dim)
 };
 
+// Arguments of the prompt-phase (causal) kernel.
+struct SwPrefillArgs {
+    const uint16_t *q;                  // [n_tokens][n_qh][head_dim]
+    const uint16_t *k;                  // caches in the dense layout
+    const uint16_t *v;
+    const int32_t  *seq_lens;           // prompt lengths
+    const int32_t  *q_starts;           // row of each request's first prompt token
+    uint16_t       *out;                // [n_tokens][n_qh][head_dim]
+    long long n_tokens;
+    int   n_req, n_qh, n_kvh, group;
+    int   head_dim, max_len;
+    int   qw;                           // waves per query head in a workgroup
+    int   n_qblocks;                    // query blocks (of 32 * qw positions) that cover max_len
+    long long stride_req, stride_kvh;   // in elements
+    float scale_log2e;
+};
+
 // Number of cached positions request r attends over, with a flag.  seq_lens[r]
 // is clamped to [0, max_len]; in the append variant it counts the positions
 // cached BEFORE the newest token, whose K/V rows this call stores at that
@@ -86,6 +103,9 @@ bool       sw_partial_mfma2_supported(const SwArgs &a);
 hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 // Merge of the chunks' partial results, normalisation and rounding to binary16.
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
+int        sw_prefill_waves_per_head(int group);
+hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 hipError_t sw_launch_advance_lens(int32_t *seq_lens, int n_req, int max_len, hipStream_t stream);
 
 // Granularity the chunk length must be a multiple of (all kernels).

@@ -175,3 +175,22 @@ def test_append_validation():
     assert sw.sw_advance_lens(0x1000, -1, 128, check=False) == sw.SW_ERR_SHAPE
     assert sw.sw_advance_lens(0x1000, 4, 0, check=False) == sw.SW_ERR_SHAPE
     assert sw.sw_advance_lens(0x1000, 0, 128, check=False) == sw.SW_OK
+
+
+def test_prefill_validation():
+    def pcall(q=0x1000, k=0x2000, v=0x3000, lens=0x4000, starts=0x5000, out=0x6000, n_tokens=100,
+              n_req=2, n_qh=8, n_kvh=1, d=128, max_len=256):
+        return sw.sw_prefill_attn(q, k, v, lens, starts, out, n_tokens, n_req, n_qh, n_kvh, d, max_len,
+                                  None, check=False)
+    # every call fails validation (or is empty), so none reaches a HIP call
+    assert pcall(starts=None) == sw.SW_ERR_NULL
+    assert pcall(q=None) == sw.SW_ERR_NULL
+    assert pcall(starts=0x5002) == sw.SW_ERR_ALIGN
+    assert pcall(out=0x6008) == sw.SW_ERR_ALIGN
+    assert pcall(d=64) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(n_qh=16) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(n_qh=8, n_kvh=3) == sw.SW_ERR_SHAPE
+    assert pcall(n_tokens=-1) == sw.SW_ERR_SHAPE
+    assert pcall(max_len=0) == sw.SW_ERR_SHAPE
+    assert pcall(n_tokens=0) == sw.SW_OK
+    assert pcall(n_req=0) == sw.SW_OK
