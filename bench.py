@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--decode-loop", action="store_true",
                     help="whole model steps: the workload's layer count of per-layer caches, one "
                          "append-then-attend call each, lengths advanced on the device per step")
+    ap.add_argument("--prefill", action="store_true",
+                    help="time the prompt-phase (causal) attention instead; workloads prefill_*")
+    ap.add_argument("--prefill-heads", type=int, default=0)
+    ap.add_argument("--prefill-waves", type=int, default=0)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch plain device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings); 0 = none")
@@ -144,12 +148,142 @@ def read_traffic(workload):
     return None
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
+
+
+def main_prefill(args):
+    """Prompt-phase attention: a step is one sw_prefill_attn call (one layer, one prompt batch)."""
+    import numpy as np
+    import torch
+    from paper_2311_18677_amd import binding as sw
+    from paper_2311_18677_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    sw.load()
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_HEADS, args.prefill_heads)
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, args.prefill_waves)
+    name = args.workload if args.workload.startswith("prefill_") else "prefill_llama70b_tp8"
+    cfg = wl.PREFILL_CONFIGS[name]
+    batch0 = wl.make_batch(cfg)
+    qt0, starts0 = wl.make_prefill_queries(batch0)
+    n_tokens = qt0.shape[0]
+    flops = wl.prefill_flops(cfg, batch0.seq_lens)
+    n_sets = args.sets or 4
+    sets = []
+    for i in range(n_sets):
+        b = batch0 if i == 0 else wl.make_batch(cfg, seed=batch0.seed + 100 + i)
+        qt = qt0 if i == 0 else wl.make_prefill_queries(b)[0]
+        bufs = sw.upload_batch(b, device="cuda:0", pad_bits=0)
+        bufs["qt"] = torch.from_numpy(qt.view(np.int16).reshape(-1)).to(dev).view(torch.float16)
+        bufs["starts"] = torch.from_numpy(starts0).to(dev)
+        bufs["pout"] = torch.zeros((n_tokens, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
+        if i:
+            bufs.pop("k_host"), bufs.pop("v_host")
+        sets.append(bufs)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_prefill_attn(s["qt"], s["k_cache"], s["v_cache"], s["seq_lens"], s["starts"], s["pout"],
+                           n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
+
+    call(sets[0], stream)
+    stream.synchronize()
+    steps, warmup = args.steps, args.warmup
+    graph = None
+    mode = args.mode
+    if mode == "graph":
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for s in sets:
+                    call(s, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+        except Exception as e:      # noqa: BLE001
+            print("bench.py: graph capture failed (%s); using eager launches" % e, file=sys.stderr)
+            graph, mode = None, "eager"
+
+    def run_steps(n):
+        if graph is not None:
+            full, rem = divmod(n, n_sets)
+            with torch.cuda.stream(stream):
+                for _ in range(full):
+                    graph.replay()
+            for i in range(rem):
+                call(sets[i], stream)
+            return
+        for i in range(n):
+            call(sets[i % n_sets], stream)
+
+    run_steps(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    prof_calls = min(steps, 200)
+    sw.sw_prof_start(prof_calls)
+    for i in range(prof_calls):
+        call(sets[i % n_sets], stream)
+    k_us_sum, _, n_rec = sw.sw_prof_stop()
+    kernel_us = k_us_sum / max(n_rec, 1)
+    achieved = flops / (kernel_us * 1e-6) / 1e12 if kernel_us > 0 else 0.0
+
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        lay = sets[0]["layout"]
+        c0 = time.perf_counter()
+        ref, used = oracle.prefill_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
+                                        starts0, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                                        cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok,
+                                        return_threads=True)
+        t_cpu = time.perf_counter() - c0
+        cpu_baseline = {"value": flops / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(used),
+                        "kind": "oracle",
+                        "sample": "set 0 of %s, the whole prompt batch once, %.1f s" % (cfg.name, t_cpu)}
+        call(sets[0], stream)
+        stream.synchronize()
+        out = sets[0]["pout"].cpu().numpy().astype(np.float64)
+        diff = out - ref
+        den = np.sqrt((ref ** 2).sum(-1))
+        rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
+        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+
+    tflops = flops * steps / elapsed / 1e12
+    line = {
+        "metric": "prompt-phase attention TFLOP/s (causal pairs only; % of MI355X fp16 matrix peak)",
+        "value": tflops, "unit": "TFLOP/s", "pct_of_peak": 100.0 * tflops / MFMA_F16_PEAK_TFLOPS,
+        "prompt_tokens_per_s_attention_only": n_tokens * steps / elapsed / cfg.n_layers,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * elapsed / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_qh": cfg.n_qh, "n_kvh": cfg.n_kvh,
+                   "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
+                   "prompt_tokens": n_tokens, "flops_per_step": flops, "cache_sets": n_sets,
+                   "launch": mode, "entry_point": "sw_prefill_attn"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "sw_prefill_mfma_kernel", "kernel_us": kernel_us,
+                     "flops_per_launch": flops, "launches_timed": n_rec},
+        "cpu_baseline": cpu_baseline,
+        "parity_set0": parity,
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.prefill:
+        return main_prefill(args)
 
     import numpy as np
     import torch

@@ -282,11 +282,19 @@ int sw_release(void);
  *                      Each is deterministic; the two differ by rounding only.
  *   SW_PARAM_WAVES     waves per workgroup of the matrix-core partial kernel:
  *                      0 = library default, else 4, 8 or 16.
+ *   SW_PARAM_PREFILL_HEADS  prompt-phase kernel: query heads of a group that share a
+ *                      workgroup (0 = library default; a value that does not divide
+ *                      the group size is ignored).
+ *   SW_PARAM_PREFILL_WAVES  prompt-phase kernel: waves (32 query positions each) per
+ *                      head in a workgroup (0 = library default; ignored if heads *
+ *                      waves would exceed 8).
  */
 #define SW_PARAM_CHUNK   1
 #define SW_PARAM_KERNEL  2
 #define SW_PARAM_COMBINE 3
 #define SW_PARAM_WAVES   4
+#define SW_PARAM_PREFILL_HEADS 5
+#define SW_PARAM_PREFILL_WAVES 6
 int sw_set_param(int key, int value);
 int sw_get_param(int key, int *value);
 

@@ -47,6 +47,8 @@ int g_chunk = 0;
 int g_kernel = 0;
 int g_combine = 0;
 int g_waves = 0;
+int g_prefill_hp = 0;   // prompt-phase kernel: query heads per workgroup
+int g_prefill_qw = 0;   //                      waves per query head
 
 // per-kernel timing
 struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
@@ -329,6 +331,14 @@ int sw_set_param(int key, int value)
             return fail(SW_ERR_PARAM, "waves must be 0, 4, 8 or 16");
         g_waves = value;
         return SW_OK;
+    case SW_PARAM_PREFILL_HEADS:
+        if (value < 0 || value > 8) return fail(SW_ERR_PARAM, "prefill heads must be in [0, 8]");
+        g_prefill_hp = value;
+        return SW_OK;
+    case SW_PARAM_PREFILL_WAVES:
+        if (value < 0 || value > 8) return fail(SW_ERR_PARAM, "prefill waves per head must be in [0, 8]");
+        g_prefill_qw = value;
+        return SW_OK;
     default:
         return fail(SW_ERR_PARAM, "unknown parameter key");
     }
@@ -343,6 +353,8 @@ int sw_get_param(int key, int *value)
     case SW_PARAM_KERNEL: *value = g_kernel; return SW_OK;
     case SW_PARAM_COMBINE: *value = g_combine; return SW_OK;
     case SW_PARAM_WAVES: *value = g_waves; return SW_OK;
+    case SW_PARAM_PREFILL_HEADS: *value = g_prefill_hp; return SW_OK;
+    case SW_PARAM_PREFILL_WAVES: *value = g_prefill_qw; return SW_OK;
     default: return fail(SW_ERR_PARAM, "unknown parameter key");
     }
 }
@@ -495,12 +507,14 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     a.group = n_qh / n_kvh;
     a.head_dim = head_dim;
     a.max_len = max_len;
-    a.qw = sw_prefill_waves_per_head(a.group);
+    sw_prefill_shape(n_req, n_kvh, a.group, max_len, &a.hp, &a.qw);
+    if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) a.hp = g_prefill_hp;
+    if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
     a.n_qblocks = (max_len + 32 * a.qw - 1) / (32 * a.qw);
     a.stride_kvh = slab_elems(head_dim, max_len);
     a.stride_req = a.stride_kvh * n_kvh;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
-    if ((long long)n_req * n_kvh * a.n_qblocks > 0x7fffffffLL)
+    if ((long long)n_req * n_qh * a.n_qblocks > 0x7fffffffLL)
         return fail(SW_ERR_SHAPE, "too many workgroups");
 
     bool prof;

@@ -53,6 +53,7 @@ struct SwPrefillArgs {
     long long n_tokens;
     int   n_req, n_qh, n_kvh, group;
     int   head_dim, max_len;
+    int   hp;                           // query heads (of one group) per workgroup
     int   qw;                           // waves per query head in a workgroup
     int   n_qblocks;                    // query blocks (of 32 * qw positions) that cover max_len
     long long stride_req, stride_kvh;   // in elements
@@ -104,7 +105,7 @@ hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const Sw
 // Merge of the chunks' partial results, normalisation and rounding to binary16.
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
-int        sw_prefill_waves_per_head(int group);
+void       sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw);
 hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 hipError_t sw_launch_advance_lens(int32_t *seq_lens, int n_req, int max_len, hipStream_t stream);
 

@@ -40,7 +40,36 @@ union Frag {
     half8_t h;
 };
 
-// NW = waves per workgroup = group * waves-per-head.
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// Lanes n16, n16+16, n16+32, n16+48 hold parts of one query's row.  Two swap
+// instructions give every one of them the maximum (or the sum) over the four:
+// the first exchanges odd rows of 16 lanes with even ones, the second the upper
+// 32 lanes with the lower.
+__device__ __forceinline__ float quad_rows_max(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+__device__ __forceinline__ float quad_rows_sum(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// The running maximum of a query is only raised when a score exceeds it by more than
+// this many binary orders of magnitude: weights then stay below 2^kLazyBits (exact
+// enough in binary16, whose precision is relative) and the accumulators are rescaled
+// rarely instead of every tile.
+constexpr float kLazyBits = 8.0f;
+
+// NW = waves per workgroup = (query heads per workgroup) * (waves per head).
 template <int NW>
 __global__ __launch_bounds__(64 * NW, 1)
 void sw_prefill_mfma_kernel(SwPrefillArgs a)
@@ -50,10 +79,14 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     constexpr int C = (16 + NW - 1) / NW;
     __shared__ __attribute__((aligned(16))) unsigned char lds[kBufs * kBufBytes];
 
+    // blockIdx -> (query block, request, key/value head, block of hp query heads)
+    const unsigned n_hb = (unsigned)(a.group / a.hp);
+    const unsigned hb = blockIdx.x % n_hb;
+    const unsigned rest = blockIdx.x / n_hb;
     const unsigned n_units = (unsigned)a.n_req * (unsigned)a.n_kvh;
-    const unsigned unit = blockIdx.x % n_units;
+    const unsigned unit = rest % n_units;
     // late query blocks see the most positions: they come first in dispatch order
-    const int qb = a.n_qblocks - 1 - (int)(blockIdx.x / n_units);
+    const int qb = a.n_qblocks - 1 - (int)(rest / n_units);
     const int r = (int)(unit / (unsigned)a.n_kvh);
     const int g = (int)(unit - (unsigned)r * (unsigned)a.n_kvh);
     int L = a.seq_lens[r];
@@ -67,8 +100,8 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n16  = lane & 15;
     const int gq   = lane >> 4;
-    const int hh   = wave % a.group;             // query head within the group
-    const int sb   = wave / a.group;             // which 32 query positions of the block
+    const int hh   = (int)hb * a.hp + wave % a.hp;   // query head within the group
+    const int sb   = wave / a.hp;                // which 32 query positions of the block
     const int qw0  = Q0 + kQPerWave * sb;
     const int h    = g * a.group + hh;
 
@@ -107,6 +140,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     };
 
     float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
+    const float lazy_raw = kLazyBits / a.scale_log2e;      // the threshold in raw score units
     float4_t o[2][8];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -175,7 +209,8 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
             vreg[n] = *reinterpret_cast<const uint4_t *>(vb + row * kRowBytes + n16 * 16);
         }
 
-        // ---- online softmax, base 2; this lane: query qw0 + 16nb + n16, positions t0 + 16tb + 4gq + i
+        // ---- online softmax, base 2; this lane: query qw0 + 16nb + n16, positions t0 + 16tb + 4gq + i.
+        // m[] is kept in raw score units; the scale enters through one fused multiply-add.
         const bool diagonal = t0 + kTile > qw0;      // some position of the tile is later than some query
         Frag p[2];
 #pragma unroll
@@ -184,7 +219,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) s[4 * tb + i] = sacc[nb][tb][i] * a.scale_log2e;
+                for (int i = 0; i < 4; ++i) s[4 * tb + i] = sacc[nb][tb][i];
             if (diagonal) {
                 const int qpos = qw0 + 16 * nb + n16;
 #pragma unroll
@@ -193,26 +228,33 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
                     for (int i = 0; i < 4; ++i)
                         if (t0 + 16 * tb + 4 * gq + i > qpos) s[4 * tb + i] = -INFINITY;
             }
-            float mt = s[0];
+            float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
+                             fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+            mt = quad_rows_max(mt);
+            const bool raise = mt > m[nb] + lazy_raw;
+            if (__builtin_amdgcn_ballot_w64(raise) != 0) {       // rare after the first tiles
+                const float m_new = raise ? mt : m[nb];
+                const float alpha = __builtin_amdgcn_exp2f((m[nb] - m_new) * a.scale_log2e);
+                m[nb] = m_new;
+                l[nb] *= alpha;
 #pragma unroll
-            for (int j = 1; j < 8; ++j) mt = fmaxf(mt, s[j]);
-            mt = fmaxf(mt, __shfl_xor(mt, 16));
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float m_new = fmaxf(m[nb], mt);
-            const float alpha = __builtin_amdgcn_exp2f(m[nb] - m_new);
-            m[nb] = m_new;
+                for (int e = 0; e < 8; ++e) o[nb][e] *= alpha;
+            }
+            const float neg_m = -m[nb] * a.scale_log2e;
+            float pj[8];
             float psum = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float pj = __builtin_amdgcn_exp2f(s[j] - m_new);
-                // the sum runs over the weights as the matrix product sees them
-                const _Float16 ph = (_Float16)pj;
-                p[nb].h[j] = ph;
-                psum += (float)ph;
+                pj[j] = __builtin_amdgcn_exp2f(fmaf(s[j], a.scale_log2e, neg_m));
+                psum += pj[j];
             }
-            l[nb] = l[nb] * alpha + psum;
+            l[nb] += psum;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[nb][e] *= alpha;
+            for (int j = 0; j < 4; ++j) {
+                const half2_t h2 = __builtin_convertvector((float2_t){pj[2 * j], pj[2 * j + 1]}, half2_t);
+                p[nb].h[2 * j] = h2[0];
+                p[nb].h[2 * j + 1] = h2[1];
+            }
         }
 
         // ---- O^T += V^T P^T : block e covers dims 8*row + e (row = MFMA row)
@@ -233,9 +275,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     // ---- this lane's query rows: dims 32gq + 8i + e
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-        float ls = l[nb];
-        ls += __shfl_xor(ls, 16);
-        ls += __shfl_xor(ls, 32);
+        const float ls = quad_rows_sum(l[nb]);
         const int qpos = qw0 + 16 * nb + n16;
         const long long row = q_first + qpos;
         if (qpos < L && row >= 0 && row < a.n_tokens) {
@@ -259,22 +299,34 @@ bool sw_prefill_mfma_supported(const SwPrefillArgs &a)
     return a.head_dim == kD && a.group >= 1 && a.group <= 8;
 }
 
-// Waves per head: enough to bring a workgroup to 8 waves.
-int sw_prefill_waves_per_head(int group)
+// How a workgroup is shaped: hp query heads of one group, qw waves (32 query positions
+// each) per head.  Large problems share each staged K/V tile among all heads of the group
+// (8 waves); small ones are cut into more, smaller workgroups so that the chip fills.
+void sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw)
 {
-    return group >= 8 ? 1 : 8 / group;
+    int h = group, w = group >= 8 ? 1 : 8 / group;
+    auto groups = [&](int hh, int ww) {
+        return (long long)n_req * n_kvh * (group / hh) * ((max_len + 32 * ww - 1) / (32 * ww));
+    };
+    // first fewer positions per workgroup, then fewer heads
+    while (w > 1 && groups(h, w) < 512) w /= 2;
+    while (h > 1 && h % 2 == 0 && groups(h, w) < 512) h /= 2;
+    *hp = h;
+    *qw = w;
 }
 
 hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
 {
     if (!sw_prefill_mfma_supported(a)) return hipErrorNotSupported;
-    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_qblocks;
+    if (a.hp < 1 || a.group % a.hp != 0 || a.qw < 1) return hipErrorInvalidValue;
+    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_qblocks * (a.group / a.hp);
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks);
-    const int nw = a.group * a.qw;
+    const int nw = a.hp * a.qw;
 #define SW_PREFILL_CASE(W) \
     if (nw == W) return sw_launch(sw_prefill_mfma_kernel<W>, grid, dim3(64 * W), 0, stream, ev, a);
     SW_PREFILL_CASE(8) SW_PREFILL_CASE(7) SW_PREFILL_CASE(6) SW_PREFILL_CASE(5)
+    SW_PREFILL_CASE(4) SW_PREFILL_CASE(3) SW_PREFILL_CASE(2) SW_PREFILL_CASE(1)
 #undef SW_PREFILL_CASE
     return hipErrorInvalidValue;
 }
