@@ -67,6 +67,17 @@ def _load():
             ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+        lib.sw_oracle_kv_pack.restype = ctypes.c_int
+        lib.sw_oracle_kv_pack.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_int,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+        lib.sw_oracle_kv_span_plan.restype = ctypes.c_int
+        lib.sw_oracle_kv_span_plan.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.sw_oracle_half_to_double.restype = ctypes.c_double
         lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
         lib.sw_oracle_max_threads.restype = ctypes.c_int
@@ -251,3 +262,52 @@ def prefill_attn(q, k, v, seq_lens, q_starts, n_req, n_qh, n_kvh, head_dim, max_
     if rc < 0:
         raise ValueError("sw_oracle_prefill_attn rejected its arguments (code %d)" % rc)
     return (ref, rc) if return_threads else ref
+
+
+def kv_pack(k_pool, v_pool, block_table, seq_lens, k_dense, v_dense, to_dense, n_req, n_kvh,
+            head_dim, max_len, block_size, max_blocks, n_blocks, stride_block, p_stride_kvh,
+            d_stride_req, d_stride_kvh, stride_tok):
+    """Copy every request's valid rows pools -> dense (to_dense) or dense -> pools, IN PLACE in
+    the destination arrays (writable uint16)."""
+    lib = _load()
+    dst = (k_dense, v_dense) if to_dense else (k_pool, v_pool)
+    src = (k_pool, v_pool) if to_dense else (k_dense, v_dense)
+    for a in dst:
+        _writable_u16(a, "destination")
+    src = [_as_u16(a, "source") for a in src]
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    table = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    if lens.size != n_req or table.size != n_req * max_blocks:
+        raise ValueError("seq_lens / block_table have the wrong number of entries")
+    need_p = (n_blocks - 1) * stride_block + (n_kvh - 1) * p_stride_kvh + (block_size - 1) * stride_tok + head_dim
+    need_d = 0 if n_req == 0 else ((n_req - 1) * d_stride_req + (n_kvh - 1) * d_stride_kvh
+                                   + (max_len - 1) * stride_tok + head_dim)
+    kp, vp = (src if to_dense else dst)
+    kd, vd = (dst if to_dense else src)
+    if kp.size < need_p or vp.size < need_p or kd.size < need_d or vd.size < need_d:
+        raise ValueError("a buffer is smaller than its strides address")
+    rc = lib.sw_oracle_kv_pack(kp.ctypes.data, vp.ctypes.data, table.ctypes.data, lens.ctypes.data,
+                               kd.ctypes.data, vd.ctypes.data, 0 if to_dense else 1,
+                               n_req, n_kvh, head_dim, max_len, block_size, max_blocks, n_blocks,
+                               stride_block, p_stride_kvh, d_stride_req, d_stride_kvh, stride_tok)
+    if rc < 0:
+        raise ValueError("sw_oracle_kv_pack rejected its arguments (code %d)" % rc)
+
+
+def kv_span_plan(block_table, seq_lens, n_req, block_size, max_blocks, n_blocks, fill=-1):
+    """Returns (span_first [n_req, max_blocks], span_blocks [n_req, max_blocks], n_spans [n_req]);
+    entries past a request's span count hold `fill`."""
+    lib = _load()
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    table = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    if lens.size != n_req or table.size != n_req * max_blocks:
+        raise ValueError("seq_lens / block_table have the wrong number of entries")
+    first = np.full((n_req, max_blocks), fill, dtype=np.int32)
+    count = np.full((n_req, max_blocks), fill, dtype=np.int32)
+    n = np.full(n_req, fill, dtype=np.int32)
+    rc = lib.sw_oracle_kv_span_plan(table.ctypes.data, lens.ctypes.data, first.ctypes.data,
+                                    count.ctypes.data, n.ctypes.data, n_req, block_size, max_blocks,
+                                    n_blocks)
+    if rc < 0:
+        raise ValueError("sw_oracle_kv_span_plan rejected its arguments (code %d)" % rc)
+    return first, count, n

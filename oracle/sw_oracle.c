@@ -403,6 +403,96 @@ int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t 
     return failed ? -4 : used;
 }
 
+/*
+ * KV-cache hand-off (sections 4.3 and 5.1: the prompt machine ships each layer's
+ * KV cache to the token machine, block by block, merging blocks that are contiguous
+ * so that fewer transfers are issued).  Three plain routines cover the part of it
+ * that happens inside one GPU's memory:
+ *
+ * sw_oracle_kv_pack: block pools -> the dense layout, i.e. every (request, head)
+ * becomes one contiguous run of L rows (dir = 0), or the reverse (dir = 1).
+ * Position t of request r, head g is
+ *     pool:  clamp(block_table[r*max_blocks + t/block_size]) * stride_block
+ *            + g*p_stride_kvh + (t % block_size)*stride_tok
+ *     dense: r*d_stride_req + g*d_stride_kvh + t*stride_tok
+ * for t < L = clamp(seq_lens[r], 0, min(max_len, max_blocks*block_size)).
+ * Nothing else is written.
+ * Pinned: packing pools built from a batch gives the dense buffer built from the
+ * same batch; unpack(pack(x)) = x (tests/test_oracle_pins.py).
+ */
+int sw_oracle_kv_pack(uint16_t *k_pool, uint16_t *v_pool, const int32_t *block_table,
+                      const int32_t *seq_lens, uint16_t *k_dense, uint16_t *v_dense, int dir,
+                      int n_req, int n_kvh, int head_dim, int max_len,
+                      int block_size, int max_blocks, int n_blocks,
+                      int64_t stride_block, int64_t p_stride_kvh,
+                      int64_t d_stride_req, int64_t d_stride_kvh, int64_t stride_tok)
+{
+    if (n_req < 0 || n_kvh <= 0 || head_dim <= 0 || max_len <= 0 || block_size <= 0 ||
+        max_blocks <= 0 || n_blocks <= 0) return -1;
+    if (n_req == 0) return 0;
+    if (!k_pool || !v_pool || !block_table || !seq_lens || !k_dense || !v_dense) return -3;
+    int64_t cap = (int64_t)max_blocks * block_size;
+    if (cap > max_len) cap = max_len;
+    for (int r = 0; r < n_req; ++r) {
+        int64_t L = seq_lens[r];
+        L = L < 0 ? 0 : (L > cap ? cap : L);
+        for (int g = 0; g < n_kvh; ++g)
+            for (int64_t t = 0; t < L; ++t) {
+                int b = clampi(block_table[(int64_t)r * max_blocks + t / block_size], 0, n_blocks - 1);
+                int64_t po = (int64_t)b * stride_block + (int64_t)g * p_stride_kvh + (t % block_size) * stride_tok;
+                int64_t dn = (int64_t)r * d_stride_req + (int64_t)g * d_stride_kvh + t * stride_tok;
+                for (int j = 0; j < head_dim; ++j) {
+                    if (dir == 0) {
+                        k_dense[dn + j] = k_pool[po + j];
+                        v_dense[dn + j] = v_pool[po + j];
+                    } else {
+                        k_pool[po + j] = k_dense[dn + j];
+                        v_pool[po + j] = v_dense[dn + j];
+                    }
+                }
+            }
+    }
+    return 0;
+}
+
+/*
+ * sw_oracle_kv_span_plan: the transfers one layer of one request needs when blocks
+ * with consecutive pool ids are shipped as one span.  For request r with
+ * nb = ceil(L / block_size) blocks in use, entry i starts a new span when i == 0
+ * or id[i] != id[i-1] + 1 (ids clamped into the pool).  Outputs, per request:
+ * n_spans[r]; span_first[r*max_blocks + k] = pool id of the k-th span's first
+ * block; span_blocks[r*max_blocks + k] = its number of blocks.  Entries past
+ * n_spans[r] are left as they were.
+ */
+int sw_oracle_kv_span_plan(const int32_t *block_table, const int32_t *seq_lens,
+                           int32_t *span_first, int32_t *span_blocks, int32_t *n_spans,
+                           int n_req, int block_size, int max_blocks, int n_blocks)
+{
+    if (n_req < 0 || block_size <= 0 || max_blocks <= 0 || n_blocks <= 0) return -1;
+    if (n_req == 0) return 0;
+    if (!block_table || !seq_lens || !span_first || !span_blocks || !n_spans) return -3;
+    const int64_t cap = (int64_t)max_blocks * block_size;
+    for (int r = 0; r < n_req; ++r) {
+        int64_t L = seq_lens[r];
+        L = L < 0 ? 0 : (L > cap ? cap : L);
+        int nb = (int)((L + block_size - 1) / block_size);
+        int k = -1;
+        int prev = 0;
+        for (int i = 0; i < nb; ++i) {
+            int id = clampi(block_table[(int64_t)r * max_blocks + i], 0, n_blocks - 1);
+            if (i == 0 || id != prev + 1) {
+                ++k;
+                span_first[(int64_t)r * max_blocks + k] = id;
+                span_blocks[(int64_t)r * max_blocks + k] = 0;
+            }
+            span_blocks[(int64_t)r * max_blocks + k] += 1;
+            prev = id;
+        }
+        n_spans[r] = k + 1;
+    }
+    return 0;
+}
+
 int sw_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -469,3 +469,59 @@ def test_prefill_rows_do_not_depend_on_later_positions_or_other_requests():
     assert not ref3[:3].any() and not ref3[35:40].any() and not ref3[60:].any()
     with pytest.raises(ValueError):
         oracle.prefill_attn(qt, k, v, b.seq_lens, [0, 40], 2, 4, 4, 64, 32, sr, sg, st)
+
+
+# ---- KV hand-off: pools <-> dense, transfer spans ----
+
+def test_kv_pack_of_pools_equals_the_dense_buffer_of_the_same_batch_and_round_trips():
+    cfg = wl.custom_config("pk", 5, 4, 2, 64, 64)
+    lens = [0, 1, 17, 64, 40]
+    b = wl.make_batch(cfg, seed=99, seq_lens=lens)
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    sg += 64; sr = 2 * sg + 128; tot = 5 * sr
+    want_k = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, 0x1234)
+    want_v = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, 0x1234)
+    for bs in (4, 16):
+        sb, sgp, stp = wl.dense_paged_layout(cfg, bs)
+        sb += 32
+        mb, nb = 64 // bs, 5 * (64 // bs) + 2
+        kp, vp, table = wl.pack_paged(b.k_rows, b.v_rows, cfg, bs, sb, sgp, stp, nb, seed=bs, pad_bits=0x7E00)
+        kd = np.full(tot, 0x1234, np.uint16)
+        vd = np.full(tot, 0x1234, np.uint16)
+        geom = (5, 2, 64, 64, bs, mb, nb, sb, sgp, sr, sg, st)
+        oracle.kv_pack(kp, vp, table, lens, kd, vd, True, *geom)
+        assert np.array_equal(kd, want_k) and np.array_equal(vd, want_v)    # and padding untouched
+        # back into fresh pools: the valid rows return, everything else keeps its fill
+        kp2 = np.full(kp.size, 0x4321, np.uint16)
+        vp2 = np.full(vp.size, 0x4321, np.uint16)
+        oracle.kv_pack(kp2, vp2, table, lens, kd, vd, False, *geom)
+        kp_ref, vp_ref, _ = wl.pack_paged(b.k_rows, b.v_rows, cfg, bs, sb, sgp, stp, nb, seed=bs, pad_bits=0x4321)
+        assert np.array_equal(kp2, kp_ref) and np.array_equal(vp2, vp_ref)
+        assert not np.array_equal(kd, vd)
+
+
+def test_kv_span_plan_matches_brute_force():
+    rng = np.random.Generator(np.random.Philox(100))
+    n_req, bs, mb, nb = 7, 8, 12, 64
+    lens = np.array([0, 1, 8, 9, 96, 50, 200], np.int32)          # 200 clamps to 96
+    table = rng.integers(0, nb, size=(n_req, mb)).astype(np.int32)
+    table[4] = np.arange(10, 22)                                   # one span
+    table[5, :7] = [3, 4, 5, 9, 10, 2, 3]                          # 3 spans: [3,4,5] [9,10] [2,3]
+    table[6, :4] = [70, 71, -5, 1]                                 # clamped ids: 63, 63, 0, 1
+    first, count, n = oracle.kv_span_plan(table, lens, n_req, bs, mb, nb)
+    for r in range(n_req):
+        L = min(max(int(lens[r]), 0), mb * bs)
+        ids = np.clip(table[r, :-(-L // bs)], 0, nb - 1).tolist()
+        spans = []
+        for i, b in enumerate(ids):
+            if i and b == ids[i - 1] + 1:
+                spans[-1][1] += 1
+            else:
+                spans.append([b, 1])
+        assert n[r] == len(spans)
+        assert first[r, :n[r]].tolist() == [s[0] for s in spans]
+        assert count[r, :n[r]].tolist() == [s[1] for s in spans]
+        assert (first[r, n[r]:] == -1).all() and (count[r, n[r]:] == -1).all()
+        assert count[r, :n[r]].sum() == len(ids)
+    assert n[4] == 1 and n[5] == 3 and n[0] == 0
+    assert first[6, :3].tolist() == [63, 63, 0] and count[6, :3].tolist() == [1, 1, 2]
