@@ -248,6 +248,42 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
                     int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream);
 
 /*
+ * KV-cache hand-off, the part inside one GPU's memory.  A prompt machine ships
+ * each layer's KV cache to a token machine block by block, merging blocks that
+ * are contiguous so that fewer transfers are issued (section 4.3, "KV-cache
+ * transfer"; section 5.1).  The transfer itself is outside this library.
+ *
+ * sw_kv_pack -- copies positions [0, L_r) of every request and key/value head
+ * from block pools (sw_kv_paged_layout) into dense caches (sw_kv_layout(n_req,
+ * n_kvh, head_dim, max_len)), where every (request, head) is one contiguous run
+ * ready to be sent or attended over; sw_kv_unpack is the reverse (dense -> the
+ * blocks the table names).  L_r = clamp(seq_lens[r], 0, min(max_len,
+ * max_blocks*block_size)).  Rows are copied bit for bit; nothing else in the
+ * destination is written.  All pointers DEVICE; pools and caches 16-byte
+ * aligned, int32 arrays 4-byte aligned; block ids clamped into the pool.
+ * Errors and asynchrony as in sw_decode_attn_paged (no workspace).
+ *
+ * sw_kv_span_plan -- the transfers one layer needs when runs of consecutive
+ * pool block ids go out as one span.  For request r with nb = ceil(L_r /
+ * block_size) blocks in use (L_r clamped to max_blocks*block_size), entry i of
+ * its table row starts a span when i == 0 or id[i] != id[i-1] + 1.  Outputs
+ * (DEVICE int32): n_spans[r]; span_first[r*max_blocks + k] = pool id of span
+ * k's first block; span_blocks[r*max_blocks + k] = its length in blocks, for
+ * k < n_spans[r]; later entries are not written.
+ */
+int sw_kv_pack(const void *k_pool, const void *v_pool, const int32_t *block_table,
+               const int32_t *seq_lens, void *k_dense, void *v_dense,
+               int n_req, int n_kvh, int head_dim, int max_len,
+               int block_size, int max_blocks, int n_blocks, void *stream);
+int sw_kv_unpack(const void *k_dense, const void *v_dense, const int32_t *block_table,
+                 const int32_t *seq_lens, void *k_pool, void *v_pool,
+                 int n_req, int n_kvh, int head_dim, int max_len,
+                 int block_size, int max_blocks, int n_blocks, void *stream);
+int sw_kv_span_plan(const int32_t *block_table, const int32_t *seq_lens,
+                    int32_t *span_first, int32_t *span_blocks, int32_t *n_spans,
+                    int n_req, int block_size, int max_blocks, int n_blocks, void *stream);
+
+/*
  * sw_last_error -- text of the calling thread's most recent failure
  * (a static or thread-local string; never NULL; valid until the thread's next
  * failing call).  Support call, not part of the step.

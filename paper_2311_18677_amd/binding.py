@@ -30,7 +30,7 @@ SW_PARAM_PREFILL_WAVES = 6
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
-           "sw_prefill_attn",
+           "sw_prefill_attn", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
 
@@ -93,6 +93,11 @@ def load():
     lib.sw_advance_lens.argtypes = [vp, ci, ci, vp]
     lib.sw_prefill_attn.restype = ci
     lib.sw_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_longlong, ci, ci, ci, ci, ci, vp]
+    for fn in (lib.sw_kv_pack, lib.sw_kv_unpack):
+        fn.restype = ci
+        fn.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.sw_kv_span_plan.restype = ci
+    lib.sw_kv_span_plan.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
     lib.sw_last_error.restype = ctypes.c_char_p
     lib.sw_last_error.argtypes = []
     lib.sw_version.restype = ci
@@ -211,6 +216,33 @@ def sw_prefill_attn(q, k_cache, v_cache, seq_lens, q_starts, out, n_tokens, n_re
     rc = load().sw_prefill_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens),
                                 _ptr(q_starts), _ptr(out), int(n_tokens), n_req, n_qh, n_kvh,
                                 head_dim, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_kv_pack(k_pool, v_pool, block_table, seq_lens, k_dense, v_dense, n_req, n_kvh, head_dim,
+               max_len, block_size, max_blocks, n_blocks, stream=None, check=True):
+    """Block pools -> dense caches (every request's valid rows)."""
+    rc = load().sw_kv_pack(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(seq_lens),
+                           _ptr(k_dense), _ptr(v_dense), n_req, n_kvh, head_dim, max_len,
+                           block_size, max_blocks, n_blocks, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_kv_unpack(k_dense, v_dense, block_table, seq_lens, k_pool, v_pool, n_req, n_kvh, head_dim,
+                 max_len, block_size, max_blocks, n_blocks, stream=None, check=True):
+    """Dense caches -> the pool blocks the table names."""
+    rc = load().sw_kv_unpack(_ptr(k_dense), _ptr(v_dense), _ptr(block_table), _ptr(seq_lens),
+                             _ptr(k_pool), _ptr(v_pool), n_req, n_kvh, head_dim, max_len,
+                             block_size, max_blocks, n_blocks, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_kv_span_plan(block_table, seq_lens, span_first, span_blocks, n_spans, n_req, block_size,
+                    max_blocks, n_blocks, stream=None, check=True):
+    """Runs of consecutive pool block ids per request (the transfers a layer needs)."""
+    rc = load().sw_kv_span_plan(_ptr(block_table), _ptr(seq_lens), _ptr(span_first),
+                                _ptr(span_blocks), _ptr(n_spans), n_req, block_size, max_blocks,
+                                n_blocks, _stream(stream))
     return _check(rc) if check else rc
 
 

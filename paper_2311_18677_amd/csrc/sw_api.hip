@@ -549,6 +549,127 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     return SW_OK;
 }
 
+// sw_kv_pack / sw_kv_unpack
+static int kv_copy(void *k_pool, void *v_pool, const int32_t *block_table, const int32_t *seq_lens,
+                   void *k_dense, void *v_dense, bool to_dense,
+                   int n_req, int n_kvh, int head_dim, int max_len,
+                   int block_size, int max_blocks, int n_blocks, void *stream_v)
+{
+    if (block_size < 4 || block_size > 4096 || (block_size & (block_size - 1)))
+        return fail(SW_ERR_UNSUPPORTED, "block_size must be a power of two in [4, 4096]");
+    if (max_blocks <= 0 || n_blocks <= 0) return fail(SW_ERR_SHAPE, "max_blocks and n_blocks must be > 0");
+    if ((long long)max_blocks * block_size > (1 << 23))
+        return fail(SW_ERR_SHAPE, "max_blocks * block_size above 2^23");
+    int rc = check_shape(n_req, n_kvh, head_dim, max_len);
+    if (rc != SW_OK) return rc;
+    if (n_req == 0) return SW_OK;
+    if (!k_pool || !v_pool || !block_table || !seq_lens || !k_dense || !v_dense)
+        return fail(SW_ERR_NULL, "pools, block_table, seq_lens and dense caches must be non-NULL");
+    if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)k_dense | (uintptr_t)v_dense) & 15u)
+        return fail(SW_ERR_ALIGN, "pools and dense caches must be 16-byte aligned");
+    if (((uintptr_t)seq_lens | (uintptr_t)block_table) & 3u)
+        return fail(SW_ERR_ALIGN, "seq_lens and block_table must be 4-byte aligned");
+
+    SwHandoffArgs a;
+    a.k_pool = (uint16_t *)k_pool;
+    a.v_pool = (uint16_t *)v_pool;
+    a.k_dense = (uint16_t *)k_dense;
+    a.v_dense = (uint16_t *)v_dense;
+    a.block_table = block_table;
+    a.seq_lens = seq_lens;
+    a.n_req = n_req;
+    a.n_kvh = n_kvh;
+    a.head_dim = head_dim;
+    const long long cap = (long long)max_blocks * block_size;
+    a.cap = (int)(cap < max_len ? cap : max_len);
+    const int rows = sw_kv_copy_rows_per_group();
+    a.n_tiles = (a.cap + rows - 1) / rows;
+    a.block_shift = 0;
+    while ((1 << a.block_shift) < block_size) ++a.block_shift;
+    a.max_blocks = max_blocks;
+    a.n_blocks = n_blocks;
+    a.p_stride_kvh = (long long)block_size * head_dim;
+    a.stride_block = a.p_stride_kvh * n_kvh;
+    a.d_stride_kvh = slab_elems(head_dim, max_len);
+    a.d_stride_req = a.d_stride_kvh * n_kvh;
+    if ((long long)n_req * n_kvh * a.n_tiles > 0x7fffffffLL) return fail(SW_ERR_SHAPE, "too many workgroups");
+
+    bool prof;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
+    }
+    SwLaunchEvents ev = {nullptr, nullptr};
+    ProfRec rec;
+    rec.has_combine = false;
+    hipError_t e;
+    if (prof) {
+        for (int i = 0; i < 4; ++i) {
+            e = hipEventCreate(&rec.ev[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
+                return fail_hip(e, "hipEventCreate");
+            }
+        }
+        ev = {rec.ev[0], rec.ev[1]};
+    }
+    e = sw_launch_kv_copy(a, to_dense, (hipStream_t)stream_v, prof ? &ev : nullptr);
+    if (e != hipSuccess) {
+        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        return fail_hip(e, "kernel launch");
+    }
+    if (prof) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
+        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+    }
+    return SW_OK;
+}
+
+int sw_kv_pack(const void *k_pool, const void *v_pool, const int32_t *block_table,
+               const int32_t *seq_lens, void *k_dense, void *v_dense,
+               int n_req, int n_kvh, int head_dim, int max_len,
+               int block_size, int max_blocks, int n_blocks, void *stream)
+{
+    return kv_copy(const_cast<void *>(k_pool), const_cast<void *>(v_pool), block_table, seq_lens,
+                   k_dense, v_dense, true, n_req, n_kvh, head_dim, max_len,
+                   block_size, max_blocks, n_blocks, stream);
+}
+
+int sw_kv_unpack(const void *k_dense, const void *v_dense, const int32_t *block_table,
+                 const int32_t *seq_lens, void *k_pool, void *v_pool,
+                 int n_req, int n_kvh, int head_dim, int max_len,
+                 int block_size, int max_blocks, int n_blocks, void *stream)
+{
+    return kv_copy(k_pool, v_pool, block_table, seq_lens, const_cast<void *>(k_dense),
+                   const_cast<void *>(v_dense), false, n_req, n_kvh, head_dim, max_len,
+                   block_size, max_blocks, n_blocks, stream);
+}
+
+int sw_kv_span_plan(const int32_t *block_table, const int32_t *seq_lens,
+                    int32_t *span_first, int32_t *span_blocks, int32_t *n_spans,
+                    int n_req, int block_size, int max_blocks, int n_blocks, void *stream)
+{
+    if (n_req < 0 || n_req > (1 << 20)) return fail(SW_ERR_SHAPE, "n_req must be in [0, 2^20]");
+    if (block_size < 4 || block_size > 4096 || (block_size & (block_size - 1)))
+        return fail(SW_ERR_UNSUPPORTED, "block_size must be a power of two in [4, 4096]");
+    if (max_blocks <= 0 || n_blocks <= 0) return fail(SW_ERR_SHAPE, "max_blocks and n_blocks must be > 0");
+    if ((long long)max_blocks * block_size > (1 << 23))
+        return fail(SW_ERR_SHAPE, "max_blocks * block_size above 2^23");
+    if (n_req == 0) return SW_OK;
+    if (!block_table || !seq_lens || !span_first || !span_blocks || !n_spans)
+        return fail(SW_ERR_NULL, "block_table, seq_lens, span_first, span_blocks and n_spans must be non-NULL");
+    if (((uintptr_t)block_table | (uintptr_t)seq_lens | (uintptr_t)span_first |
+         (uintptr_t)span_blocks | (uintptr_t)n_spans) & 3u)
+        return fail(SW_ERR_ALIGN, "int32 arrays must be 4-byte aligned");
+    int shift = 0;
+    while ((1 << shift) < block_size) ++shift;
+    hipError_t e = sw_launch_kv_span_plan(block_table, seq_lens, span_first, span_blocks, n_spans,
+                                          n_req, shift, max_blocks, n_blocks, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return SW_OK;
+}
+
 int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream)
 {
     if (n_req < 0 || max_len <= 0) return fail(SW_ERR_SHAPE, "n_req must be >= 0 and max_len > 0");

@@ -60,6 +60,20 @@ struct SwPrefillArgs {
     float scale_log2e;
 };
 
+// Arguments of the pools <-> dense copy of the KV hand-off.
+struct SwHandoffArgs {
+    uint16_t *k_pool, *v_pool;          // block pools
+    uint16_t *k_dense, *v_dense;        // dense caches
+    const int32_t *block_table;
+    const int32_t *seq_lens;
+    int   n_req, n_kvh, head_dim;
+    int   cap;                          // positions copied at most: min(max_len, max_blocks * block_size)
+    int   n_tiles;                      // workgroups per (request, head)
+    int   block_shift, max_blocks, n_blocks;
+    long long stride_block, p_stride_kvh;       // pools, in elements
+    long long d_stride_req, d_stride_kvh;       // dense, in elements
+};
+
 // Number of cached positions request r attends over, with a flag.  seq_lens[r]
 // is clamped to [0, max_len]; in the append variant it counts the positions
 // cached BEFORE the newest token, whose K/V rows this call stores at that
@@ -107,6 +121,12 @@ hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunch
 bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
 void       sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw);
 hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+int        sw_kv_copy_rows_per_group();
+hipError_t sw_launch_kv_copy(const SwHandoffArgs &a, bool to_dense, hipStream_t stream, const SwLaunchEvents *ev);
+hipError_t sw_launch_kv_span_plan(const int32_t *block_table, const int32_t *seq_lens,
+                                  int32_t *span_first, int32_t *span_blocks, int32_t *n_spans,
+                                  int n_req, int block_shift, int max_blocks, int n_blocks,
+                                  hipStream_t stream);
 hipError_t sw_launch_advance_lens(int32_t *seq_lens, int n_req, int max_len, hipStream_t stream);
 
 // Granularity the chunk length must be a multiple of (all kernels).

@@ -194,3 +194,28 @@ def test_prefill_validation():
     assert pcall(max_len=0) == sw.SW_ERR_SHAPE
     assert pcall(n_tokens=0) == sw.SW_OK
     assert pcall(n_req=0) == sw.SW_OK
+
+
+def test_kv_handoff_validation():
+    def pk(fn, a=0x1000, b=0x2000, tab=0x3000, lens=0x4000, c=0x5000, d=0x6000, n_req=2, n_kvh=2,
+           hd=128, max_len=256, bs=16, mb=16, nb=40):
+        return fn(a, b, tab, lens, c, d, n_req, n_kvh, hd, max_len, bs, mb, nb, None, check=False)
+    for fn in (sw.sw_kv_pack, sw.sw_kv_unpack):
+        assert pk(fn, a=None) == sw.SW_ERR_NULL
+        assert pk(fn, tab=None) == sw.SW_ERR_NULL
+        assert pk(fn, d=0x6004) == sw.SW_ERR_ALIGN
+        assert pk(fn, lens=0x4001) == sw.SW_ERR_ALIGN
+        assert pk(fn, bs=12) == sw.SW_ERR_UNSUPPORTED
+        assert pk(fn, hd=96) == sw.SW_ERR_UNSUPPORTED
+        assert pk(fn, mb=0) == sw.SW_ERR_SHAPE
+        assert pk(fn, max_len=0) == sw.SW_ERR_SHAPE
+        assert pk(fn, n_req=0) == sw.SW_OK
+
+    def sp(tab=0x1000, lens=0x2000, f=0x3000, c=0x4000, n=0x5000, n_req=3, bs=16, mb=8, nb=20):
+        return sw.sw_kv_span_plan(tab, lens, f, c, n, n_req, bs, mb, nb, None, check=False)
+    assert sp(f=None) == sw.SW_ERR_NULL
+    assert sp(n=0x5002) == sw.SW_ERR_ALIGN
+    assert sp(bs=3) == sw.SW_ERR_UNSUPPORTED
+    assert sp(nb=0) == sw.SW_ERR_SHAPE
+    assert sp(n_req=-1) == sw.SW_ERR_SHAPE
+    assert sp(n_req=0) == sw.SW_OK
