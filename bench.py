@@ -48,6 +48,9 @@ def parse_args():
                          "append-then-attend call each, lengths advanced on the device per step")
     ap.add_argument("--prefill", action="store_true",
                     help="time the prompt-phase (causal) attention instead; workloads prefill_*")
+    ap.add_argument("--handoff", action="store_true",
+                    help="time the KV hand-off copy (block pools -> dense) instead; uses --paged "
+                         "BLOCK (default 16)")
     ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--prefill-waves", type=int, default=0)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -276,6 +279,130 @@ def main_prefill(args):
     print(json.dumps(line))
 
 
+def main_handoff(args):
+    """KV hand-off packing: a step is one sw_kv_pack call (one layer of one batch, pools -> dense)."""
+    import numpy as np
+    import torch
+    from paper_2311_18677_amd import binding as sw
+    from paper_2311_18677_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    sw.load()
+    cfg = wl.CONFIGS[args.workload]
+    bs = args.paged or 16
+    lay = sw.sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+    batch0 = wl.make_batch(cfg)
+    set0 = sw.upload_paged_batch(batch0, bs, device="cuda:0", pad_bits=0)
+    set0["kv_bytes"] = batch0.kv_bytes
+    # the copy reads and writes every byte: the rotation must exceed the LLC on both sides
+    n_sets = args.sets or max(2, -(-4 * LLC_BYTES // max(2 * batch0.kv_bytes, 1)))
+    sets = [set0]
+    for i in range(1, n_sets):
+        sets.append(make_paged_set(cfg, bs, wl.BASE_SEED + 1000 * cfg.seed_index + i, torch, np, wl, sw, dev))
+    for s in sets:
+        s["k_dense"] = torch.zeros(lay.total_elems, dtype=torch.float16, device=dev)
+        s["v_dense"] = torch.zeros(lay.total_elems, dtype=torch.float16, device=dev)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_kv_pack(s["k_pool"], s["v_pool"], s["block_table"], s["seq_lens"], s["k_dense"],
+                      s["v_dense"], cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len, bs,
+                      s["max_blocks"], s["n_blocks"], st)
+
+    call(sets[0], stream)
+    stream.synchronize()
+    steps, warmup = args.steps, args.warmup
+    graph, mode = None, args.mode
+    if mode == "graph":
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for s in sets:
+                    call(s, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+        except Exception as e:      # noqa: BLE001
+            print("bench.py: graph capture failed (%s); using eager launches" % e, file=sys.stderr)
+            graph, mode = None, "eager"
+
+    def run_steps(n):
+        if graph is not None:
+            full, rem = divmod(n, n_sets)
+            with torch.cuda.stream(stream):
+                for _ in range(full):
+                    graph.replay()
+            for i in range(rem):
+                call(sets[i], stream)
+            return
+        for i in range(n):
+            call(sets[i % n_sets], stream)
+
+    run_steps(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    moved = 2 * sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))      # read + written
+
+    prof_calls = min(steps, 50 * n_sets)
+    sw.sw_prof_start(prof_calls)
+    for i in range(prof_calls):
+        call(sets[i % n_sets], stream)
+    k_us_sum, _, n_rec = sw.sw_prof_stop()
+    kernel_us = k_us_sum / max(n_rec, 1)
+    prof_bytes = 2 * sum(sets[i % n_sets]["kv_bytes"] for i in range(n_rec)) / max(n_rec, 1)
+    achieved = prof_bytes / (kernel_us * 1e-6) / 1e9 if kernel_us > 0 else 0.0
+
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        pl = set0["layout"]
+        kd = np.zeros(lay.total_elems, np.uint16)
+        vd = np.zeros(lay.total_elems, np.uint16)
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 200:
+            c0 = time.perf_counter()
+            oracle.kv_pack(set0["k_host"], set0["v_host"], set0["table_host"], batch0.seq_lens, kd, vd,
+                           True, cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len, bs, set0["max_blocks"],
+                           set0["n_blocks"], pl.stride_block, pl.stride_kvh, lay.stride_req,
+                           lay.stride_kvh, lay.stride_tok)
+            t_cpu += time.perf_counter() - c0
+            reps += 1
+        cpu_baseline = {"value": 2 * batch0.kv_bytes * reps / t_cpu / 1e9, "unit": "GB/s", "cores": 1,
+                        "kind": "oracle",
+                        "sample": "set 0 of %s (whole batch), %d repetitions, %.1f s" % (cfg.name, reps, t_cpu)}
+        set0["k_dense"].zero_(), set0["v_dense"].zero_()
+        call(set0, stream)
+        stream.synchronize()
+        same = (np.array_equal(set0["k_dense"].cpu().numpy().view(np.uint16), kd)
+                and np.array_equal(set0["v_dense"].cpu().numpy().view(np.uint16), vd))
+        parity = {"bit_exact": bool(same)}
+
+    gbps = moved / elapsed / 1e9
+    line = {
+        "metric": "KV hand-off packing GB/s (bytes read + bytes written; % of MI355X HBM peak)",
+        "value": gbps, "unit": "GB/s", "pct_of_peak": 100.0 * gbps / HBM_PEAK_GBPS,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * elapsed / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16 (bit copy)",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_kvh": cfg.n_kvh,
+                   "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
+                   "block_size": bs, "bytes_moved_per_step": moved / steps, "cache_sets": n_sets,
+                   "launch": mode, "entry_point": "sw_kv_pack"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "sw_kv_copy_kernel", "kernel_us": kernel_us,
+                     "bytes_per_launch": prof_bytes, "launches_timed": n_rec},
+        "cpu_baseline": cpu_baseline,
+        "parity_set0": parity,
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -284,6 +411,8 @@ def main():
         sys.exit(2)
     if args.prefill:
         return main_prefill(args)
+    if args.handoff:
+        return main_handoff(args)
 
     import numpy as np
     import torch
