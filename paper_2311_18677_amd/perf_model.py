@@ -1,0 +1,193 @@
+"""Piece-wise linear performance model of the token-phase attention call.
+
+The paper drives its cluster simulator with a piece-wise linear performance
+model fitted to profiles at various batch and sequence sizes and validates it
+on an 80:20 train:test split (section 5.2, "Performance model": mean absolute
+percentage error below 3 %).  This module does the same for this library's own
+measurements on one MI355X:
+
+    python -m paper_2311_18677_amd.perf_model --sweep out.txt     (needs the GPU)
+    python -m paper_2311_18677_amd.perf_model --fit out.txt       (CPU only)
+
+The model is a continuous function of (batch size, context length) that is
+linear inside every cell of a knot grid: a tensor product of one-dimensional
+"hat" bases, fitted by least squares.  Both axes are used in log2 units, which
+is how the profile points are spaced.
+"""
+import argparse
+import math
+import sys
+import time
+
+import numpy as np
+
+
+def hat_basis(x, knots):
+    """Values of the piece-wise linear hat functions on `knots` at points x: [len(x), len(knots)].
+
+    Rows sum to one; points outside the knot range take the value of the nearest end
+    (clamped), so the model never extrapolates a slope.
+    """
+    knots = np.asarray(knots, dtype=np.float64)
+    if knots.ndim != 1 or knots.size < 2 or np.any(np.diff(knots) <= 0):
+        raise ValueError("knots must be at least two strictly increasing values")
+    x = np.clip(np.asarray(x, dtype=np.float64), knots[0], knots[-1])
+    idx = np.clip(np.searchsorted(knots, x, side="right") - 1, 0, knots.size - 2)
+    w = (x - knots[idx]) / (knots[idx + 1] - knots[idx])
+    out = np.zeros((x.size, knots.size))
+    rows = np.arange(x.size)
+    out[rows, idx] = 1.0 - w
+    out[rows, idx + 1] += w
+    return out
+
+
+class PiecewiseLinearModel:
+    """time(batch, context): linear inside every cell of (batch knots) x (context knots)."""
+
+    def __init__(self, batch_knots, context_knots):
+        self.bk = np.log2(np.asarray(batch_knots, dtype=np.float64))
+        self.ck = np.log2(np.asarray(context_knots, dtype=np.float64))
+        self.coef = None
+
+    def _design(self, batch, context):
+        hb = hat_basis(np.log2(np.asarray(batch, dtype=np.float64)), self.bk)
+        hc = hat_basis(np.log2(np.asarray(context, dtype=np.float64)), self.ck)
+        return (hb[:, :, None] * hc[:, None, :]).reshape(hb.shape[0], -1)
+
+    def fit(self, batch, context, t):
+        a = self._design(batch, context)
+        # a small ridge keeps grid nodes that no training point touches finite
+        lam = 1e-9
+        ata = a.T @ a + lam * np.eye(a.shape[1])
+        self.coef = np.linalg.solve(ata, a.T @ np.asarray(t, dtype=np.float64))
+        return self
+
+    def predict(self, batch, context):
+        if self.coef is None:
+            raise RuntimeError("fit first")
+        return self._design(batch, context) @ self.coef
+
+
+def mape(pred, true):
+    pred, true = np.asarray(pred, dtype=np.float64), np.asarray(true, dtype=np.float64)
+    return float(np.mean(np.abs(pred - true) / np.abs(true))) * 100.0
+
+
+def split_80_20(n, seed=0):
+    """Seeded 80:20 split of range(n): (train indices, test indices)."""
+    order = np.random.Generator(np.random.Philox(int(seed))).permutation(n)
+    n_test = max(1, int(round(0.2 * n)))
+    return np.sort(order[n_test:]), np.sort(order[:n_test])
+
+
+def evaluate(batch, context, t, batch_knots, context_knots, seed=0):
+    """Fit on 80 %, report MAPE on the held-out 20 % and on the training points."""
+    batch, context, t = (np.asarray(x, dtype=np.float64) for x in (batch, context, t))
+    tr, te = split_80_20(batch.size, seed)
+    m = PiecewiseLinearModel(batch_knots, context_knots).fit(batch[tr], context[tr], t[tr])
+    return {"train_mape": mape(m.predict(batch[tr], context[tr]), t[tr]),
+            "test_mape": mape(m.predict(batch[te], context[te]), t[te]),
+            "n_train": int(tr.size), "n_test": int(te.size), "model": m}
+
+
+# ---- measurement on the GPU -------------------------------------------------------------
+
+BATCHES = (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128)
+CONTEXTS = (128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 8192)
+# knots at the powers of two; the profile grid also has the points half-way between them
+BATCH_KNOTS = (1, 2, 4, 8, 16, 32, 64, 128)
+CONTEXT_KNOTS = (128, 256, 512, 1024, 2048, 4096, 8192)
+
+
+def measure_point(sw, torch, n_req, ctx, n_qh=8, n_kvh=1, d=128, calls=1500, budget_bytes=1 << 30):
+    """Microseconds per sw_decode_attn call, all requests at context ctx, rotating over
+    enough cache sets to keep the rows out of the last-level cache (at most 48 sets)."""
+    dev = torch.device("cuda:0")
+    lay = sw.sw_kv_layout(n_req, n_kvh, d, ctx)
+    kv_bytes = n_req * n_kvh * ctx * d * 4
+    n_sets = int(min(48, max(2, budget_bytes // max(kv_bytes, 1))))
+    g = torch.Generator(device=dev)
+    g.manual_seed(1000 * n_req + ctx)
+    sets = []
+    for _ in range(n_sets):
+        s = {}
+        for name in ("k", "v"):
+            s[name] = torch.empty(lay.total_elems, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+        s["q"] = torch.empty(n_req * n_qh * d, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+        s["lens"] = torch.full((n_req,), ctx, dtype=torch.int32, device=dev)
+        s["out"] = torch.zeros(n_req * n_qh * d, dtype=torch.float16, device=dev)
+        sets.append(s)
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_decode_attn(s["q"], s["k"], s["v"], s["lens"], s["out"], n_req, n_qh, n_kvh, d, ctx, st)
+
+    call(sets[0], stream)
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for s in sets:
+            call(s, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    reps = max(2, calls // n_sets)
+    with torch.cuda.stream(stream):
+        for _ in range(max(1, reps // 5)):
+            graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for _ in range(reps):
+            graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (reps * n_sets) * 1e6
+
+
+def sweep(path):
+    import torch
+    from . import binding as sw
+    if not torch.cuda.is_available():
+        print("perf_model: no GPU visible", file=sys.stderr)
+        return 1
+    sw.load()
+    with open(path, "w") as f:
+        f.write("# sw_decode_attn, 8 query heads on 1 KV head, head_dim 128, every request at the "
+                "given context\n# batch context microseconds_per_call\n")
+        for b in BATCHES:
+            for c in CONTEXTS:
+                us = measure_point(sw, torch, b, c)
+                f.write("%d %d %.3f\n" % (b, c, us))
+                f.flush()
+            print("batch", b, "done", flush=True)
+            sw.sw_release()
+            torch.cuda.empty_cache()
+    return 0
+
+
+def load_points(path):
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    arr = np.array(rows, dtype=np.float64)
+    return arr[:, 0], arr[:, 1], arr[:, 2]
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--sweep", metavar="FILE", help="measure the grid on the GPU and write it to FILE")
+    ap.add_argument("--fit", metavar="FILE", help="fit the model to FILE (80:20 split) and print the errors")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args(argv)
+    if args.sweep:
+        rc = sweep(args.sweep)
+        if rc:
+            return rc
+    path = args.fit or args.sweep
+    if not path:
+        ap.error("give --sweep FILE or --fit FILE")
+    b, c, t = load_points(path)
+    res = evaluate(b, c, t, BATCH_KNOTS, CONTEXT_KNOTS, seed=args.seed)
+    print("points %d (train %d, test %d)  train MAPE %.2f %%  held-out MAPE %.2f %%"
+          % (b.size, res["n_train"], res["n_test"], res["train_mape"], res["test_mape"]))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
