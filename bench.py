@@ -376,6 +376,7 @@ def main_handoff(args):
                         "kind": "oracle",
                         "sample": "set 0 of %s (whole batch), %d repetitions, %.1f s" % (cfg.name, reps, t_cpu)}
         set0["k_dense"].zero_(), set0["v_dense"].zero_()
+        torch.cuda.synchronize()          # the fills ran on another stream than the call below
         call(set0, stream)
         stream.synchronize()
         same = (np.array_equal(set0["k_dense"].cpu().numpy().view(np.uint16), kd)
