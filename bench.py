@@ -53,6 +53,7 @@ def parse_args():
                          "BLOCK (default 16)")
     ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--prefill-waves", type=int, default=0)
+    ap.add_argument("--prefill-kernel", type=int, default=0)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch plain device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings); 0 = none")
@@ -168,6 +169,7 @@ def main_prefill(args):
     sw.load()
     sw.sw_set_param(sw.SW_PARAM_PREFILL_HEADS, args.prefill_heads)
     sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, args.prefill_waves)
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, args.prefill_kernel)
     name = args.workload if args.workload.startswith("prefill_") else "prefill_llama70b_tp8"
     cfg = wl.PREFILL_CONFIGS[name]
     batch0 = wl.make_batch(cfg)

@@ -238,7 +238,7 @@ int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream);
  *              ranges must not overlap; row indices outside [0, n_tokens) are never
  *              dereferenced (such rows are skipped).
  *   n_tokens   rows of q and out (0 returns SW_OK without touching the device).
- *   head_dim must be 128 and n_qh / n_kvh at most 8 (SW_ERR_UNSUPPORTED otherwise).
+ *   head_dim must be 128 (SW_ERR_UNSUPPORTED otherwise); n_qh / n_kvh at most 64.
  * One kernel, no workspace; asynchrony, ownership and the other errors as in
  * sw_decode_attn.  Weights enter the second matrix product as binary16 and the
  * normaliser sums those same rounded weights.
@@ -323,7 +323,13 @@ int sw_release(void);
  *                      the group size is ignored).
  *   SW_PARAM_PREFILL_WAVES  prompt-phase kernel: waves (32 query positions each) per
  *                      head in a workgroup (0 = library default; ignored if heads *
- *                      waves would exceed 8).
+ *                      waves would exceed 8).  For the key-split kernel: waves per
+ *                      workgroup, 2, 4 or 8.
+ *   SW_PARAM_PREFILL_KERNEL  0 = library default, 1 = the kernel that shares staged
+ *                      K/V tiles among the heads of a group (at most 8 query heads per
+ *                      key/value head, SW_ERR_UNSUPPORTED at call time otherwise),
+ *                      2 = the kernel that splits a query block's key range over the
+ *                      waves of a workgroup.  The two differ by rounding only.
  */
 #define SW_PARAM_CHUNK   1
 #define SW_PARAM_KERNEL  2
@@ -331,6 +337,7 @@ int sw_release(void);
 #define SW_PARAM_WAVES   4
 #define SW_PARAM_PREFILL_HEADS 5
 #define SW_PARAM_PREFILL_WAVES 6
+#define SW_PARAM_PREFILL_KERNEL 7
 int sw_set_param(int key, int value);
 int sw_get_param(int key, int *value);
 

@@ -27,6 +27,7 @@ SW_PARAM_COMBINE = 3
 SW_PARAM_WAVES = 4
 SW_PARAM_PREFILL_HEADS = 5
 SW_PARAM_PREFILL_WAVES = 6
+SW_PARAM_PREFILL_KERNEL = 7
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",

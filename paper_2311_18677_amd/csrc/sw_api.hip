@@ -18,6 +18,9 @@ namespace {
 
 constexpr int kVersion = 100;   // 0.1.0
 
+// prompts up to this many positions go to the key-split prompt kernel by default
+constexpr int kPrefillSplitMaxLen = 16384;
+
 thread_local std::string t_last_error = "";
 
 int fail(int code, const std::string &msg)
@@ -48,7 +51,8 @@ int g_kernel = 0;
 int g_combine = 0;
 int g_waves = 0;
 int g_prefill_hp = 0;   // prompt-phase kernel: query heads per workgroup
-int g_prefill_qw = 0;   //                      waves per query head
+int g_prefill_qw = 0;   //                      waves per query head (key-split kernel: waves per workgroup)
+int g_prefill_kernel = 0;   // 0 = default, 1 = shared-tile kernel, 2 = key-split kernel
 
 // per-kernel timing
 struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
@@ -339,6 +343,10 @@ int sw_set_param(int key, int value)
         if (value < 0 || value > 8) return fail(SW_ERR_PARAM, "prefill waves per head must be in [0, 8]");
         g_prefill_qw = value;
         return SW_OK;
+    case SW_PARAM_PREFILL_KERNEL:
+        if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "prefill kernel must be 0, 1 or 2");
+        g_prefill_kernel = value;
+        return SW_OK;
     default:
         return fail(SW_ERR_PARAM, "unknown parameter key");
     }
@@ -355,6 +363,7 @@ int sw_get_param(int key, int *value)
     case SW_PARAM_WAVES: *value = g_waves; return SW_OK;
     case SW_PARAM_PREFILL_HEADS: *value = g_prefill_hp; return SW_OK;
     case SW_PARAM_PREFILL_WAVES: *value = g_prefill_qw; return SW_OK;
+    case SW_PARAM_PREFILL_KERNEL: *value = g_prefill_kernel; return SW_OK;
     default: return fail(SW_ERR_PARAM, "unknown parameter key");
     }
 }
@@ -483,8 +492,8 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     int rc = check_shape(n_req, n_kvh, head_dim, max_len);
     if (rc != SW_OK) return rc;
     if (n_tokens < 0 || n_tokens > (1LL << 31)) return fail(SW_ERR_SHAPE, "n_tokens must be in [0, 2^31]");
-    if (head_dim != 128 || n_qh / n_kvh > 8)
-        return fail(SW_ERR_UNSUPPORTED, "the prompt-phase kernel needs head_dim 128 and at most 8 query heads per key/value head");
+    if (head_dim != 128) return fail(SW_ERR_UNSUPPORTED, "the prompt-phase kernels need head_dim 128");
+    if (n_qh / n_kvh > 64) return fail(SW_ERR_UNSUPPORTED, "more than 64 query heads per key/value head");
     if (n_req == 0 || n_tokens == 0) return SW_OK;
     if (!q || !k_cache || !v_cache || !seq_lens || !q_starts || !out)
         return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens, q_starts and out must be non-NULL");
@@ -507,9 +516,24 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     a.group = n_qh / n_kvh;
     a.head_dim = head_dim;
     a.max_len = max_len;
-    sw_prefill_shape(n_req, n_kvh, a.group, max_len, &a.hp, &a.qw);
-    if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) a.hp = g_prefill_hp;
-    if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
+    // Two kernels.  Short and medium prompts are chains of dependent tiles on a mostly
+    // idle chip: the key-split kernel gives every (32 queries, head) pair a whole
+    // workgroup.  Long prompts fill the chip anyway and gain from sharing each staged
+    // tile among the heads of a group.
+    int which = g_prefill_kernel;
+    if (which == 0) which = (a.group > 8 || max_len <= kPrefillSplitMaxLen) ? 2 : 1;
+    if (which == 1 && a.group > 8)
+        return fail(SW_ERR_UNSUPPORTED, "the shared-tile prompt kernel takes at most 8 query heads per key/value head");
+    int split_waves = 4;
+    if (which == 2) {
+        a.hp = 1;
+        a.qw = 1;
+        if (g_prefill_qw == 2 || g_prefill_qw == 4 || g_prefill_qw == 8) split_waves = g_prefill_qw;
+    } else {
+        sw_prefill_shape(n_req, n_kvh, a.group, max_len, &a.hp, &a.qw);
+        if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) a.hp = g_prefill_hp;
+        if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
+    }
     a.n_qblocks = (max_len + 32 * a.qw - 1) / (32 * a.qw);
     a.stride_kvh = slab_elems(head_dim, max_len);
     a.stride_req = a.stride_kvh * n_kvh;
@@ -536,7 +560,8 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
         }
         ev = {rec.ev[0], rec.ev[1]};
     }
-    e = sw_launch_prefill_mfma(a, (hipStream_t)stream_v, prof ? &ev : nullptr);
+    e = which == 2 ? sw_launch_prefill_split(a, split_waves, (hipStream_t)stream_v, prof ? &ev : nullptr)
+                   : sw_launch_prefill_mfma(a, (hipStream_t)stream_v, prof ? &ev : nullptr);
     if (e != hipSuccess) {
         if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
         return fail_hip(e, "kernel launch");

@@ -120,6 +120,7 @@ hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const Sw
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
 void       sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw);
+hipError_t sw_launch_prefill_split(const SwPrefillArgs &a, int waves, hipStream_t stream, const SwLaunchEvents *ev);
 hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 int        sw_kv_copy_rows_per_group();
 hipError_t sw_launch_kv_copy(const SwHandoffArgs &a, bool to_dense, hipStream_t stream, const SwLaunchEvents *ev);

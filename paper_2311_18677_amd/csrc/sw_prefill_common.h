@@ -1,0 +1,183 @@
+// Pieces shared by the two prompt-phase (causal attention) kernels: operand
+// types, the per-query online softmax and the second matrix product, both for a
+// wave that owns 32 query positions (two 16-wide MFMA column blocks) of one head
+// and works on tiles of 32 cached positions.  Lane (n16 = lane % 16, gq = lane / 16)
+// owns query 16*nb + n16 of block nb and, of a tile's scores, positions
+// 16*tb + 4*gq + i.
+#pragma once
+#include "sw_internal.h"
+
+namespace sw_prefill {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+constexpr int   kD         = 128;
+constexpr int   kTile      = 32;             // cached positions per tile
+constexpr int   kRowBytes  = 256;
+constexpr int   kTileBytes = kTile * kRowBytes;       // 8192: one K or one V tile
+constexpr int   kQPerWave  = 32;             // query positions per wave
+constexpr float kNegBig    = -1.0e30f;
+
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (n < 64),
+// leaving the other counters unconstrained; & 0xc07f adds "no LDS operation outstanding".
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+union Frag {
+    uint4_t u;
+    half8_t h;
+};
+
+// Lanes n16, n16+16, n16+32, n16+48 hold parts of one query's row.  Two swap
+// instructions give every one of them the maximum (or the sum) over the four:
+// the first exchanges odd rows of 16 lanes with even ones, the second the upper
+// 32 lanes with the lower.
+__device__ __forceinline__ float quad_rows_max(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+__device__ __forceinline__ float quad_rows_sum(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// The running maximum of a query is only raised when a score exceeds it by more than
+// this many binary orders of magnitude: weights then stay below 2^kLazyBits (exact
+// enough in binary16, whose precision is relative) and the accumulators are rescaled
+// rarely instead of every tile.
+constexpr float kLazyBits = 8.0f;
+
+// Q^T operands of a wave: lane (n16, gq) holds dims 32kk + 8gq .. +7 of query
+// q0 + 16nb + n16.  Rows past the prompt repeat its last row (never stored); row
+// indices are clamped into [0, n_tokens).
+__device__ __forceinline__ void load_q(const SwPrefillArgs &a, long long q_first, int q0, int L, int h,
+                                       int n16, int gq, Frag (&qreg)[2][4])
+{
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        int qpos = q0 + 16 * nb + n16;
+        qpos = qpos < L ? qpos : L - 1;
+        long long row = q_first + qpos;
+        row = row < 0 ? 0 : (row >= a.n_tokens ? a.n_tokens - 1 : row);
+        const uint16_t *src = a.q + (row * a.n_qh + h) * kD + 8 * gq;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qreg[nb][kk].u = *reinterpret_cast<const uint4_t *>(src + 32 * kk);
+    }
+}
+
+// S^T = K Q^T for one tile staged at kb (rows XOR-swizzled by 16-byte piece):
+// two 16-position blocks x two 16-query blocks, four 32-dim steps.
+__device__ __forceinline__ void qk_tile(const unsigned char *kb, const Frag (&qreg)[2][4], int n16, int gq,
+                                        float4_t (&sacc)[2][2])
+{
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) sacc[nb][tb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const int off = n16 * kRowBytes + (((4 * kk + gq) ^ n16) << 4);   // row n16, piece 4kk+gq
+        Frag k0, k1;
+        k0.u = *reinterpret_cast<const uint4_t *>(kb + off);
+        k1.u = *reinterpret_cast<const uint4_t *>(kb + 16 * kRowBytes + off);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0.h, qreg[nb][kk].h, sacc[nb][0], 0, 0, 0);
+            sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1.h, qreg[nb][kk].h, sacc[nb][1], 0, 0, 0);
+        }
+    }
+}
+
+// V rows of a tile staged at vb: lane group gq takes the 8 positions its P operand holds.
+__device__ __forceinline__ void load_v_rows(const unsigned char *vb, int n16, int gq, uint4_t (&vreg)[8])
+{
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        const int row = n < 4 ? 4 * gq + n : 16 + 4 * gq + (n - 4);
+        vreg[n] = *reinterpret_cast<const uint4_t *>(vb + row * kRowBytes + n16 * 16);
+    }
+}
+
+// Online softmax of one tile, base 2, for both query blocks.  m[] is kept in raw score
+// units; the scale enters through one fused multiply-add.  `diagonal`: some position of
+// the tile is later than some query of the wave (q0 = the wave's first query, t0 = the
+// tile's first position).
+__device__ __forceinline__ void softmax_tile(const float4_t (&sacc)[2][2], bool diagonal, int q0, int t0,
+                                             int n16, int gq, float scale_log2e, float lazy_raw,
+                                             float (&m)[2], float (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
+{
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        float s[8];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[4 * tb + i] = sacc[nb][tb][i];
+        if (diagonal) {
+            const int qpos = q0 + 16 * nb + n16;
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (t0 + 16 * tb + 4 * gq + i > qpos) s[4 * tb + i] = -INFINITY;
+        }
+        float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
+                         fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+        mt = quad_rows_max(mt);
+        const bool raise = mt > m[nb] + lazy_raw;
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {       // rare after the first tiles
+            const float m_new = raise ? mt : m[nb];
+            const float alpha = __builtin_amdgcn_exp2f((m[nb] - m_new) * scale_log2e);
+            m[nb] = m_new;
+            l[nb] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[nb][e] *= alpha;
+        }
+        const float neg_m = -m[nb] * scale_log2e;
+        float pj[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            pj[j] = __builtin_amdgcn_exp2f(fmaf(s[j], scale_log2e, neg_m));
+            psum += pj[j];
+        }
+        l[nb] += psum;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const half2_t h2 = __builtin_convertvector((float2_t){pj[2 * j], pj[2 * j + 1]}, half2_t);
+            p[nb].h[2 * j] = h2[0];
+            p[nb].h[2 * j + 1] = h2[1];
+        }
+    }
+}
+
+// O^T += V^T P^T : block e covers dims 8*row + e (row = MFMA row); V^T is built in
+// registers from the V rows with byte permutes.
+__device__ __forceinline__ void pv_tile(const uint4_t (&vreg)[8], const Frag (&p)[2], float4_t (&o)[2][8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int w2 = e >> 1;
+        const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        Frag va;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            va.u[j] = __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], sel);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+            o[nb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, p[nb].h, o[nb][e], 0, 0, 0);
+    }
+}
+
+}  // namespace sw_prefill

@@ -1,0 +1,227 @@
+// Prompt-phase (causal) attention, key-split form for short and medium prompts
+// (gfx950, wave64), head_dim 128.
+//
+// A prompt batch on a prompt machine is capped at about two thousand tokens
+// (paper section 4.2), which at one GPU's share of the heads is only a few
+// hundred (query block, head) pairs: with one wave per pair the chip is mostly
+// idle and every wave walks a long chain of key tiles.  Here the waves of a
+// workgroup share ONE pair -- 32 query positions of one head -- and split its
+// key range instead: wave w takes tiles w, w + W, ...  Each wave stages its own
+// K and V tiles global->LDS and waits on its own counters (no barrier in the
+// loop), exactly like the token-phase kernel; at the end the waves' partial
+// (maximum, sum, accumulator) triples are merged through LDS and the rows are
+// normalised and stored.  The arithmetic per tile is the one of
+// sw_prefill_mfma.hip (shared code in sw_prefill_common.h).
+#include "sw_prefill_common.h"
+
+#include <type_traits>
+
+namespace {
+
+using namespace sw_prefill;
+
+constexpr int kWaveLds = 2 * kTileBytes;     // K tile + V tile; reused for the merge (32 rows x 128 floats)
+
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES)
+void sw_prefill_split_kernel(SwPrefillArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
+    // the block's 32 query rows
+    __shared__ __attribute__((aligned(16))) unsigned char sm_q[kQPerWave * kRowBytes];
+    __shared__ float sm_m[WAVES][kQPerWave];
+    __shared__ float sm_l[WAVES][kQPerWave];
+
+    // blockIdx -> (query block, request, key/value head, query head of the group);
+    // late query blocks see the most positions: they come first in dispatch order
+    const unsigned hh = blockIdx.x % (unsigned)a.group;
+    const unsigned rest = blockIdx.x / (unsigned)a.group;
+    const unsigned n_units = (unsigned)a.n_req * (unsigned)a.n_kvh;
+    const unsigned unit = rest % n_units;
+    const int qb = a.n_qblocks - 1 - (int)(rest / n_units);
+    const int r = (int)(unit / (unsigned)a.n_kvh);
+    const int g = (int)(unit - (unsigned)r * (unsigned)a.n_kvh);
+    int L = a.seq_lens[r];
+    const long long q_first = a.q_starts[r];
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    const int Q0 = qb * kQPerWave;
+    if (Q0 >= L) return;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n16  = lane & 15;
+    const int gq   = lane >> 4;
+    const int h    = g * a.group + (int)hh;
+    unsigned char *wlds = lds + wave * kWaveLds;
+    unsigned char *vlds = wlds + kTileBytes;
+
+    // ---- the block's query rows go global->LDS (pieces XOR-swizzled by row like K's), each
+    // wave fetching its share; every load of the kernel is then of one kind and the waits
+    // below count exactly.  Rows past the prompt repeat its last row (never stored).
+    // (sm_q is filled by global->LDS loads only; one ordinary store keeps the compiler
+    // from treating it as never written)
+    if (threadIdx.x < 16) *reinterpret_cast<uint4_t *>(sm_q + threadIdx.x * 16) = uint4_t{0u, 0u, 0u, 0u};
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int c = 0; c < 8 / WAVES; ++c) {
+        const int j = wave + WAVES * c;                   // rows 4j .. 4j+3
+        const int qi = 4 * j + gq;
+        const int qpos = min(Q0 + qi, L - 1);
+        long long row = q_first + qpos;
+        row = row < 0 ? 0 : (row >= a.n_tokens ? a.n_tokens - 1 : row);
+        const uint16_t *src = a.q + (row * a.n_qh + h) * kD + 8 * (n16 ^ (qi & 15));
+        __builtin_amdgcn_global_load_lds(src, sm_q + j * 1024, 16, 0, 0);
+    }
+
+    const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
+
+    // tiles 0 .. Q0/32 hold every position the block's queries may see; all start inside the prompt
+    const int n_tiles = Q0 / kTile + 1;
+
+    auto issue_k = [&](int t0) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int rho = 4 * n + gq;
+            const int t = min(t0 + rho, L - 1);          // rows past the prompt repeat its last row (masked)
+            const char *src = kslab + (((unsigned)t << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
+            __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, 0);
+        }
+    };
+    auto issue_v = [&](int t0) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int t = min(t0 + 4 * n + gq, L - 1);
+            __builtin_amdgcn_global_load_lds(vslab + (((unsigned)t << 8) | (unsigned)(n16 << 4)),
+                                             vlds + n * 1024, 16, 0, 0);
+        }
+    };
+
+    Frag qreg[2][4];
+    float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
+    const float lazy_raw = kLazyBits / a.scale_log2e;
+    float4_t o[2][8];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[nb][e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // One tile: its loads are in flight on entry (K first, then V).  MORE (compile time)
+    // says whether the wave has a further tile, whose loads are then issued from here,
+    // so that every wait counts exactly which loads are still outstanding.
+    auto process_tile = [&](int t0, int t0_next, auto more_c) {
+        constexpr bool MORE = decltype(more_c)::value;
+        // outstanding, oldest first: K(t0) x8, V(t0) x8
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        float4_t sacc[2][2];
+        qk_tile(wlds, qreg, n16, gq, sacc);
+        if (MORE) {
+            // every read of the K tile has returned before its area is refilled
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            issue_k(t0_next);
+        }
+        Frag p[2];
+        softmax_tile(sacc, t0 + kTile > Q0, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
+        // outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile
+        if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        uint4_t vreg[8];
+        load_v_rows(vlds, n16, gq, vreg);
+        if (MORE) {
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            issue_v(t0_next);
+        }
+        pv_tile(vreg, p, o);
+    };
+
+    int ti = wave;
+    if (ti < n_tiles) {
+        issue_k(ti * kTile);
+        issue_v(ti * kTile);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(16));      // this wave's query rows have landed
+    } else {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+    __builtin_amdgcn_s_barrier();                       // ... and so have the other waves'
+
+    if (ti < n_tiles) {
+        // Q^T operands: lane (n16, gq) holds dims 32kk + 8gq .. +7 of query 16nb + n16
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                qreg[nb][kk].u = *reinterpret_cast<const uint4_t *>(
+                    sm_q + (16 * nb + n16) * kRowBytes + (((4 * kk + gq) ^ n16) << 4));
+        while (ti + WAVES < n_tiles) {
+            process_tile(ti * kTile, (ti + WAVES) * kTile, std::true_type{});
+            ti += WAVES;
+        }
+        process_tile(ti * kTile, 0, std::false_type{});
+    }
+
+    // ---- merge the waves through LDS.  Each wave writes its accumulators over its own
+    // staging area as [query 0..31][dim 0..127] floats (16-byte pieces XOR-swizzled by
+    // query); this lane owns query 16nb + n16, dims 32gq + 8i + e.
+    float *mo = reinterpret_cast<float *>(wlds);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int qi = 16 * nb + n16;
+        const float ls = quad_rows_sum(l[nb]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int piece = 8 * gq + 2 * i + hf;                    // dims 4*piece .. 4*piece+3
+                *reinterpret_cast<float4_t *>(mo + qi * kD + 4 * (piece ^ qi)) =
+                    float4_t{o[nb][4 * hf][i], o[nb][4 * hf + 1][i], o[nb][4 * hf + 2][i], o[nb][4 * hf + 3][i]};
+            }
+        if (gq == 0) {
+            sm_m[wave][qi] = m[nb];
+            sm_l[wave][qi] = ls;
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kQPerWave * (kD / 4); idx += 64 * WAVES) {
+        const int qi = idx >> 5;
+        const int piece = idx & 31;
+        const int qpos = Q0 + qi;
+        const long long row = q_first + qpos;
+        if (qpos >= L || row < 0 || row >= a.n_tokens) continue;
+        float mx = sm_m[0][qi];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) mx = fmaxf(mx, sm_m[w][qi]);
+        float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            const float f = __builtin_amdgcn_exp2f((sm_m[w][qi] - mx) * a.scale_log2e);
+            const float4_t x = *reinterpret_cast<const float4_t *>(
+                reinterpret_cast<const float *>(lds + w * kWaveLds) + qi * kD + 4 * (piece ^ qi));
+#pragma unroll
+            for (int t = 0; t < 4; ++t) num[t] = fmaf(f, x[t], num[t]);
+            den = fmaf(f, sm_l[w][qi], den);
+        }
+        const float inv = 1.0f / den;
+        const half2_t lo = __builtin_convertvector((float2_t){num[0] * inv, num[1] * inv}, half2_t);
+        const half2_t hi = __builtin_convertvector((float2_t){num[2] * inv, num[3] * inv}, half2_t);
+        union { half2_t h[2]; unsigned long long u; } pk;
+        pk.h[0] = lo;
+        pk.h[1] = hi;
+        *reinterpret_cast<unsigned long long *>(reinterpret_cast<_Float16 *>(a.out) + (row * a.n_qh + h) * kD + 4 * piece) = pk.u;
+    }
+}
+
+}  // namespace
+
+hipError_t sw_launch_prefill_split(const SwPrefillArgs &a, int waves, hipStream_t stream, const SwLaunchEvents *ev)
+{
+    if (a.head_dim != kD) return hipErrorNotSupported;
+    const long long blocks = (long long)a.n_req * a.n_qh * a.n_qblocks;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks);
+    if (waves == 8) return sw_launch(sw_prefill_split_kernel<8>, grid, dim3(512), 0, stream, ev, a);
+    if (waves == 4) return sw_launch(sw_prefill_split_kernel<4>, grid, dim3(256), 0, stream, ev, a);
+    if (waves == 2) return sw_launch(sw_prefill_split_kernel<2>, grid, dim3(128), 0, stream, ev, a);
+    return hipErrorInvalidValue;
+}

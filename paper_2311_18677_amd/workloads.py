@@ -156,6 +156,8 @@ PREFILL_CONFIGS = {
     # one long prompt, where the quadratic term dominates
     "prefill_long_8k": Config("prefill_long_8k", 1, 8, 1, 128, 8192, ("fixed", (8192,)),
                               n_layers=80, seed_index=14),
+    "prefill_long_32k": Config("prefill_long_32k", 1, 8, 1, 128, 32768, ("fixed", (32768,)),
+                               n_layers=80, seed_index=15),
 }
 
 

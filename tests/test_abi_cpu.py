@@ -188,7 +188,7 @@ def test_prefill_validation():
     assert pcall(starts=0x5002) == sw.SW_ERR_ALIGN
     assert pcall(out=0x6008) == sw.SW_ERR_ALIGN
     assert pcall(d=64) == sw.SW_ERR_UNSUPPORTED
-    assert pcall(n_qh=16) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(n_qh=65) == sw.SW_ERR_UNSUPPORTED
     assert pcall(n_qh=8, n_kvh=3) == sw.SW_ERR_SHAPE
     assert pcall(n_tokens=-1) == sw.SW_ERR_SHAPE
     assert pcall(max_len=0) == sw.SW_ERR_SHAPE
