@@ -25,6 +25,7 @@
 #include "sw_internal.h"
 #include "sw_worklist.h"
 #include "sw_fused.h"
+#include "sw_lane_ops.h"
 
 #include <type_traits>
 
@@ -41,6 +42,12 @@ constexpr int   kHeadStride = 132;         // floats; merge buffer row = head, 1
 constexpr int   kTileBytes = kTile * kRowBytes;         // 8192
 constexpr int   kWaveLds  = 2 * kTileBytes;             // K tile + V tile; the merge buffer reuses it
 constexpr float kNegBig   = -1.0e30f;
+// A running maximum is raised only when a score exceeds it by more than this many
+// binary orders of magnitude: weights then stay below 2^kLazyBits.
+constexpr float kLazyBits = 8.0f;
+
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 // Cache policy of the K/V stream: non-temporal (read once; must not push the
 // partial results, which are written and read back, out of L2).
 constexpr int   kStream   = 2;
@@ -114,7 +121,8 @@ void sw_partial_mfma2_kernel(SwArgs a)
         __builtin_amdgcn_global_load_lds(src, sm_new, 16, 0, 0);
     }
 
-    float m = kNegBig, l = 0.f;
+    float m = kNegBig, l = 0.f;                        // m in raw score units
+    const float lazy_raw = kLazyBits / a.scale_log2e;  // the raise threshold in raw score units
     float4_t o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -217,12 +225,15 @@ void sw_partial_mfma2_kernel(SwArgs a)
             issue_k(t0_next, nb);
         }
 
-        // ---- online softmax, base 2; this lane: head n16, tokens t0 + 16tb + 4gq + i
+        // ---- online softmax, base 2; this lane: head n16, tokens t0 + 16tb + 4gq + i.
+        // m is kept in raw score units (the scale enters through one fused multiply-add) and
+        // is only raised when a score exceeds it by more than kLazyBits binary orders of
+        // magnitude, so the accumulators are rescaled rarely instead of every tile.
         float s[8];
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s[4 * tb + i] = sacc[tb][i] * a.scale_log2e;
+            for (int i = 0; i < 4; ++i) s[4 * tb + i] = sacc[tb][i];
         // only a wave's last tile can reach past the chunk's end
         const bool ragged = !MORE && t0 + kTile > t_end;
         if (ragged) {
@@ -232,31 +243,39 @@ void sw_partial_mfma2_kernel(SwArgs a)
                 for (int i = 0; i < 4; ++i)
                     if (t0 + 16 * tb + 4 * gq + i >= t_end) s[4 * tb + i] = -INFINITY;
         }
-        float mt = s[0];
+        float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
+                         fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+        mt = quad_rows_max(mt);
+        const bool raise = mt > m + lazy_raw;
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            const float m_new = raise ? mt : m;
+            const float alpha = __builtin_amdgcn_exp2f((m - m_new) * a.scale_log2e);
+            m = m_new;
+            l *= alpha;
 #pragma unroll
-        for (int j = 1; j < 8; ++j) mt = fmaxf(mt, s[j]);
-        mt = fmaxf(mt, __shfl_xor(mt, 16));
-        mt = fmaxf(mt, __shfl_xor(mt, 32));
-        const float m_new = fmaxf(m, mt);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
+            for (int e = 0; e < 8; ++e) o[e] *= alpha;
+        }
+        const float neg_m = -m * a.scale_log2e;
         float p[8];
         float psum = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            p[j] = __builtin_amdgcn_exp2f(s[j] - m_new);
+            p[j] = __builtin_amdgcn_exp2f(fmaf(s[j], a.scale_log2e, neg_m));
             psum += p[j];
         }
-        l = l * alpha + psum;
+        l += psum;
+        // weights as a binary16 pair hi + lo (together ~22 bits)
         Frag phi, plo;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const _Float16 hi = (_Float16)p[j];
-            phi.h[j] = hi;
-            plo.h[j] = (_Float16)(p[j] - (float)hi);
+        for (int j = 0; j < 4; ++j) {
+            const half2_t hi = __builtin_convertvector((float2_t){p[2 * j], p[2 * j + 1]}, half2_t);
+            const half2_t lo = __builtin_convertvector(
+                (float2_t){p[2 * j] - (float)hi[0], p[2 * j + 1] - (float)hi[1]}, half2_t);
+            phi.h[2 * j] = hi[0];
+            phi.h[2 * j + 1] = hi[1];
+            plo.h[2 * j] = lo[0];
+            plo.h[2 * j + 1] = lo[1];
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] *= alpha;
 
         // ---- V(t0): LDS -> registers.  Lane group gq takes the 8 tokens its P operand
         // holds, 4gq .. 4gq+3 and 16+4gq .. 16+4gq+3.
@@ -337,8 +356,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
     }
 
     // ---- the lane groups summed disjoint tokens into l
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    l = quad_rows_sum(l);
 
     // ---- merge the waves through LDS (each wave reuses its own K staging area):
     // row = head (stride 132 floats), column = dim; this lane owns dims
@@ -352,7 +370,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
                 *reinterpret_cast<float4_t *>(mo + n16 * kHeadStride + 32 * gq + 8 * i + 4 * hf) =
                     float4_t{o[4 * hf][i], o[4 * hf + 1][i], o[4 * hf + 2][i], o[4 * hf + 3][i]};
         if (gq == 0) {
-            sm_m[wave][n16] = m;
+            sm_m[wave][n16] = m * a.scale_log2e;       // from here on in scaled (base-2 exponent) units
             sm_l[wave][n16] = l;
         }
     }

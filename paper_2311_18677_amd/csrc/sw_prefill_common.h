@@ -6,6 +6,7 @@
 // 16*tb + 4*gq + i.
 #pragma once
 #include "sw_internal.h"
+#include "sw_lane_ops.h"
 
 namespace sw_prefill {
 
@@ -30,26 +31,6 @@ union Frag {
     uint4_t u;
     half8_t h;
 };
-
-// Lanes n16, n16+16, n16+32, n16+48 hold parts of one query's row.  Two swap
-// instructions give every one of them the maximum (or the sum) over the four:
-// the first exchanges odd rows of 16 lanes with even ones, the second the upper
-// 32 lanes with the lower.
-__device__ __forceinline__ float quad_rows_max(float x)
-{
-    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
-}
-
-__device__ __forceinline__ float quad_rows_sum(float x)
-{
-    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
 
 // The running maximum of a query is only raised when a score exceeds it by more than
 // this many binary orders of magnitude: weights then stay below 2^kLazyBits (exact
