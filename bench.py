@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
+    ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--combine", type=int, default=0)
     ap.add_argument("--paged", type=int, default=0, metavar="BLOCK",
                     help="run the block-table variant with this block size (0 = dense layout)")
     ap.add_argument("--append", action="store_true",
@@ -429,6 +431,8 @@ def main():
     sw.load()
     sw.sw_set_param(sw.SW_PARAM_CHUNK, args.chunk)
     sw.sw_set_param(sw.SW_PARAM_KERNEL, args.kernel)
+    sw.sw_set_param(sw.SW_PARAM_WAVES, args.waves)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, args.combine)
 
     cfg = wl.CONFIGS[args.workload]
     lay = sw.sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)

@@ -309,3 +309,48 @@ def test_repeated_calls_on_cache_resident_data_are_stable(n_qh, n_kvh):
             first = got
             assert_parity(got, ref, cfg.name)
         assert np.array_equal(got.view(np.uint16), first.view(np.uint16)), rep
+
+
+@pytest.mark.parametrize("kernel", [0, 1])
+def test_maximum_context_length(kernel):
+    """max_len at the documented limit of 2^23 positions (a 2 GiB slab per head): one key, placed
+    at the very end / in the middle, is aligned with the query so strongly that every other
+    weight vanishes below binary32 resolution -- the result must be that position's V row."""
+    import torch
+    max_len = 1 << 23
+    lay = sw.sw_kv_layout(1, 1, 128, max_len)
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    k = torch.zeros(lay.total_elems, dtype=torch.float16, device=dev)
+    v = torch.empty(lay.total_elems, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+    q1 = torch.empty(128, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+    q = q1.repeat(8)                                   # the same query in all 8 heads
+    out = torch.full((1, 8, 128), float("nan"), dtype=torch.float16, device=dev)
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    for L, pos in ((max_len, max_len - 1), (max_len, 4_194_305), (max_len - 5, max_len - 6)):
+        k.zero_()
+        k[pos * 128:(pos + 1) * 128] = 4.0 * q1
+        lens = torch.tensor([L], dtype=torch.int32, device=dev)
+        print("max context: L", L, "key at", pos, "kernel", kernel, flush=True)
+        sw.sw_decode_attn(q, k, v, lens, out, 1, 8, 1, 128, max_len)
+        torch.cuda.synchronize()
+        want = v[pos * 128:(pos + 1) * 128].cpu().numpy().view(np.uint16)
+        got = out.cpu().numpy().view(np.uint16)
+        for h in range(8):
+            assert np.array_equal(got[0, h], want), (L, pos, h)
+    del k, v
+    torch.cuda.empty_cache()
+
+
+def test_maximum_number_of_rows():
+    """n_req * n_qh at the documented limit of 2^20 (direct work mapping, a grid of 131072 groups)."""
+    n_req = 1 << 17
+    rng = np.random.Generator(np.random.Philox(7800))
+    lens = rng.integers(0, 5, size=n_req).astype(np.int32)
+    cfg = wl.custom_config("rows", n_req, 8, 1, 128, 4)
+    batch = wl.make_batch(cfg, seed=7800, seq_lens=lens)
+    out, bufs = gpu_out(batch, pad_bits=0x7E00)
+    ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
+    assert_parity(out, ref, cfg.name)
+    assert not out[lens == 0].any()
