@@ -80,6 +80,31 @@ __device__ __forceinline__ void qk_tile(const unsigned char *kb, const Frag (&qr
     }
 }
 
+// The same product in two steps, so that work of the two query blocks can be interleaved:
+// the K operands of a tile (both 16-position blocks, four 32-dim steps) ...
+__device__ __forceinline__ void load_k_ops(const unsigned char *kb, int n16, int gq, Frag (&kop)[2][4])
+{
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const int off = n16 * kRowBytes + (((4 * kk + gq) ^ n16) << 4);
+        kop[0][kk].u = *reinterpret_cast<const uint4_t *>(kb + off);
+        kop[1][kk].u = *reinterpret_cast<const uint4_t *>(kb + 16 * kRowBytes + off);
+    }
+}
+
+// ... and S^T of one query block from them.
+__device__ __forceinline__ void qk_block(int nb, const Frag (&kop)[2][4], const Frag (&qreg)[2][4],
+                                         float4_t (&sacc)[2][2])
+{
+    sacc[nb][0] = float4_t{0.f, 0.f, 0.f, 0.f};
+    sacc[nb][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kop[0][kk].h, qreg[nb][kk].h, sacc[nb][0], 0, 0, 0);
+        sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kop[1][kk].h, qreg[nb][kk].h, sacc[nb][1], 0, 0, 0);
+    }
+}
+
 // V rows of a tile staged at vb: lane group gq takes the 8 positions its P operand holds.
 __device__ __forceinline__ void load_v_rows(const unsigned char *vb, int n16, int gq, uint4_t (&vreg)[8])
 {
@@ -94,12 +119,11 @@ __device__ __forceinline__ void load_v_rows(const unsigned char *vb, int n16, in
 // units; the scale enters through one fused multiply-add.  `diagonal`: some position of
 // the tile is later than some query of the wave (q0 = the wave's first query, t0 = the
 // tile's first position).
-__device__ __forceinline__ void softmax_tile(const float4_t (&sacc)[2][2], bool diagonal, int q0, int t0,
-                                             int n16, int gq, float scale_log2e, float lazy_raw,
-                                             float (&m)[2], float (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
+__device__ __forceinline__ void softmax_block(int nb, const float4_t (&sacc)[2][2], bool diagonal, int q0, int t0,
+                                              int n16, int gq, float scale_log2e, float lazy_raw,
+                                              float (&m)[2], float (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
 {
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    {
         float s[8];
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
@@ -143,22 +167,42 @@ __device__ __forceinline__ void softmax_tile(const float4_t (&sacc)[2][2], bool 
     }
 }
 
-// O^T += V^T P^T : block e covers dims 8*row + e (row = MFMA row); V^T is built in
-// registers from the V rows with byte permutes.
-__device__ __forceinline__ void pv_tile(const uint4_t (&vreg)[8], const Frag (&p)[2], float4_t (&o)[2][8])
+__device__ __forceinline__ void softmax_tile(const float4_t (&sacc)[2][2], bool diagonal, int q0, int t0,
+                                             int n16, int gq, float scale_log2e, float lazy_raw,
+                                             float (&m)[2], float (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
+{
+    softmax_block(0, sacc, diagonal, q0, t0, n16, gq, scale_log2e, lazy_raw, m, l, o, p);
+    softmax_block(1, sacc, diagonal, q0, t0, n16, gq, scale_log2e, lazy_raw, m, l, o, p);
+}
+
+// V^T operands of the second product, built in registers from the V rows with byte
+// permutes: block e covers dims 8*row + e (row = MFMA row).
+__device__ __forceinline__ void build_vt(const uint4_t (&vreg)[8], Frag (&va)[8])
 {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int w2 = e >> 1;
         const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        Frag va;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            va.u[j] = __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], sel);
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-            o[nb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, p[nb].h, o[nb][e], 0, 0, 0);
+            va[e].u[j] = __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], sel);
     }
+}
+
+// O^T += V^T P^T for one query block
+__device__ __forceinline__ void pv_block(int nb, const Frag (&va)[8], const Frag (&p)[2], float4_t (&o)[2][8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        o[nb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[e].h, p[nb].h, o[nb][e], 0, 0, 0);
+}
+
+__device__ __forceinline__ void pv_tile(const uint4_t (&vreg)[8], const Frag (&p)[2], float4_t (&o)[2][8])
+{
+    Frag va[8];
+    build_vt(vreg, va);
+    pv_block(0, va, p, o);
+    pv_block(1, va, p, o);
 }
 
 }  // namespace sw_prefill

@@ -80,21 +80,50 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     // tiles 0 .. Q0/32 hold every position the block's queries may see; all start inside the prompt
     const int n_tiles = Q0 / kTile + 1;
 
-    auto issue_k = [&](int t0) {
+    // Per-lane byte offsets of a tile's load instructions relative to the tile's first row,
+    // computed once: instruction n brings rows 4n .. 4n+3 (lane group gq row 4n+gq, lane n16
+    // one 16-byte piece; K pieces XOR-swizzled by row).  A tile that lies wholly inside the
+    // prompt then needs no per-tile address arithmetic in the vector unit: a wave-uniform
+    // base plus these offsets.  Only a tile that reaches past the prompt's end (the last
+    // one) takes the slow path that clamps every row.
+    unsigned koff[4];
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
-            const int rho = 4 * n + gq;
-            const int t = min(t0 + rho, L - 1);          // rows past the prompt repeat its last row (masked)
-            const char *src = kslab + (((unsigned)t << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
-            __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, 0);
+    for (int n = 0; n < 4; ++n) {
+        const int rho = 4 * n + gq;
+        koff[n] = (unsigned)(rho * kRowBytes + ((n16 ^ (rho & 15)) << 4));     // rows 16..31: + 4096
+    }
+    const unsigned voff = (unsigned)(gq * kRowBytes + n16 * 16);                // instruction n: + 1024 n
+
+    auto issue_k = [&](int t0) {
+        if (t0 + kTile <= L) {
+            // slab base (scalar) + one 32-bit add per instruction (a slab is below 4 GiB)
+            const unsigned tile = (unsigned)t0 << 8;
+#pragma unroll
+            for (int n = 0; n < 8; ++n)
+                __builtin_amdgcn_global_load_lds(kslab + (tile + (n >> 2) * 4096 + koff[n & 3]), wlds + n * 1024, 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                const int rho = 4 * n + gq;
+                const int t = min(t0 + rho, L - 1);      // rows past the prompt repeat its last row (masked)
+                const char *src = kslab + (((unsigned)t << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
+                __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, 0);
+            }
         }
     };
     auto issue_v = [&](int t0) {
+        if (t0 + kTile <= L) {
+            const unsigned tile = (unsigned)t0 << 8;
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
-            const int t = min(t0 + 4 * n + gq, L - 1);
-            __builtin_amdgcn_global_load_lds(vslab + (((unsigned)t << 8) | (unsigned)(n16 << 4)),
-                                             vlds + n * 1024, 16, 0, 0);
+            for (int n = 0; n < 8; ++n)
+                __builtin_amdgcn_global_load_lds(vslab + (tile + n * 1024 + voff), vlds + n * 1024, 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                const int t = min(t0 + 4 * n + gq, L - 1);
+                __builtin_amdgcn_global_load_lds(vslab + (((unsigned)t << 8) | (unsigned)(n16 << 4)),
+                                                 vlds + n * 1024, 16, 0, 0);
+            }
         }
     };
 
@@ -114,15 +143,21 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         constexpr bool MORE = decltype(more_c)::value;
         // outstanding, oldest first: K(t0) x8, V(t0) x8
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        // The two query blocks are independent: the vector-unit work of one is placed
+        // next to the matrix-core work of the other so that the two units overlap.
+        Frag kop[2][4];
+        load_k_ops(wlds, n16, gq, kop);
         float4_t sacc[2][2];
-        qk_tile(wlds, qreg, n16, gq, sacc);
+        qk_block(0, kop, qreg, sacc);
+        qk_block(1, kop, qreg, sacc);
         if (MORE) {
             // every read of the K tile has returned before its area is refilled
             __builtin_amdgcn_s_waitcnt(0xc07f);
             issue_k(t0_next);
         }
+        const bool diagonal = t0 + kTile > Q0;
         Frag p[2];
-        softmax_tile(sacc, t0 + kTile > Q0, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
+        softmax_block(0, sacc, diagonal, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         // outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile
         if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
@@ -132,7 +167,11 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
             __builtin_amdgcn_s_waitcnt(0xc07f);
             issue_v(t0_next);
         }
-        pv_tile(vreg, p, o);
+        Frag va[8];
+        build_vt(vreg, va);
+        pv_block(0, va, p, o);
+        softmax_block(1, sacc, diagonal, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
+        pv_block(1, va, p, o);
     };
 
     int ti = wave;
