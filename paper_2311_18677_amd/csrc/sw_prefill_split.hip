@@ -23,7 +23,7 @@ using namespace sw_prefill;
 constexpr int kWaveLds = 2 * kTileBytes;     // K tile + V tile; reused for the merge (32 rows x 128 floats)
 
 template <int WAVES>
-__global__ __launch_bounds__(64 * WAVES, 8 / WAVES)
+__global__ __launch_bounds__(64 * WAVES, WAVES >= 4 ? 8 / WAVES : 2)
 void sw_prefill_split_kernel(SwPrefillArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
