@@ -159,3 +159,28 @@ def test_prefill_unsupported_shapes_are_refused():
                               check=False) == sw.SW_ERR_UNSUPPORTED
     assert sw.sw_prefill_attn(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 10, 1, 130, 2, 128, 128,
                               check=False) == sw.SW_ERR_UNSUPPORTED
+
+
+def test_prefill_repeated_calls_on_cache_resident_data_are_stable():
+    """A small prompt batch stays in the on-chip caches, so staged tiles come back fast; every
+    call must still give the first call's bits (staging areas are refilled only after the reads
+    of the previous tile have returned)."""
+    import torch
+    lens = [300, 200, 257, 33]
+    cfg = wl.custom_config("pfhot", len(lens), 8, 2, 128, 320)
+    batch = wl.make_batch(cfg, seed=6500, seq_lens=lens)
+    qt, starts = wl.make_prefill_queries(batch)
+    bufs = sw.upload_batch(batch, pad_bits=NAN_BITS)
+    q_d = to_dev(qt)
+    starts_d = torch.from_numpy(starts).to("cuda:0")
+    first = None
+    for rep in range(40):
+        out = torch.full((qt.shape[0], cfg.n_qh, cfg.head_dim), float("nan"), dtype=torch.float16, device="cuda:0")
+        sw.sw_prefill_attn(q_d, bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], starts_d, out,
+                           qt.shape[0], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        if first is None:
+            first = got
+            assert not np.isnan(got.astype(np.float32)).any()
+        assert np.array_equal(got.view(np.uint16), first.view(np.uint16)), rep
