@@ -240,8 +240,9 @@ int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream);
  *   n_tokens   rows of q and out (0 returns SW_OK without touching the device).
  *   head_dim must be 128 (SW_ERR_UNSUPPORTED otherwise); n_qh / n_kvh at most 64.
  * One kernel, no workspace; asynchrony, ownership and the other errors as in
- * sw_decode_attn.  Weights enter the second matrix product as binary16 and the
- * normaliser sums those same rounded weights.
+ * sw_decode_attn.  Weights enter the second matrix product rounded to binary16 (the
+ * normaliser sums them in binary32 before that rounding); results differ from the fp64
+ * definition by about 1e-3 absolute at most for values of order one.
  */
 int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
                     const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,

@@ -16,7 +16,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 
 // prompts up to this many positions go to the key-split prompt kernel by default
 constexpr int kPrefillSplitMaxLen = 16384;
