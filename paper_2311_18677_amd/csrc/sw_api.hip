@@ -59,6 +59,45 @@ struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
 bool g_prof_on = false;
 int g_prof_cap = 0;
 std::vector<ProfRec> g_prof;
+std::vector<hipEvent_t> g_event_pool;   // created by sw_prof_start so that profiled calls stay cheap on the host
+constexpr int kEventPoolRecords = 8192;
+
+// Per-kernel timing of one call.  prof_begin decides whether this call is recorded and, if
+// so, hands out its four events (from the pool while it lasts); after the launches the
+// record is either kept (prof_commit) or its events are destroyed (prof_abort).
+int prof_begin(ProfRec &rec, bool has_combine, bool *active)
+{
+    rec.has_combine = has_combine;
+    *active = false;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_prof_on || (int)g_prof.size() >= g_prof_cap) return SW_OK;
+    for (int i = 0; i < 4; ++i) {
+        if (!g_event_pool.empty()) {
+            rec.ev[i] = g_event_pool.back();
+            g_event_pool.pop_back();
+            continue;
+        }
+        hipError_t e = hipEventCreate(&rec.ev[i]);
+        if (e != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
+            return fail_hip(e, "hipEventCreate");
+        }
+    }
+    *active = true;
+    return SW_OK;
+}
+
+void prof_abort(ProfRec &rec)
+{
+    for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+}
+
+void prof_commit(ProfRec &rec)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
+    else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+}
 
 int check_shape(int n_req, int n_kvh, int head_dim, int max_len)
 {
@@ -140,7 +179,7 @@ int run_step(const StepIn &in)
         kernel = g_kernel;
         combine = g_combine;
         waves = g_waves;
-        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
+        prof = false;
     }
     if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
     // keep the partial kernel's grid below 2^31 workgroups
@@ -258,15 +297,9 @@ int run_step(const StepIn &in)
 
     SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
     ProfRec rec;
-    rec.has_combine = !fused;
+    int prc = prof_begin(rec, !fused, &prof);
+    if (prc != SW_OK) return prc;
     if (prof) {
-        for (int i = 0; i < 4; ++i) {
-            e = hipEventCreate(&rec.ev[i]);
-            if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
-                return fail_hip(e, "hipEventCreate");
-            }
-        }
         ev_p = {rec.ev[0], rec.ev[1]};
         ev_c = {rec.ev[2], rec.ev[3]};
     }
@@ -276,14 +309,10 @@ int run_step(const StepIn &in)
                    : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
     if (e == hipSuccess && !fused) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
     if (e != hipSuccess) {
-        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        if (prof) prof_abort(rec);
         return fail_hip(e, "kernel launch");
     }
-    if (prof) {
-        std::lock_guard<std::mutex> lk(g_mu);
-        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
-        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
-    }
+    if (prof) prof_commit(rec);
     return SW_OK;
 }
 
@@ -375,6 +404,17 @@ int sw_prof_start(int capacity)
     if (capacity <= 0 || capacity > (1 << 20)) return fail(SW_ERR_PARAM, "capacity out of range");
     g_prof.clear();
     g_prof.reserve((size_t)capacity);
+    // events for the first records up front: creating them inside a profiled call would
+    // leave the GPU idle between kernels and distort what is being measured
+    const int pooled = 4 * (capacity < kEventPoolRecords ? capacity : kEventPoolRecords);
+    for (int i = 0; i < pooled; ++i) {
+        hipEvent_t ev;
+        if (hipEventCreate(&ev) != hipSuccess) {
+            (void)hipGetLastError();
+            break;                      // calls fall back to creating their own
+        }
+        g_event_pool.push_back(ev);
+    }
     g_prof_cap = capacity;
     g_prof_on = true;
     return SW_OK;
@@ -402,6 +442,8 @@ int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls)
         for (hipEvent_t ev : rec.ev) (void)hipEventDestroy(ev);
     }
     g_prof.clear();
+    for (hipEvent_t ev : g_event_pool) (void)hipEventDestroy(ev);
+    g_event_pool.clear();
     if (partial_us_sum) *partial_us_sum = p;
     if (combine_us_sum) *combine_us_sum = c;
     if (n_calls) *n_calls = n;
@@ -541,36 +583,20 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     if ((long long)n_req * n_qh * a.n_qblocks > 0x7fffffffLL)
         return fail(SW_ERR_SHAPE, "too many workgroups");
 
-    bool prof;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
-    }
+    bool prof = false;
     SwLaunchEvents ev = {nullptr, nullptr};
     ProfRec rec;
-    rec.has_combine = false;
+    int prc = prof_begin(rec, false, &prof);
+    if (prc != SW_OK) return prc;
+    if (prof) ev = {rec.ev[0], rec.ev[1]};
     hipError_t e;
-    if (prof) {
-        for (int i = 0; i < 4; ++i) {
-            e = hipEventCreate(&rec.ev[i]);
-            if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
-                return fail_hip(e, "hipEventCreate");
-            }
-        }
-        ev = {rec.ev[0], rec.ev[1]};
-    }
     e = which == 2 ? sw_launch_prefill_split(a, split_waves, (hipStream_t)stream_v, prof ? &ev : nullptr)
                    : sw_launch_prefill_mfma(a, (hipStream_t)stream_v, prof ? &ev : nullptr);
     if (e != hipSuccess) {
-        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        if (prof) prof_abort(rec);
         return fail_hip(e, "kernel launch");
     }
-    if (prof) {
-        std::lock_guard<std::mutex> lk(g_mu);
-        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
-        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
-    }
+    if (prof) prof_commit(rec);
     return SW_OK;
 }
 
@@ -619,35 +645,19 @@ static int kv_copy(void *k_pool, void *v_pool, const int32_t *block_table, const
     a.d_stride_req = a.d_stride_kvh * n_kvh;
     if ((long long)n_req * n_kvh * a.n_tiles > 0x7fffffffLL) return fail(SW_ERR_SHAPE, "too many workgroups");
 
-    bool prof;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        prof = g_prof_on && (int)g_prof.size() < g_prof_cap;
-    }
+    bool prof = false;
     SwLaunchEvents ev = {nullptr, nullptr};
     ProfRec rec;
-    rec.has_combine = false;
+    int prc = prof_begin(rec, false, &prof);
+    if (prc != SW_OK) return prc;
+    if (prof) ev = {rec.ev[0], rec.ev[1]};
     hipError_t e;
-    if (prof) {
-        for (int i = 0; i < 4; ++i) {
-            e = hipEventCreate(&rec.ev[i]);
-            if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(rec.ev[j]);
-                return fail_hip(e, "hipEventCreate");
-            }
-        }
-        ev = {rec.ev[0], rec.ev[1]};
-    }
     e = sw_launch_kv_copy(a, to_dense, (hipStream_t)stream_v, prof ? &ev : nullptr);
     if (e != hipSuccess) {
-        if (prof) for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
+        if (prof) prof_abort(rec);
         return fail_hip(e, "kernel launch");
     }
-    if (prof) {
-        std::lock_guard<std::mutex> lk(g_mu);
-        if (g_prof_on && (int)g_prof.size() < g_prof_cap) g_prof.push_back(rec);
-        else for (hipEvent_t x : rec.ev) (void)hipEventDestroy(x);
-    }
+    if (prof) prof_commit(rec);
     return SW_OK;
 }
 
