@@ -105,14 +105,47 @@ __device__ __forceinline__ void qk_block(int nb, const Frag (&kop)[2][4], const 
     }
 }
 
-// V rows of a tile staged at vb: lane group gq takes the 8 positions its P operand holds.
-__device__ __forceinline__ void load_v_rows(const unsigned char *vb, int n16, int gq, uint4_t (&vreg)[8])
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short4_t __attribute__((address_space(3))) *lds_short4_ptr;
+
+// A staged V row keeps its sixteen 16-byte pieces XOR-swizzled by row, in pairs:
+// piece p of row rho sits in slot p ^ v_swizzle(rho).  (Pairs, because the transposing
+// read below takes 8 bytes per lane and two neighbouring lanes share a piece.)
+__device__ __forceinline__ int v_swizzle(int rho) { return (rho & 7) << 1; }
+
+// Byte offsets, inside a staged V tile, of this lane's sixteen transposing reads: entry
+// [hk][e] serves keys 16hk + 4gq .. +3 and dims 16e .. 16e+15.  They depend on the lane
+// only, so a kernel computes them once.
+__device__ __forceinline__ void vt_offsets(int n16, int gq, unsigned (&off)[2][8])
 {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-        const int row = n < 4 ? 4 * gq + n : 16 + 4 * gq + (n - 4);
-        vreg[n] = *reinterpret_cast<const uint4_t *>(vb + row * kRowBytes + n16 * 16);
+    for (int hk = 0; hk < 2; ++hk) {
+        const int rho = 16 * hk + 4 * gq + (n16 >> 2);        // the row whose 8 bytes this lane addresses
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int piece = 2 * e + ((n16 >> 1) & 1);       // dims 16e + 4(n16 % 4) .. +3 live in this piece
+            off[hk][e] = (unsigned)(rho * kRowBytes + ((piece ^ v_swizzle(rho)) << 4) + 8 * (n16 & 1));
+        }
     }
+}
+
+// V^T operands of the second product straight from LDS with the transposing read of
+// gfx950 (ds_read_b64_tr_b16).  Within 16 lanes, result j of lane l is element l % 4 of
+// the 8 bytes that lane 4j + l / 4 addresses; with the addresses of vt_offsets lane
+// (n16, gq) therefore receives V[key 16hk + 4gq + j][dim 16e + n16], j = 0..3 -- exactly
+// the A operand (row = dim 16e + n16, k-slots = the keys this lane group's P operand
+// holds).  Block e covers dims 16e .. 16e+15 (row = MFMA row).
+__device__ __forceinline__ void load_vt(const unsigned char *vb, const unsigned (&off)[2][8], Frag (&va)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int hk = 0; hk < 2; ++hk) {
+            union { short4_t s; unsigned int u[2]; } x;
+            x.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vb + off[hk][e]));
+            va[e].u[2 * hk] = x.u[0];
+            va[e].u[2 * hk + 1] = x.u[1];
+        }
 }
 
 // Online softmax of one tile, base 2, for both query blocks.  m[] is kept in raw score
@@ -175,34 +208,12 @@ __device__ __forceinline__ void softmax_tile(const float4_t (&sacc)[2][2], bool 
     softmax_block(1, sacc, diagonal, q0, t0, n16, gq, scale_log2e, lazy_raw, m, l, o, p);
 }
 
-// V^T operands of the second product, built in registers from the V rows with byte
-// permutes: block e covers dims 8*row + e (row = MFMA row).
-__device__ __forceinline__ void build_vt(const uint4_t (&vreg)[8], Frag (&va)[8])
-{
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int w2 = e >> 1;
-        const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            va[e].u[j] = __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], sel);
-    }
-}
-
 // O^T += V^T P^T for one query block
 __device__ __forceinline__ void pv_block(int nb, const Frag (&va)[8], const Frag (&p)[2], float4_t (&o)[2][8])
 {
 #pragma unroll
     for (int e = 0; e < 8; ++e)
         o[nb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[e].h, p[nb].h, o[nb][e], 0, 0, 0);
-}
-
-__device__ __forceinline__ void pv_tile(const uint4_t (&vreg)[8], const Frag (&p)[2], float4_t (&o)[2][8])
-{
-    Frag va[8];
-    build_vt(vreg, va);
-    pv_block(0, va, p, o);
-    pv_block(1, va, p, o);
 }
 
 }  // namespace sw_prefill

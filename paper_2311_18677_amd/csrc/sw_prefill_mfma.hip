@@ -89,12 +89,14 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
             const bool is_v = j >= 8;
             const int rho = 4 * n + gq;
             const int t = min(t0 + rho, L - 1);                      // rows past the prompt repeat its last row
-            const int piece = is_v ? n16 : (n16 ^ (rho & 15));
+            const int piece = is_v ? (n16 ^ v_swizzle(rho)) : (n16 ^ (rho & 15));
             const char *src = (is_v ? vslab : kslab) + (((unsigned)t << 8) | (unsigned)(piece << 4));
             __builtin_amdgcn_global_load_lds(src, buf + (is_v ? kTileBytes : 0) + n * 1024, 16, 0, 0);
         }
     };
 
+    unsigned vt_off[2][8];
+    vt_offsets(n16, gq, vt_off);
     float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
     const float lazy_raw = kLazyBits / a.scale_log2e;      // the threshold in raw score units
     float4_t o[2][8];
@@ -129,14 +131,15 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 
         float4_t sacc[2][2];
         qk_tile(kb, qreg, n16, gq, sacc);
-        uint4_t vreg[8];
-        load_v_rows(vb, n16, gq, vreg);
+        Frag va[8];
+        load_vt(vb, vt_off, va);
         Frag p[2];
         softmax_tile(sacc, t0 + kTile > qw0, qw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
-        pv_tile(vreg, p, o);
+        pv_block(0, va, p, o);
+        pv_block(1, va, p, o);
     }
 
-    // ---- this lane's query rows: dims 32gq + 8i + e
+    // ---- this lane's query rows: dims 16e + 4gq + i
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const float ls = quad_rows_sum(l[nb]);
@@ -144,13 +147,15 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
         const long long row = q_first + qpos;
         if (qpos < L && row >= 0 && row < a.n_tokens) {
             const float inv = 1.0f / ls;
-            _Float16 *dst = reinterpret_cast<_Float16 *>(a.out) + (row * a.n_qh + h) * kD + 32 * gq;
+            _Float16 *dst = reinterpret_cast<_Float16 *>(a.out) + (row * a.n_qh + h) * kD + 4 * gq;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                Frag x;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) x.h[e] = (_Float16)(o[nb][e][i] * inv);
-                *reinterpret_cast<uint4_t *>(dst + 8 * i) = x.u;
+            for (int e = 0; e < 8; ++e) {
+                const half2_t lo = __builtin_convertvector((float2_t){o[nb][e][0] * inv, o[nb][e][1] * inv}, half2_t);
+                const half2_t hi = __builtin_convertvector((float2_t){o[nb][e][2] * inv, o[nb][e][3] * inv}, half2_t);
+                union { half2_t h[2]; unsigned long long u; } pk;
+                pk.h[0] = lo;
+                pk.h[1] = hi;
+                *reinterpret_cast<unsigned long long *>(dst + 16 * e) = pk.u;
             }
         }
     }

@@ -92,7 +92,15 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         const int rho = 4 * n + gq;
         koff[n] = (unsigned)(rho * kRowBytes + ((n16 ^ (rho & 15)) << 4));     // rows 16..31: + 4096
     }
-    const unsigned voff = (unsigned)(gq * kRowBytes + n16 * 16);                // instruction n: + 1024 n
+    // V pieces are swizzled too (v_swizzle); rows 4n+gq and 4(n+2)+gq share a swizzle
+    unsigned voff[2];
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        const int rho = 4 * n + gq;
+        voff[n] = (unsigned)(rho * kRowBytes + ((n16 ^ v_swizzle(rho)) << 4));   // rows +8, +16, +24: + 2048 each
+    }
+    unsigned vt_off[2][8];
+    vt_offsets(n16, gq, vt_off);
 
     auto issue_k = [&](int t0) {
         if (t0 + kTile <= L) {
@@ -116,12 +124,13 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
             const unsigned tile = (unsigned)t0 << 8;
 #pragma unroll
             for (int n = 0; n < 8; ++n)
-                __builtin_amdgcn_global_load_lds(vslab + (tile + n * 1024 + voff), vlds + n * 1024, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(vslab + (tile + (n >> 1) * 2048 + voff[n & 1]), vlds + n * 1024, 16, 0, 0);
         } else {
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
-                const int t = min(t0 + 4 * n + gq, L - 1);
-                __builtin_amdgcn_global_load_lds(vslab + (((unsigned)t << 8) | (unsigned)(n16 << 4)),
+                const int rho = 4 * n + gq;
+                const int t = min(t0 + rho, L - 1);
+                __builtin_amdgcn_global_load_lds(vslab + (((unsigned)t << 8) | (unsigned)((n16 ^ v_swizzle(rho)) << 4)),
                                                  vlds + n * 1024, 16, 0, 0);
             }
         }
@@ -161,14 +170,12 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         // outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile
         if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        uint4_t vreg[8];
-        load_v_rows(vlds, n16, gq, vreg);
+        Frag va[8];
+        load_vt(vlds, vt_off, va);
         if (MORE) {
             __builtin_amdgcn_s_waitcnt(0xc07f);
             issue_v(t0_next);
         }
-        Frag va[8];
-        build_vt(vreg, va);
         pv_block(0, va, p, o);
         softmax_block(1, sacc, diagonal, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         pv_block(1, va, p, o);
@@ -201,20 +208,17 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 
     // ---- merge the waves through LDS.  Each wave writes its accumulators over its own
     // staging area as [query 0..31][dim 0..127] floats (16-byte pieces XOR-swizzled by
-    // query); this lane owns query 16nb + n16, dims 32gq + 8i + e.
+    // query); this lane owns query 16nb + n16, dims 16e + 4gq + i.
     float *mo = reinterpret_cast<float *>(wlds);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const int qi = 16 * nb + n16;
         const float ls = quad_rows_sum(l[nb]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const int piece = 8 * gq + 2 * i + hf;                    // dims 4*piece .. 4*piece+3
-                *reinterpret_cast<float4_t *>(mo + qi * kD + 4 * (piece ^ qi)) =
-                    float4_t{o[nb][4 * hf][i], o[nb][4 * hf + 1][i], o[nb][4 * hf + 2][i], o[nb][4 * hf + 3][i]};
-            }
+        for (int e = 0; e < 8; ++e) {
+            const int piece = 4 * e + gq;                                 // dims 4*piece .. 4*piece+3
+            *reinterpret_cast<float4_t *>(mo + qi * kD + 4 * (piece ^ qi)) = o[nb][e];
+        }
         if (gq == 0) {
             sm_m[wave][qi] = m[nb];
             sm_l[wave][qi] = ls;
