@@ -141,12 +141,15 @@ int default_kernel(const SwArgs &a)
     return sw_partial_mfma_supported(a) && !a.block_table && !a.k_new ? 2 : 1;
 }
 
-// Whether the last workgroup of each unit merges the chunks itself (one launch)
-// or a second kernel does.  The second kernel measured faster on every shape.
-bool default_fused(int n_req, int n_kvh, int max_len)
+// Whether the last workgroup of each unit merges the chunks itself (one launch) or a
+// second kernel does.  One launch saves a dispatch (about half a microsecond of a call
+// that takes 7-12 us on short contexts) but its merge runs behind a ticket taken at the
+// device's coherence point and reads the other chunks from there: measured faster while
+// a request has at most 8 chunks (one round of loads), slower beyond.  The choice
+// depends on max_len alone (through the chunk length), never on the batch.
+bool default_fused(int n_chunks)
 {
-    (void)n_req; (void)n_kvh; (void)max_len;
-    return false;
+    return n_chunks <= 8;
 }
 
 // Everything one step needs, dense or block-table.
@@ -237,7 +240,7 @@ int run_step(const StepIn &in)
     if (which == 2 && in.block_table)
         return fail(SW_ERR_UNSUPPORTED, "the register-staged matrix-core kernel has no block-table form");
 
-    const bool fused = combine == 0 ? default_fused(n_req, n_kvh, max_len) : combine == 2;
+    const bool fused = combine == 0 ? default_fused(n_chunks) : combine == 2;
 
     // ---- workspace: slots of (head_dim + 2) floats per (request, query head, chunk) ----
     int dev = 0;

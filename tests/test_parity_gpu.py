@@ -267,11 +267,18 @@ def test_prof_reports_kernel_times():
     bufs = sw.upload_batch(batch)
     sw.run_batch(bufs, batch.cfg)
     torch.cuda.synchronize()
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, 1)          # two kernels: both are timed
     sw.sw_prof_start(3)
     for _ in range(5):
         sw.run_batch(bufs, batch.cfg)
     p, c, n = sw.sw_prof_stop()
     assert n == 3 and 0 < p < 1e5 and 0 < c < 1e5
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, 2)          # single launch: there is no second kernel
+    sw.sw_prof_start(4)
+    for _ in range(4):
+        sw.run_batch(bufs, batch.cfg)
+    p, c, n = sw.sw_prof_stop()
+    assert n == 4 and 0 < p < 1e5 and c == 0
 
 
 def test_sampled_outputs_at_full_size_in_bench_configuration():
