@@ -58,6 +58,18 @@ __device__ __forceinline__ void sw_store_partial2(float *p, float x, float y, bo
     else *reinterpret_cast<sw_float2_t *>(p) = sw_float2_t{x, y};
 }
 
+// A request with a single chunk needs no merge at all: in the single-launch variant its
+// workgroup normalises and writes the output rows itself (the same arithmetic the merge
+// would do with one chunk, so the same bits), and takes no ticket.
+template <int D>
+__device__ __forceinline__ void sw_store_final4(const SwArgs &a, long long rh, int j4, sw_float4_t num, float den)
+{
+    sw_half4_t res;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) res[t] = (_Float16)(num[t] / den);   // round to nearest even
+    *reinterpret_cast<sw_half4_t *>(reinterpret_cast<_Float16 *>(a.out) + rh * D + 4 * j4) = res;
+}
+
 // Called by every thread of the workgroup after its partial-result stores.
 //   r, g, hh_first, n_heads : heads hh_first .. hh_first + n_heads - 1 of the group of
 //                         key/value head g of request r

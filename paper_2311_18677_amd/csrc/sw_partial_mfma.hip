@@ -281,6 +281,8 @@ void sw_partial_mfma_kernel(SwArgs a)
         }
     }
     __syncthreads();
+    // single-launch variant: a request of one chunk is finished here
+    const bool alone = FUSED && w.L <= a.chunk;
     for (int idx = threadIdx.x; idx < a.group * (kD / 4); idx += 64 * WAVES) {
         const int hh = idx >> 5;
         const int j4 = idx & 31;
@@ -298,11 +300,15 @@ void sw_partial_mfma_kernel(SwArgs a)
             for (int t = 0; t < 4; ++t) num[t] = fmaf(f, x[t], num[t]);
             den = fmaf(f, sm_l[w][hh], den);
         }
+        if (alone) {
+            sw_store_final4<kD>(a, (long long)r * a.n_qh + g * a.group + hh, j4, num, den);
+            continue;
+        }
         const long long slot = sw_ws_slot(a, r, g, c, hh);
         sw_store_partial4(a.ws_o + slot * kD + 4 * j4, num, FUSED);
         if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, FUSED);
     }
-    if (FUSED)
+    if (FUSED && !alone)
         sw_fused_tail<kD>(a, r, g, 0, a.group, (w.L + a.chunk - 1) >> a.chunk_shift,
                           a.counters + (r * a.n_kvh + g), &sm_flag);
 }

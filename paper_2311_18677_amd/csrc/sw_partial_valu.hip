@@ -214,6 +214,8 @@ void sw_partial_valu_kernel(SwArgs a)
         }
     }
     __syncthreads();
+    // single-launch variant: a request of one chunk is finished here
+    const bool alone = fused && w.L <= a.chunk;
     for (int idx = threadIdx.x; idx < n_valid * (D / 4); idx += 64 * kWaves) {
         const int hh = idx / (D / 4);
         const int j4 = idx - hh * (D / 4);
@@ -229,11 +231,15 @@ void sw_partial_valu_kernel(SwArgs a)
             for (int t = 0; t < 4; ++t) num[t] = fmaf(f, sm_o[w2][hh][4 * j4 + t], num[t]);
             den = fmaf(f, sm_l[w2][hh], den);
         }
+        if (alone) {
+            sw_store_final4<D>(a, (long long)r * a.n_qh + h0 + hh, j4, num, den);
+            continue;
+        }
         const long long slot = sw_ws_slot(a, r, g, c, ht * GT + hh);
         sw_store_partial4(a.ws_o + slot * D + 4 * j4, num, fused);
         if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, fused);
     }
-    if (fused) {
+    if (fused && !alone) {
         const int tiles = (a.group + GT - 1) / GT;
         sw_fused_tail<D>(a, r, g, ht * GT, n_valid, (w.L + a.chunk - 1) >> a.chunk_shift,
                          a.counters + ((long long)(r * a.n_kvh + g) * tiles + ht), &sm_flag);
