@@ -68,6 +68,47 @@ class PiecewiseLinearModel:
         return self._design(batch, context) @ self.coef
 
 
+class RegimeModel:
+    """Separate piece-wise linear surfaces per context regime (discontinuous at the breaks).
+
+    The library changes how it works at fixed context limits (one chunk per request up to
+    256 positions, a single launch up to 2048, longer chunks beyond 4096), and the call time
+    steps there; a continuous model would smear each step over a whole knot interval.
+    regimes: list of (upper context bound inclusive, context knots inside the regime).
+    """
+
+    def __init__(self, batch_knots, regimes):
+        self.regimes = [(float(hi), PiecewiseLinearModel(batch_knots, ck)) for hi, ck in regimes]
+
+    def _which(self, context):
+        context = np.asarray(context, dtype=np.float64)
+        idx = np.zeros(context.shape, dtype=np.int64)
+        for i, (hi, _) in enumerate(self.regimes[:-1]):
+            idx[context > hi] = i + 1
+        return idx
+
+    def fit(self, batch, context, t):
+        batch, context, t = (np.asarray(x, dtype=np.float64) for x in (batch, context, t))
+        idx = self._which(context)
+        for i, (_, m) in enumerate(self.regimes):
+            sel = idx == i
+            if sel.any():
+                m.fit(batch[sel], context[sel], t[sel])
+        return self
+
+    def predict(self, batch, context):
+        batch, context = (np.asarray(x, dtype=np.float64) for x in (batch, context))
+        idx = self._which(context)
+        out = np.zeros(batch.shape)
+        for i, (_, m) in enumerate(self.regimes):
+            sel = idx == i
+            if sel.any():
+                if m.coef is None:
+                    raise RuntimeError("regime %d was never fitted" % i)
+                out[sel] = m.predict(batch[sel], context[sel])
+        return out
+
+
 def mape(pred, true):
     pred, true = np.asarray(pred, dtype=np.float64), np.asarray(true, dtype=np.float64)
     return float(np.mean(np.abs(pred - true) / np.abs(true))) * 100.0
@@ -80,11 +121,18 @@ def split_80_20(n, seed=0):
     return np.sort(order[n_test:]), np.sort(order[:n_test])
 
 
-def evaluate(batch, context, t, batch_knots, context_knots, seed=0):
-    """Fit on 80 %, report MAPE on the held-out 20 % and on the training points."""
+def evaluate(batch, context, t, batch_knots, context_knots, seed=0, regimes=None):
+    """Fit on 80 %, report MAPE on the held-out 20 % and on the training points.
+
+    With `regimes` (see RegimeModel) the context axis is cut there and context_knots is unused.
+    """
     batch, context, t = (np.asarray(x, dtype=np.float64) for x in (batch, context, t))
     tr, te = split_80_20(batch.size, seed)
-    m = PiecewiseLinearModel(batch_knots, context_knots).fit(batch[tr], context[tr], t[tr])
+    if regimes is not None:
+        m = RegimeModel(batch_knots, regimes)
+    else:
+        m = PiecewiseLinearModel(batch_knots, context_knots)
+    m.fit(batch[tr], context[tr], t[tr])
     return {"train_mape": mape(m.predict(batch[tr], context[tr]), t[tr]),
             "test_mape": mape(m.predict(batch[te], context[te]), t[te]),
             "n_train": int(tr.size), "n_test": int(te.size), "model": m}
@@ -97,6 +145,10 @@ CONTEXTS = (128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 81
 # knots at the powers of two; the profile grid also has the points half-way between them
 BATCH_KNOTS = (1, 2, 4, 8, 16, 32, 64, 128)
 CONTEXT_KNOTS = (128, 256, 512, 1024, 2048, 4096, 8192)
+# where sw_decode_attn's call time steps (context = max_len): one chunk per request up to 256
+# positions, a single launch up to 2048, two kernels beyond; context knots inside each regime
+REGIMES = ((256, (128, 256)), (2048, (384, 1024, 2048)), (8192, (3072, 4096, 6144, 8192)))
+REGIME_BATCH_KNOTS = (1, 8, 16, 32, 64, 128)
 
 
 def measure_point(sw, torch, n_req, ctx, n_qh=8, n_kvh=1, d=128, calls=1500, budget_bytes=1 << 30):
@@ -183,9 +235,11 @@ def main(argv=None):
     if not path:
         ap.error("give --sweep FILE or --fit FILE")
     b, c, t = load_points(path)
-    res = evaluate(b, c, t, BATCH_KNOTS, CONTEXT_KNOTS, seed=args.seed)
+    res = evaluate(b, c, t, REGIME_BATCH_KNOTS, None, seed=args.seed, regimes=REGIMES)
     print("points %d (train %d, test %d)  train MAPE %.2f %%  held-out MAPE %.2f %%"
           % (b.size, res["n_train"], res["n_test"], res["train_mape"], res["test_mape"]))
+    one = evaluate(b, c, t, BATCH_KNOTS, CONTEXT_KNOTS, seed=args.seed)
+    print("(one continuous surface instead of one per regime: held-out MAPE %.2f %%)" % one["test_mape"])
     return 0
 
 

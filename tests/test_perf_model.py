@@ -56,3 +56,20 @@ def test_split_is_seeded_and_disjoint_and_mape_is_a_percentage():
     assert len(te) == 10 and len(tr) == 40 and not set(tr) & set(te)
     assert set(tr) | set(te) == set(range(50))
     assert pm.mape([110.0, 90.0], [100.0, 100.0]) == pytest.approx(10.0)
+
+
+def test_regime_model_fits_a_surface_with_steps_at_the_breaks():
+    rng = np.random.Generator(np.random.Philox(5))
+    b = 2.0 ** rng.uniform(0, 7, 600)
+    c = 2.0 ** rng.uniform(7, 13, 600)
+
+    def truth(b, c):
+        base = 3.0 + 0.002 * b * np.log2(c)                      # smooth part
+        return base + np.where(c > 256, 2.0, 0.0) + np.where(c > 2048, 1.5, 0.0)   # steps at the breaks
+    t = truth(b, c)
+    res = pm.evaluate(b, c, t, pm.REGIME_BATCH_KNOTS, None, seed=1, regimes=pm.REGIMES)
+    one = pm.evaluate(b, c, t, pm.BATCH_KNOTS, pm.CONTEXT_KNOTS, seed=1)
+    assert res["test_mape"] < 1.5 and res["test_mape"] < 0.5 * one["test_mape"]
+    m = res["model"]
+    lo, hi = m.predict([8.0, 8.0], [256.0, 257.0])
+    assert hi - lo > 1.5                                          # the step is kept, not smeared
