@@ -78,6 +78,12 @@ def _load():
         lib.sw_oracle_kv_span_plan.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.sw_oracle_mixed_attn.restype = ctypes.c_int
+        lib.sw_oracle_mixed_attn.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
         lib.sw_oracle_half_to_double.restype = ctypes.c_double
         lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
         lib.sw_oracle_max_threads.restype = ctypes.c_int
@@ -311,3 +317,35 @@ def kv_span_plan(block_table, seq_lens, n_req, block_size, max_blocks, n_blocks,
     if rc < 0:
         raise ValueError("sw_oracle_kv_span_plan rejected its arguments (code %d)" % rc)
     return first, count, n
+
+
+def mixed_attn(q, k, v, seq_lens, q_starts, q_lens, n_req, n_qh, n_kvh, head_dim, max_len, max_q_len,
+               stride_req, stride_kvh, stride_tok, n_threads=0, return_threads=False):
+    """Mixed-batch causal attention: request r's last q_lens[r] tokens are its queries (rows
+    q_starts[r] .. of q).  Returns ref float64 [n_tokens, n_qh, head_dim] (rows of no query are 0)."""
+    lib = _load()
+    q = _as_u16(q, "q")
+    k = _as_u16(k, "k")
+    v = _as_u16(v, "v")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    starts = np.ascontiguousarray(np.asarray(q_starts, dtype=np.int32))
+    qlens = np.ascontiguousarray(np.asarray(q_lens, dtype=np.int32))
+    if lens.size != n_req or starts.size != n_req or qlens.size != n_req:
+        raise ValueError("seq_lens / q_starts / q_lens need n_req entries")
+    if q.size % (n_qh * head_dim):
+        raise ValueError("q is not a whole number of token rows")
+    n_tokens = q.size // (n_qh * head_dim)
+    need = 0
+    if n_req > 0:
+        need = ((n_req - 1) * stride_req + (n_kvh - 1) * stride_kvh
+                + (max_len - 1) * stride_tok + head_dim)
+    if k.size < need or v.size < need:
+        raise ValueError("k/v buffers are smaller than the strides address")
+    ref = np.zeros((n_tokens, n_qh, head_dim), dtype=np.float64)
+    rc = lib.sw_oracle_mixed_attn(q.ctypes.data, k.ctypes.data, v.ctypes.data, lens.ctypes.data,
+                                  starts.ctypes.data, qlens.ctypes.data, ref.ctypes.data, n_req, n_qh,
+                                  n_kvh, head_dim, max_len, max_q_len, n_tokens, stride_req,
+                                  stride_kvh, stride_tok, int(n_threads))
+    if rc < 0:
+        raise ValueError("sw_oracle_mixed_attn rejected its arguments (code %d)" % rc)
+    return (ref, rc) if return_threads else ref

@@ -347,19 +347,34 @@ int sw_oracle_kv_append_paged(const uint16_t *k_new, const uint16_t *v_new,
  * masked dense matrix formulation; rows do not depend on later positions
  * (tests/test_oracle_pins.py).
  */
-int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
-                           const int32_t *seq_lens, const int32_t *q_starts, double *ref,
-                           int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int64_t n_tokens,
-                           int64_t stride_req, int64_t stride_kvh, int64_t stride_tok,
-                           int n_threads)
+/*
+ * Mixed batch (section 2.4, "mixed batching": prompt and token phases run together in
+ * one forward pass): request r contributes its LAST nq_r tokens as queries,
+ * nq_r = clamp(q_lens[r], 0, min(L_r, max_q_len)); query i is the token at position
+ * L_r - nq_r + i and sees cached positions 0 .. L_r - nq_r + i.  nq_r = L_r is a whole
+ * prompt, nq_r = 1 a token-phase request, anything between a prompt processed in pieces.
+ * q_lens == NULL means nq_r = L_r for every request (the prompt phase above).
+ * Still one attend_one per (request, head, query token).
+ * Pins: nq = L is the prompt routine; nq = 1 is sw_oracle_decode_attn; a prompt in two
+ * pieces gives the rows of the prompt in one piece, bit for bit (tests/test_oracle_pins.py).
+ */
+int sw_oracle_mixed_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                         const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                         double *ref,
+                         int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int max_q_len,
+                         int64_t n_tokens,
+                         int64_t stride_req, int64_t stride_kvh, int64_t stride_tok,
+                         int n_threads)
 {
-    if (n_req < 0 || n_qh <= 0 || n_kvh <= 0 || head_dim <= 0 || max_len <= 0 || n_tokens < 0) return -1;
+    if (n_req < 0 || n_qh <= 0 || n_kvh <= 0 || head_dim <= 0 || max_len <= 0 || max_q_len <= 0 ||
+        n_tokens < 0) return -1;
     if (n_qh % n_kvh != 0) return -2;
     if (n_req == 0) return 1;
     if (!q || !k || !v || !seq_lens || !q_starts || !ref) return -3;
     for (int r = 0; r < n_req; ++r) {
         int L = clampi(seq_lens[r], 0, max_len);
-        if (L > 0 && (q_starts[r] < 0 || (int64_t)q_starts[r] + L > n_tokens)) return -5;
+        int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
+        if (nq > 0 && (q_starts[r] < 0 || (int64_t)q_starts[r] + nq > n_tokens)) return -5;
     }
     const int group = n_qh / n_kvh;
     int used = 1;
@@ -383,6 +398,8 @@ int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t 
         }
         for (int r = 0; r < n_req; ++r) {
             int L = clampi(seq_lens[r], 0, max_len);
+            int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
+            int p0 = L - nq;                                 /* position of the first query token */
             for (int h = 0; h < n_qh; ++h) {
                 int g = h / group;
                 const uint16_t *kg = k + (int64_t)r * stride_req + (int64_t)g * stride_kvh;
@@ -390,10 +407,10 @@ int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t 
 #ifdef _OPENMP
 #pragma omp for schedule(dynamic, 4) nowait
 #endif
-                for (int i = 0; i < L; ++i) {
+                for (int i = 0; i < nq; ++i) {
                     if (!scores) continue;
                     int64_t row = ((int64_t)q_starts[r] + i) * n_qh + h;
-                    attend_one(q + row * head_dim, kg, vg, i + 1, head_dim, stride_tok, scores,
+                    attend_one(q + row * head_dim, kg, vg, p0 + i + 1, head_dim, stride_tok, scores,
                                ref + row * head_dim, NULL, NULL);
                 }
             }
@@ -401,6 +418,17 @@ int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t 
         free(scores);
     }
     return failed ? -4 : used;
+}
+
+int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                           const int32_t *seq_lens, const int32_t *q_starts, double *ref,
+                           int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int64_t n_tokens,
+                           int64_t stride_req, int64_t stride_kvh, int64_t stride_tok,
+                           int n_threads)
+{
+    return sw_oracle_mixed_attn(q, k, v, seq_lens, q_starts, NULL, ref, n_req, n_qh, n_kvh, head_dim,
+                                max_len, max_len, n_tokens, stride_req, stride_kvh, stride_tok,
+                                n_threads);
 }
 
 /*

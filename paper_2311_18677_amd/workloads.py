@@ -177,6 +177,31 @@ def make_prefill_queries(batch, seed=None):
     return q, starts
 
 
+def make_mixed_queries(batch, q_lens, seed=None):
+    """Queries of a mixed batch: request r contributes its last q_lens[r] tokens (clamped to its
+    valid length), packed request after request.
+
+    Returns (q_tokens float16 [n_tokens, n_qh, head_dim], q_starts int32 [n_req], q_lens int32 as
+    clamped).
+    """
+    cfg = batch.cfg
+    nq = np.minimum(np.clip(np.asarray(q_lens, dtype=np.int64), 0, None), batch.valid_lens.astype(np.int64))
+    starts = np.concatenate([[0], np.cumsum(nq)[:-1]]).astype(np.int32)
+    n_tokens = int(nq.sum())
+    ss = np.random.SeedSequence([int(batch.seed if seed is None else seed), 0x6D697864])
+    rng = np.random.Generator(np.random.Philox(ss))
+    q = rng.standard_normal((n_tokens, cfg.n_qh, cfg.head_dim), dtype=np.float32).astype(np.float16)
+    return q, starts, nq.astype(np.int32)
+
+
+def mixed_flops(cfg, lens, q_lens):
+    """Algorithmic flops of a mixed batch: 4*head_dim per (query, visible key) pair and head."""
+    lens = np.clip(np.asarray(lens, dtype=np.int64), 0, cfg.max_len)
+    nq = np.minimum(np.clip(np.asarray(q_lens, dtype=np.int64), 0, None), lens)
+    pairs = int((nq * (lens - nq) + nq * (nq + 1) // 2).sum())
+    return 4 * cfg.head_dim * pairs * cfg.n_qh
+
+
 def prefill_flops(cfg, lens):
     """Algorithmic flops of causal attention: 4*head_dim per (query, visible key) pair and head."""
     lens = np.clip(np.asarray(lens, dtype=np.int64), 0, cfg.max_len)

@@ -525,3 +525,39 @@ def test_kv_span_plan_matches_brute_force():
         assert count[r, :n[r]].sum() == len(ids)
     assert n[4] == 1 and n[5] == 3 and n[0] == 0
     assert first[6, :3].tolist() == [63, 63, 0] and count[6, :3].tolist() == [1, 1, 2]
+
+
+# ---- mixed batch: the last q_lens tokens of every request are queries ----
+
+def test_mixed_batch_reduces_to_prompt_phase_and_to_token_phase():
+    cfg, b, qt, starts, k, v, (sr, sg, st), ref = _prefill_case(4, 2, 64, 24, [24, 1, 0, 9], 101)
+    lens = b.seq_lens
+    # all tokens as queries: the prompt routine
+    full = oracle.mixed_attn(qt, k, v, lens, starts, lens, 4, 4, 2, 64, 24, 24, sr, sg, st)
+    assert np.array_equal(full, ref)
+    # one query per request: the token-phase step on the same cache
+    q1 = np.stack([qt[starts[r] + max(int(L) - 1, 0)] if L > 0 else np.zeros((4, 64), np.float16)
+                   for r, L in enumerate(lens)])
+    dec = oracle.decode_attn(q1, k, v, lens, 4, 4, 2, 64, 24, sr, sg, st)
+    one = oracle.mixed_attn(q1, k, v, lens, [0, 1, 2, 3], [1, 1, 1, 1], 4, 4, 2, 64, 24, 24, sr, sg, st)
+    assert np.array_equal(one[[0, 1, 3]], dec[[0, 1, 3]]) and not one[2].any()
+
+
+def test_a_prompt_in_two_pieces_gives_the_rows_of_the_prompt_in_one_piece():
+    cfg, b, qt, starts, k, v, (sr, sg, st), ref = _prefill_case(4, 4, 64, 40, [40, 23], 102)
+    # piece 1: the first 17 (resp. 10) tokens; piece 2: the rest, with the whole prompt cached
+    cut = np.array([17, 10], np.int32)
+    q_a = np.concatenate([qt[0:17], qt[40:50]])
+    a = oracle.mixed_attn(q_a, k, v, cut, [0, 17], cut, 2, 4, 4, 64, 40, 40, sr, sg, st)
+    q_b = np.concatenate([qt[17:40], qt[50:63]])
+    bq = np.array([23, 13], np.int32)
+    bb = oracle.mixed_attn(q_b, k, v, b.seq_lens, [0, 23], bq, 2, 4, 4, 64, 40, 40, sr, sg, st)
+    assert np.array_equal(a[:17], ref[0:17]) and np.array_equal(a[17:], ref[40:50])
+    assert np.array_equal(bb[:23], ref[17:40]) and np.array_equal(bb[23:], ref[50:63])
+    # q_lens above the length or above max_q_len are clamped; negative counts give no rows
+    c = oracle.mixed_attn(qt[:8], k, v, [5, 3], [0, 5], [99, 3], 2, 4, 4, 64, 40, 40, sr, sg, st)
+    d = oracle.mixed_attn(qt[:8], k, v, [5, 3], [0, 5], [5, 3], 2, 4, 4, 64, 40, 40, sr, sg, st)
+    assert np.array_equal(c, d)
+    e = oracle.mixed_attn(qt[:8], k, v, [5, 3], [0, 2], [99, -4], 2, 4, 4, 64, 40, 2, sr, sg, st)
+    f = oracle.mixed_attn(qt[:8], k, v, [5, 3], [0, 2], [2, 0], 2, 4, 4, 64, 40, 40, sr, sg, st)
+    assert np.array_equal(e, f) and not e[2:].any()
