@@ -172,20 +172,37 @@ def main_prefill(args):
     sw.sw_set_param(sw.SW_PARAM_PREFILL_HEADS, args.prefill_heads)
     sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, args.prefill_waves)
     sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, args.prefill_kernel)
-    name = args.workload if args.workload.startswith("prefill_") else "prefill_llama70b_tp8"
-    cfg = wl.PREFILL_CONFIGS[name]
-    batch0 = wl.make_batch(cfg)
-    qt0, starts0 = wl.make_prefill_queries(batch0)
+    mixed = args.workload.startswith("mixed_")
+    if mixed:
+        # prompt and token phases of different requests in one call (sw_mixed_attn)
+        name = args.workload
+        cfg = wl.MIXED_CONFIGS[name][0]
+        batch0, qlens0 = wl.make_mixed_batch(name)
+        qt0, starts0, qlens0 = wl.make_mixed_queries(batch0, qlens0)
+        flops = wl.mixed_flops(cfg, batch0.seq_lens, qlens0)
+        max_q = int(qlens0.max())
+    else:
+        name = args.workload if args.workload.startswith("prefill_") else "prefill_llama70b_tp8"
+        cfg = wl.PREFILL_CONFIGS[name]
+        batch0 = wl.make_batch(cfg)
+        qt0, starts0 = wl.make_prefill_queries(batch0)
+        flops = wl.prefill_flops(cfg, batch0.seq_lens)
     n_tokens = qt0.shape[0]
-    flops = wl.prefill_flops(cfg, batch0.seq_lens)
     n_sets = args.sets or 4
     sets = []
     for i in range(n_sets):
-        b = batch0 if i == 0 else wl.make_batch(cfg, seed=batch0.seed + 100 + i)
-        qt = qt0 if i == 0 else wl.make_prefill_queries(b)[0]
+        # the other sets: the same lengths (so that one q_starts array serves all), other values
+        b = batch0 if i == 0 else wl.make_batch(cfg, seed=batch0.seed + 100 + i,
+                                                seq_lens=list(batch0.seq_lens) if mixed else None)
+        if mixed:
+            qt = qt0 if i == 0 else wl.make_mixed_queries(b, qlens0)[0]
+        else:
+            qt = qt0 if i == 0 else wl.make_prefill_queries(b)[0]
         bufs = sw.upload_batch(b, device="cuda:0", pad_bits=0)
         bufs["qt"] = torch.from_numpy(qt.view(np.int16).reshape(-1)).to(dev).view(torch.float16)
         bufs["starts"] = torch.from_numpy(starts0).to(dev)
+        if mixed:
+            bufs["qlens"] = torch.from_numpy(qlens0).to(dev)
         bufs["pout"] = torch.zeros((n_tokens, cfg.n_qh, cfg.head_dim), dtype=torch.float16, device=dev)
         if i:
             bufs.pop("k_host"), bufs.pop("v_host")
@@ -194,8 +211,13 @@ def main_prefill(args):
     stream = torch.cuda.Stream(device=dev)
 
     def call(s, st):
-        sw.sw_prefill_attn(s["qt"], s["k_cache"], s["v_cache"], s["seq_lens"], s["starts"], s["pout"],
-                           n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
+        if mixed:
+            sw.sw_mixed_attn(s["qt"], s["k_cache"], s["v_cache"], s["seq_lens"], s["starts"], s["qlens"],
+                             s["pout"], n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                             cfg.max_len, max_q, st)
+        else:
+            sw.sw_prefill_attn(s["qt"], s["k_cache"], s["v_cache"], s["seq_lens"], s["starts"], s["pout"],
+                               n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
 
     call(sets[0], stream)
     stream.synchronize()
@@ -233,11 +255,16 @@ def main_prefill(args):
     elapsed = time.perf_counter() - t0
 
     prof_calls = min(steps, 200)
-    sw.sw_prof_start(prof_calls)
+    sw.sw_prof_start(prof_calls * (2 if mixed else 1))
     for i in range(prof_calls):
         call(sets[i % n_sets], stream)
-    k_us_sum, _, n_rec = sw.sw_prof_stop()
-    kernel_us = k_us_sum / max(n_rec, 1)
+    k_us_sum, c_us_sum, n_rec = sw.sw_prof_stop()
+    if mixed:
+        # two records per call: the token-phase kernels (partial + merge), then the prompt kernel
+        kernel_us = (k_us_sum + c_us_sum) / prof_calls
+        n_rec = prof_calls
+    else:
+        kernel_us = k_us_sum / max(n_rec, 1)
     achieved = flops / (kernel_us * 1e-6) / 1e12 if kernel_us > 0 else 0.0
 
     cpu_baseline, parity = None, None
@@ -245,10 +272,16 @@ def main_prefill(args):
         import oracle
         lay = sets[0]["layout"]
         c0 = time.perf_counter()
-        ref, used = oracle.prefill_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
-                                        starts0, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
-                                        cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok,
-                                        return_threads=True)
+        if mixed:
+            ref, used = oracle.mixed_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
+                                          starts0, qlens0, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                                          cfg.max_len, max_q, lay.stride_req, lay.stride_kvh,
+                                          lay.stride_tok, return_threads=True)
+        else:
+            ref, used = oracle.prefill_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
+                                            starts0, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                                            cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok,
+                                            return_threads=True)
         t_cpu = time.perf_counter() - c0
         cpu_baseline = {"value": flops / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(used),
                         "kind": "oracle",
@@ -280,6 +313,29 @@ def main_prefill(args):
         "cpu_baseline": cpu_baseline,
         "parity_set0": parity,
     }
+    if mixed:
+        # The token-phase requests dominate the bytes, the prompt the flops: the call is
+        # priced against the HBM roofline on the K/V rows every request reads once (+ q, out),
+        # and the flops are reported beside it.
+        kv = int(batch0.kv_bytes) + 2 * 2 * n_tokens * cfg.n_qh * cfg.head_dim
+        gbps = kv / (kernel_us * 1e-6) / 1e9 if kernel_us > 0 else 0.0
+        line["metric"] = "mixed-batch attention calls per second (one layer; prompt and token phases in one call)"
+        line["value"] = steps / elapsed
+        line["unit"] = "calls/s"
+        line.pop("pct_of_peak")
+        line.pop("prompt_tokens_per_s_attention_only")
+        line["config"]["entry_point"] = "sw_mixed_attn"
+        line["config"]["query_tokens"] = n_tokens
+        line["config"]["prompt_requests"] = int((qlens0 > 1).sum())
+        line["config"]["algorithmic_bytes_per_step"] = kv
+        line["roofline"] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                            "kernel": "token-phase partial + merge, then the prompt kernel (sum of the three)",
+                            "kernel_us": kernel_us, "bytes_per_launch": kv, "launches_timed": n_rec,
+                            "tflops": achieved}
+        if cpu_baseline:
+            cpu_baseline["value"] = 1.0 / t_cpu
+            cpu_baseline["unit"] = "calls/s"
     print(json.dumps(line))
 
 

@@ -240,13 +240,44 @@ int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream);
  *   n_tokens   rows of q and out (0 returns SW_OK without touching the device).
  *   head_dim must be 128 (SW_ERR_UNSUPPORTED otherwise); n_qh / n_kvh at most 64.
  * One kernel, no workspace; asynchrony, ownership and the other errors as in
- * sw_decode_attn.  Weights enter the second matrix product rounded to binary16 (the
+ * sw_decode_attn.  The launch is sized by the smaller of n_req * max_len and about
+ * n_tokens + 64 * n_req query tokens, so a batch of a few long and many short prompts
+ * costs what its tokens cost.  Weights enter the second matrix product rounded to binary16 (the
  * normaliser sums them in binary32 before that rounding); results differ from the fp64
  * definition by about 1e-3 absolute at most for values of order one.
  */
 int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
                     const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,
                     int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream);
+
+/*
+ * sw_mixed_attn -- attention of a mixed batch (section 2.4, "mixed batching": the
+ * scheduler runs prompt and token phases together in one forward pass; the paper's
+ * baseline and the mixed pool of section 4.1 work this way).  Request r contributes
+ * its LAST nq_r cached tokens as queries, nq_r = clamp(q_lens[r], 0, min(L_r,
+ * max_q_len)); query i (row q_starts[r] + i of q and out) is the token at position
+ * L_r - nq_r + i and attends to positions 0 .. L_r - nq_r + i.  nq_r = L_r is a whole
+ * prompt (sw_prefill_attn is this call with q_lens = all of them), nq_r = 1 a request in
+ * its token phase, values between a prompt processed in pieces.  The K/V rows of the
+ * query tokens are already in the cache, as in sw_prefill_attn.
+ *   q_lens      DEVICE int32 [n_req], 4-byte aligned.
+ *   max_q_len   bound on nq_r known to the host (> 0; values above max_len mean
+ *               max_len).
+ * Everything else as in sw_prefill_attn, including the rule that the requests' row
+ * ranges must not overlap (the launch is sized by n_tokens and n_req on that
+ * assumption; overlapping ranges leave rows of out undefined, nothing out of bounds).
+ * Two families of kernels serve the call, enqueued one after the other: requests with
+ * nq_r == 1 (token phase: memory bound) go through sw_decode_attn's kernels, reading
+ * and writing row q_starts[r] -- their results are bit for bit those of sw_decode_attn
+ * for the same max_len -- and the others through the prompt kernels.  Which family
+ * serves a request depends on that request alone.  A request with nq_r == 1 whose row
+ * lies outside [0, n_tokens) is skipped.  Uses sw_decode_attn's workspace.
+ */
+int sw_mixed_attn(const void *q, const void *k_cache, const void *v_cache,
+                  const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                  void *out, long long n_tokens,
+                  int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int max_q_len,
+                  void *stream);
 
 /*
  * KV-cache hand-off, the part inside one GPU's memory.  A prompt machine ships

@@ -31,7 +31,7 @@ SW_PARAM_PREFILL_KERNEL = 7
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
-           "sw_prefill_attn", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
+           "sw_prefill_attn", "sw_mixed_attn", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
 
@@ -94,6 +94,8 @@ def load():
     lib.sw_advance_lens.argtypes = [vp, ci, ci, vp]
     lib.sw_prefill_attn.restype = ci
     lib.sw_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_longlong, ci, ci, ci, ci, ci, vp]
+    lib.sw_mixed_attn.restype = ci
+    lib.sw_mixed_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_longlong, ci, ci, ci, ci, ci, ci, vp]
     for fn in (lib.sw_kv_pack, lib.sw_kv_unpack):
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
@@ -217,6 +219,15 @@ def sw_prefill_attn(q, k_cache, v_cache, seq_lens, q_starts, out, n_tokens, n_re
     rc = load().sw_prefill_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens),
                                 _ptr(q_starts), _ptr(out), int(n_tokens), n_req, n_qh, n_kvh,
                                 head_dim, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_mixed_attn(q, k_cache, v_cache, seq_lens, q_starts, q_lens, out, n_tokens, n_req, n_qh, n_kvh,
+                  head_dim, max_len, max_q_len, stream=None, check=True):
+    """Mixed-batch causal attention: the last q_lens[r] cached tokens of request r are its queries."""
+    rc = load().sw_mixed_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(q_starts),
+                              _ptr(q_lens), _ptr(out), int(n_tokens), n_req, n_qh, n_kvh, head_dim,
+                              max_len, max_q_len, _stream(stream))
     return _check(rc) if check else rc
 
 

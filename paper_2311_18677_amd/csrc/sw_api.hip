@@ -162,6 +162,10 @@ struct StepIn {
     const int32_t *block_table;     // null for the dense layout
     int block_size, max_blocks, n_blocks;
     hipStream_t stream;
+    // token-phase part of a mixed batch: see SwArgs (null / 0 otherwise)
+    const int32_t *q_rows = nullptr, *q_lens = nullptr;
+    long long n_rows = 0;
+    int max_q = 0;
 };
 
 // Policy, workspace and launches; the arguments have been validated.
@@ -211,6 +215,10 @@ int run_step(const StepIn &in)
     // chunk / 128 tiles of 32 positions
     a.waves = waves ? waves : 4;
     if (a.waves * 32 > chunk) a.waves = 4;      // a chunk of 64 still runs 4 waves (2 idle)
+    a.q_rows = in.q_rows;
+    a.q_lens = in.q_lens;
+    a.n_rows = in.n_rows;
+    a.max_q = in.max_q;
     a.block_table = in.block_table;
     if (in.block_table) {
         a.block_shift = 0;
@@ -526,9 +534,12 @@ int sw_decode_attn_append(const void *q, const void *k_new, const void *v_new,
                         n_req, n_qh, n_kvh, head_dim, max_len, stream);
 }
 
-int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
-                    const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,
-                    int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream_v)
+// sw_prefill_attn (q_lens == NULL: every cached token is a query) and sw_mixed_attn
+static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
+                       const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                       bool mixed, void *out, long long n_tokens,
+                       int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int max_q_len,
+                       void *stream_v)
 {
     // ---- validation, before any HIP call ----
     if (n_qh <= 0) return fail(SW_ERR_SHAPE, "n_qh must be > 0");
@@ -537,15 +548,17 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     int rc = check_shape(n_req, n_kvh, head_dim, max_len);
     if (rc != SW_OK) return rc;
     if (n_tokens < 0 || n_tokens > (1LL << 31)) return fail(SW_ERR_SHAPE, "n_tokens must be in [0, 2^31]");
+    if (max_q_len <= 0) return fail(SW_ERR_SHAPE, "max_q_len must be > 0");
+    if (max_q_len > max_len) max_q_len = max_len;
     if (head_dim != 128) return fail(SW_ERR_UNSUPPORTED, "the prompt-phase kernels need head_dim 128");
     if (n_qh / n_kvh > 64) return fail(SW_ERR_UNSUPPORTED, "more than 64 query heads per key/value head");
     if (n_req == 0 || n_tokens == 0) return SW_OK;
-    if (!q || !k_cache || !v_cache || !seq_lens || !q_starts || !out)
-        return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens, q_starts and out must be non-NULL");
+    if (!q || !k_cache || !v_cache || !seq_lens || !q_starts || !out || (mixed && !q_lens))
+        return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens, q_starts, q_lens and out must be non-NULL");
     if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u)
         return fail(SW_ERR_ALIGN, "q, k_cache, v_cache and out must be 16-byte aligned");
-    if (((uintptr_t)seq_lens | (uintptr_t)q_starts) & 3u)
-        return fail(SW_ERR_ALIGN, "seq_lens and q_starts must be 4-byte aligned");
+    if (((uintptr_t)seq_lens | (uintptr_t)q_starts | (uintptr_t)q_lens) & 3u)
+        return fail(SW_ERR_ALIGN, "seq_lens, q_starts and q_lens must be 4-byte aligned");
 
     SwPrefillArgs a;
     a.q = (const uint16_t *)q;
@@ -553,6 +566,10 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     a.v = (const uint16_t *)v_cache;
     a.seq_lens = seq_lens;
     a.q_starts = q_starts;
+    a.q_lens = q_lens;
+    a.max_q = max_q_len;
+    a.skip_single = 0;
+    a.compact = 0;                  // the launchers decide
     a.out = (uint16_t *)out;
     a.n_tokens = n_tokens;
     a.n_req = n_req;
@@ -575,16 +592,37 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
         a.qw = 1;
         if (g_prefill_qw == 2 || g_prefill_qw == 4 || g_prefill_qw == 8) split_waves = g_prefill_qw;
     } else {
-        sw_prefill_shape(n_req, n_kvh, a.group, max_len, &a.hp, &a.qw);
+        sw_prefill_shape(n_req, n_kvh, a.group, max_q_len, &a.hp, &a.qw);
         if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) a.hp = g_prefill_hp;
         if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
     }
-    a.n_qblocks = (max_len + 32 * a.qw - 1) / (32 * a.qw);
+    a.n_qblocks = (max_q_len + 32 * a.qw - 1) / (32 * a.qw);      // the grid covers max_q_len query tokens
     a.stride_kvh = slab_elems(head_dim, max_len);
     a.stride_req = a.stride_kvh * n_kvh;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     if ((long long)n_req * n_qh * a.n_qblocks > 0x7fffffffLL)
         return fail(SW_ERR_SHAPE, "too many workgroups");
+
+    // A mixed batch is served by both families of kernels: requests with exactly one query
+    // token are token-phase requests (memory bound, one pass over their cache: the
+    // split-over-context kernels, reading and writing row q_starts[r]); the prompt kernel
+    // takes the others.  Which family serves a request depends on that request alone.
+    if (mixed) {
+        StepIn in{};
+        in.q = q; in.k = k_cache; in.v = v_cache;
+        in.k_new = in.v_new = nullptr;
+        in.seq_lens = seq_lens;
+        in.out = out;
+        in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
+        in.block_table = nullptr;
+        in.block_size = in.max_blocks = in.n_blocks = 0;
+        in.stream = (hipStream_t)stream_v;
+        in.q_rows = q_starts; in.q_lens = q_lens; in.n_rows = n_tokens; in.max_q = max_q_len;
+        rc = run_step(in);
+        if (rc != SW_OK) return rc;
+        a.skip_single = 1;
+        if (max_q_len == 1) return SW_OK;          // no request can have more than one query
+    }
 
     bool prof = false;
     SwLaunchEvents ev = {nullptr, nullptr};
@@ -601,6 +639,24 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
     }
     if (prof) prof_commit(rec);
     return SW_OK;
+}
+
+int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,
+                    int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream)
+{
+    return causal_attn(q, k_cache, v_cache, seq_lens, q_starts, nullptr, false, out, n_tokens,
+                       n_req, n_qh, n_kvh, head_dim, max_len, max_len > 0 ? max_len : 1, stream);
+}
+
+int sw_mixed_attn(const void *q, const void *k_cache, const void *v_cache,
+                  const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                  void *out, long long n_tokens,
+                  int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int max_q_len,
+                  void *stream)
+{
+    return causal_attn(q, k_cache, v_cache, seq_lens, q_starts, q_lens, true, out, n_tokens,
+                       n_req, n_qh, n_kvh, head_dim, max_len, max_q_len, stream);
 }
 
 // sw_kv_pack / sw_kv_unpack

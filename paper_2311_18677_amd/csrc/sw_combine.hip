@@ -48,9 +48,11 @@ void sw_combine_kernel(SwArgs a)
         mlc[u] = ml[c * cs];
         x[u]   = po[c * cs * V4];
     }
-    const int L = sw_request_len(a, r);
+    const int lf = sw_request_len_flagged(a, r);
+    if (lf == kSwSkip) return;                   // the request takes no part in this call
+    const int L = lf & kSwLenMask;
     const int nc = (L + a.chunk - 1) >> a.chunk_shift;
-    half4_t *out = reinterpret_cast<half4_t *>(reinterpret_cast<_Float16 *>(a.out) + (long long)rh * D) + j4;
+    half4_t *out = reinterpret_cast<half4_t *>(reinterpret_cast<_Float16 *>(a.out) + (sw_q_row(a, r) * a.n_qh + h) * D) + j4;
     if (nc == 0) {
         if (k == 0) *out = half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
         return;

@@ -98,7 +98,7 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int
     for (int idx = threadIdx.x; idx < n_heads * V4; idx += blockDim.x) {
         const int hh = idx / V4;
         const int j4 = idx - hh * V4;
-        const long long rh = (long long)r * a.n_qh + g * a.group + hh_first + hh;
+        const long long rh = sw_q_row(a, r) * a.n_qh + g * a.group + hh_first + hh;
         const long long slot0 = sw_ws_slot(a, r, g, 0, hh_first + hh);
         const long long cs = a.group;                     // slots between consecutive chunks
         const float *ml = a.ws_ml + slot0 * 2;
@@ -143,9 +143,9 @@ __device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int
 template <int D>
 __device__ __forceinline__ void sw_fused_zero_rows(const SwArgs &a, int req)
 {
-    if (sw_request_len(a, req) > 0) return;
+    if (sw_request_len_flagged(a, req) != 0) return;      // has positions, or takes no part in the call
     sw_half4_t z = sw_half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
-    _Float16 *row = reinterpret_cast<_Float16 *>(a.out) + (long long)req * a.n_qh * D;
+    _Float16 *row = reinterpret_cast<_Float16 *>(a.out) + sw_q_row(a, req) * a.n_qh * D;
     for (int idx = threadIdx.x; idx < a.n_qh * (D / 4); idx += blockDim.x)
         *reinterpret_cast<sw_half4_t *>(row + 4 * idx) = z;
 }

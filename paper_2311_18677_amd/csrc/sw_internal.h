@@ -30,6 +30,14 @@ struct SwArgs {
     const uint16_t *k_new;              // append variant: the newest token's K rows [n_req][n_kvh][head_dim], else null
     const uint16_t *v_new;              //                 and V rows
     const int32_t  *block_table;        // block-table variant: [n_req][max_blocks] pool block ids, else null
+    // Token-phase part of a mixed batch (all null / 0 otherwise): request r takes part only
+    // if exactly one of its tokens is a query (q_lens[r] clamped to [0, min(L, max_q)] is 1)
+    // and q_rows[r] is a row of q and out ([n_rows][n_qh][head_dim]); its query and result
+    // are that row instead of row r.  The other requests are neither read nor written.
+    const int32_t  *q_rows;
+    const int32_t  *q_lens;
+    long long       n_rows;
+    int             max_q;
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
     int   chunk, chunk_shift, n_chunks; // chunk = 1 << chunk_shift; n_chunks = ceil(max_len / chunk)
@@ -48,11 +56,15 @@ struct SwPrefillArgs {
     const uint16_t *k;                  // caches in the dense layout
     const uint16_t *v;
     const int32_t  *seq_lens;           // prompt lengths
-    const int32_t  *q_starts;           // row of each request's first prompt token
+    const int32_t  *q_starts;           // row of each request's first query token
+    const int32_t  *q_lens;             // query tokens per request (the last ones), or null: all of them
     uint16_t       *out;                // [n_tokens][n_qh][head_dim]
     long long n_tokens;
     int   n_req, n_qh, n_kvh, group;
     int   head_dim, max_len;
+    int   max_q;                        // bound on the query tokens of a request (sizes the grid)
+    int   skip_single;                  // non-zero: requests with exactly one query token are left out
+    int   compact;                      // non-zero: workgroups find their (request, query block) by a scan of the lengths
     int   hp;                           // query heads (of one group) per workgroup
     int   qw;                           // waves per query head in a workgroup
     int   n_qblocks;                    // query blocks (of 32 * qw positions) that cover max_len
@@ -80,15 +92,30 @@ struct SwHandoffArgs {
 // position (and attends over) unless the cache is already full.  Bit
 // kSwAppendedBit of the result says that the rows are stored, i.e. that
 // position L - 1 is the new one; the bits below it hold L (max_len <= 2^23).
+// kSwSkip (negative, length bits 0) marks a request that takes no part in the call:
+// it has no work item and its output row is left alone.
 constexpr int kSwAppendedBit = 30;
 constexpr int kSwLenMask     = (1 << kSwAppendedBit) - 1;
+constexpr int kSwSkip        = (int)0x80000000u;
 
 __device__ inline int sw_request_len_flagged(const SwArgs &a, int r)
 {
     int L = a.seq_lens[r];
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    if (a.q_lens) {
+        const int cap = L < a.max_q ? L : a.max_q;
+        const int nq = a.q_lens[r] < cap ? a.q_lens[r] : cap;
+        const long long row = a.q_rows[r];
+        if (nq != 1 || row < 0 || row >= a.n_rows) return kSwSkip;
+    }
     if (a.k_new && L < a.max_len) L += 1 + (1 << kSwAppendedBit);
     return L;
+}
+
+// Row of q and out that belongs to request r (valid for requests that take part).
+__device__ inline long long sw_q_row(const SwArgs &a, int r)
+{
+    return a.q_rows ? (long long)a.q_rows[r] : (long long)r;
 }
 
 __device__ inline int sw_request_len(const SwArgs &a, int r)
@@ -118,6 +145,17 @@ bool       sw_partial_mfma2_supported(const SwArgs &a);
 hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 // Merge of the chunks' partial results, normalisation and rounding to binary16.
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+// Bound on the (request, block of q_block query tokens) items of a prompt-phase call, which
+// sizes its grid: no request has more than n_qblocks of them, and requests whose rows of q
+// and out do not overlap have at most n_tokens / q_block + 2 per request between them.
+static inline long long sw_prefill_items(const SwPrefillArgs &a, int q_block, bool *compact)
+{
+    const long long by_shape = (long long)a.n_req * a.n_qblocks;
+    const long long by_rows = a.n_tokens / q_block + 2LL * a.n_req;
+    // the scan costs every workgroup a little; it pays once it removes a good part of the grid
+    *compact = by_rows * 4 < by_shape * 3;
+    return *compact ? by_rows : by_shape;
+}
 bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
 void       sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw);
 hipError_t sw_launch_prefill_split(const SwPrefillArgs &a, int waves, hipStream_t stream, const SwLaunchEvents *ev);

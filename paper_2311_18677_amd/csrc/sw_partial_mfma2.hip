@@ -106,7 +106,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
         if (row < 16 && row >= a.group)
             *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
         if (row < a.group) {       // group <= 16: waves past the fourth stage nothing
-            const uint16_t *src = a.q + ((long long)r * a.n_qh + g * a.group + row) * kD + 8 * (n16 ^ row);
+            const uint16_t *src = a.q + (sw_q_row(a, r) * a.n_qh + g * a.group + row) * kD + 8 * (n16 ^ row);
             __builtin_amdgcn_global_load_lds(src, sm_q + wave * 1024, 16, 0, 0);
         }
     }
@@ -395,7 +395,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
             den = fmaf(f, sm_l[w][hh], den);
         }
         if (alone) {
-            sw_store_final4<kD>(a, (long long)r * a.n_qh + g * a.group + hh, j4, num, den);
+            sw_store_final4<kD>(a, sw_q_row(a, r) * a.n_qh + g * a.group + hh, j4, num, den);
             continue;
         }
         const long long slot = sw_ws_slot(a, r, g, c, hh);

@@ -81,7 +81,7 @@ void sw_partial_valu_kernel(SwArgs a)
     for (int hh = 0; hh < GT; ++hh) {
         Row8 x = {};
         if (hh < n_valid)
-            x = *reinterpret_cast<const Row8 *>(a.q + ((long long)r * a.n_qh + h0 + hh) * D + sub * 8);
+            x = *reinterpret_cast<const Row8 *>(a.q + (sw_q_row(a, r) * a.n_qh + h0 + hh) * D + sub * 8);
 #pragma unroll
         for (int i = 0; i < 4; ++i) qv[hh][i] = x.h[i];
     }
@@ -232,7 +232,7 @@ void sw_partial_valu_kernel(SwArgs a)
             den = fmaf(f, sm_l[w2][hh], den);
         }
         if (alone) {
-            sw_store_final4<D>(a, (long long)r * a.n_qh + h0 + hh, j4, num, den);
+            sw_store_final4<D>(a, sw_q_row(a, r) * a.n_qh + h0 + hh, j4, num, den);
             continue;
         }
         const long long slot = sw_ws_slot(a, r, g, c, ht * GT + hh);

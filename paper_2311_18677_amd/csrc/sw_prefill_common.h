@@ -7,6 +7,7 @@
 #pragma once
 #include "sw_internal.h"
 #include "sw_lane_ops.h"
+#include "sw_worklist.h"
 
 namespace sw_prefill {
 
@@ -38,16 +39,133 @@ union Frag {
 // rarely instead of every tile.
 constexpr float kLazyBits = 8.0f;
 
-// Q^T operands of a wave: lane (n16, gq) holds dims 32kk + 8gq .. +7 of query
-// q0 + 16nb + n16.  Rows past the prompt repeat its last row (never stored); row
-// indices are clamped into [0, n_tokens).
-__device__ __forceinline__ void load_q(const SwPrefillArgs &a, long long q_first, int q0, int L, int h,
+// Query tokens of a request: with L cached positions and nq of them queries (the last
+// nq; nq = L when no q_lens array is given), query index i is the token at position
+// L - nq + i.
+__device__ __forceinline__ int request_queries(const SwPrefillArgs &a, int r, int L)
+{
+    if (!a.q_lens) return L;
+    const int cap = L < a.max_q ? L : a.max_q;
+    int nq = a.q_lens[r];
+    nq = nq < 0 ? 0 : (nq > cap ? cap : nq);
+    // a request with a single query token is a token-phase request: when the call runs
+    // those through the token-phase kernels, it is none of this kernel's business
+    return (a.skip_single && nq == 1) ? 0 : nq;
+}
+
+// ---- workgroup -> (request, query block).  How many query blocks a request has depends
+// on lengths only the device knows, so the grid is sized by a host-side bound and every
+// wave finds its workgroup's item itself (no LDS, no barrier): items are numbered request
+// by request, a request's late blocks (which see the most positions) first.  (When the
+// bound is no smaller than requests x blocks-per-request anyway, the host asks for the
+// direct mapping instead, which puts the late blocks of ALL requests first.)  A request
+// owns one item per block of q_block query indices that holds a query whose row exists
+// (rows outside [0, n_tokens) are never stored, so blocks of only such rows are no items).
+struct QItem {
+    int  r;            // request
+    int  qb;           // query block: query indices qb * q_block ...
+    int  L;            // cached positions of the request
+    int  NQ;           // its query tokens (the last NQ positions)
+    long long q_first; // row of its query index 0
+    bool valid;        // false: nothing to do for this workgroup
+};
+
+__device__ __forceinline__ void request_span(const SwPrefillArgs &a, int r, int q_block, int &L, int &NQ,
+                                             long long &q_first, int &qb_lo, int &cnt)
+{
+    L = a.seq_lens[r];
+    q_first = a.q_starts[r];
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    NQ = request_queries(a, r, L);
+    const long long lo = q_first < 0 ? -q_first : 0;                       // first query index with a row
+    const long long room = a.n_tokens - q_first;
+    const long long hi = room < (long long)NQ ? room : (long long)NQ;      // one past the last
+    qb_lo = cnt = 0;
+    if (hi > lo) {
+        qb_lo = (int)(lo / q_block);
+        cnt = (int)((hi - 1) / q_block) - qb_lo + 1;
+    }
+}
+
+// Called by all 64 lanes of a wave; every wave of a workgroup gets the same answer.
+__device__ __forceinline__ QItem find_item(const SwPrefillArgs &a, unsigned item, int q_block)
+{
+    QItem it;
+    it.r = it.qb = it.L = it.NQ = 0;
+    it.q_first = 0;
+    it.valid = false;
+    if (!a.compact) {
+        // direct mapping: item = (n_qblocks - 1 - qb) * n_req + r, late blocks of all requests first
+        const int r = (int)(item % (unsigned)a.n_req);
+        int L = a.seq_lens[r];
+        it.q_first = a.q_starts[r];          // read together with the length: one wait for both
+        L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+        it.r = r;
+        it.qb = a.n_qblocks - 1 - (int)(item / (unsigned)a.n_req);
+        it.L = L;
+        it.NQ = request_queries(a, r, L);
+        it.valid = it.qb >= 0;
+        return it;
+    }
+    const int lane = threadIdx.x & 63;
+    const int per = (a.n_req + 63) >> 6;            // consecutive requests per lane
+    int L = 0, NQ = 0, qb_lo = 0, cnt = 0, mine = 0;
+    long long qf = 0;
+    for (int j = 0; j < per; ++j) {
+        const int r = lane * per + j;
+        if (r < a.n_req) {
+            request_span(a, r, q_block, L, NQ, qf, qb_lo, cnt);
+            mine += cnt;
+        }
+    }
+    const int incl = sw_wave_inclusive_scan(mine);
+    const unsigned long long hit = __ballot((unsigned)incl > item);
+    if (hit == 0) return it;                        // past the last item
+    const int owner = __builtin_ctzll(hit);         // first lane whose requests reach the item
+    unsigned before = (unsigned)__builtin_amdgcn_readlane(incl - mine, owner);
+    int r = owner;
+    if (per == 1) {
+        L = __builtin_amdgcn_readlane(L, owner);
+        NQ = __builtin_amdgcn_readlane(NQ, owner);
+        qb_lo = __builtin_amdgcn_readlane(qb_lo, owner);
+        cnt = __builtin_amdgcn_readlane(cnt, owner);
+        const unsigned lo32 = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)qf, owner);
+        const unsigned hi32 = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)qf >> 32), owner);
+        qf = (long long)(((unsigned long long)hi32 << 32) | lo32);
+    } else {
+        // walk the owner lane's requests again (wave-uniform loads, served from cache)
+        cnt = 0;
+        for (int j = 0; j < per; ++j) {
+            before += (unsigned)cnt;
+            r = min(owner * per + j, a.n_req - 1);
+            request_span(a, r, q_block, L, NQ, qf, qb_lo, cnt);
+            if (before + (unsigned)cnt > item) break;
+        }
+    }
+    const unsigned local = item - before;
+    if (local >= (unsigned)cnt) return it;          // cannot happen when the scan is right
+    // wave-uniform by construction; say so, so that everything derived stays in scalar registers
+    it.r = __builtin_amdgcn_readfirstlane(r);
+    it.qb = __builtin_amdgcn_readfirstlane(qb_lo + cnt - 1 - (int)local);
+    it.L = __builtin_amdgcn_readfirstlane(L);
+    it.NQ = __builtin_amdgcn_readfirstlane(NQ);
+    const unsigned lo32 = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)qf);
+    const unsigned hi32 = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)qf >> 32));
+    it.q_first = (long long)(((unsigned long long)hi32 << 32) | lo32);
+    it.valid = true;
+    return it;
+}
+
+// Q^T operands of a wave: lane (n16, gq) holds dims 32kk + 8gq .. +7 of the query with
+// index q0 + 16nb + n16 (of nq).  Indices past the last query repeat it (never stored);
+// row indices are clamped into [0, n_tokens).
+__device__ __forceinline__ void load_q(const SwPrefillArgs &a, long long q_first, int q0, int nq, int h,
                                        int n16, int gq, Frag (&qreg)[2][4])
 {
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         int qpos = q0 + 16 * nb + n16;
-        qpos = qpos < L ? qpos : L - 1;
+        qpos = qpos < nq ? qpos : nq - 1;
         long long row = q_first + qpos;
         row = row < 0 ? 0 : (row >= a.n_tokens ? a.n_tokens - 1 : row);
         const uint16_t *src = a.q + (row * a.n_qh + h) * kD + 8 * gq;

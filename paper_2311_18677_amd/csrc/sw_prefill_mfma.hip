@@ -35,22 +35,19 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     constexpr int C = (16 + NW - 1) / NW;
     __shared__ __attribute__((aligned(16))) unsigned char lds[kBufs * kBufBytes];
 
-    // blockIdx -> (query block, request, key/value head, block of hp query heads)
+    // blockIdx -> (item = (request, query block), key/value head, block of hp query heads)
+    const int q_block = kQPerWave * a.qw;        // query tokens per workgroup
     const unsigned n_hb = (unsigned)(a.group / a.hp);
     const unsigned hb = blockIdx.x % n_hb;
     const unsigned rest = blockIdx.x / n_hb;
-    const unsigned n_units = (unsigned)a.n_req * (unsigned)a.n_kvh;
-    const unsigned unit = rest % n_units;
-    // late query blocks see the most positions: they come first in dispatch order
-    const int qb = a.n_qblocks - 1 - (int)(rest / n_units);
-    const int r = (int)(unit / (unsigned)a.n_kvh);
-    const int g = (int)(unit - (unsigned)r * (unsigned)a.n_kvh);
-    int L = a.seq_lens[r];
-    const long long q_first = a.q_starts[r];     // read together with the length: one wait for both
-    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int q_block = kQPerWave * a.qw;        // query positions per workgroup
-    const int Q0 = qb * q_block;
-    if (Q0 >= L) return;
+    const int g = (int)(rest % (unsigned)a.n_kvh);
+    const QItem it = find_item(a, rest / (unsigned)a.n_kvh, q_block);
+    if (!it.valid) return;
+    const int r = it.r, qb = it.qb, L = it.L, NQ = it.NQ;   // NQ: the request's last NQ tokens are its queries
+    const long long q_first = it.q_first;
+    const int P0 = L - NQ;                       // position of query index 0
+    const int Q0 = qb * q_block;                 // first query index of the workgroup
+    if (Q0 >= NQ) return;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -58,7 +55,8 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     const int gq   = lane >> 4;
     const int hh   = (int)hb * a.hp + wave % a.hp;   // query head within the group
     const int sb   = wave / a.hp;                // which 32 query positions of the block
-    const int qw0  = Q0 + kQPerWave * sb;
+    const int qw0  = Q0 + kQPerWave * sb;        // first query index of the wave ...
+    const int aw0  = P0 + qw0;                   // ... and its position
     const int h    = g * a.group + hh;
 
     // The staging area is filled by global->LDS loads only; one ordinary store keeps
@@ -70,11 +68,11 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
     const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
 
-    // tiles the workgroup walks: up to its last query position, within the prompt
-    const int last_q = min(Q0 + q_block, L) - 1;
-    const int n_tiles = last_q / kTile + 1;
-    // tiles this wave computes on: up to its own last query position
-    const int my_tiles = qw0 < L ? qw0 / kTile + 1 : 0;
+    // tiles the workgroup walks: up to the position of its last query
+    const int last_pos = P0 + min(Q0 + q_block, NQ) - 1;
+    const int n_tiles = last_pos / kTile + 1;
+    // tiles this wave computes on: up to the position of its own last query
+    const int my_tiles = qw0 < NQ ? min(aw0 + kQPerWave - 1, L - 1) / kTile + 1 : 0;
 
     // this wave's share of tile ti's loads -> buffer ti % 3.  Instruction j < 8 is K rows
     // 4j .. 4j+3 (16-byte pieces XOR-swizzled by row), j >= 8 is V rows 4(j-8) .. +3.
@@ -111,7 +109,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     // ---- Q^T operands.  Requested after the first tiles so that both latencies overlap;
     // awaited here, once, so that no wait inside the loop has to cover them.
     Frag qreg[2][4];
-    load_q(a, q_first, qw0, L, h, n16, gq, qreg);
+    load_q(a, q_first, qw0, NQ, h, n16, gq, qreg);
 
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 
@@ -134,7 +132,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
         Frag va[8];
         load_vt(vb, vt_off, va);
         Frag p[2];
-        softmax_tile(sacc, t0 + kTile > qw0, qw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
+        softmax_tile(sacc, t0 + kTile > aw0, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         pv_block(0, va, p, o);
         pv_block(1, va, p, o);
     }
@@ -143,9 +141,9 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const float ls = quad_rows_sum(l[nb]);
-        const int qpos = qw0 + 16 * nb + n16;
+        const int qpos = qw0 + 16 * nb + n16;        // query index
         const long long row = q_first + qpos;
-        if (qpos < L && row >= 0 && row < a.n_tokens) {
+        if (qpos < NQ && row >= 0 && row < a.n_tokens) {
             const float inv = 1.0f / ls;
             _Float16 *dst = reinterpret_cast<_Float16 *>(a.out) + (row * a.n_qh + h) * kD + 4 * gq;
 #pragma unroll
@@ -184,11 +182,14 @@ void sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int
     *qw = w;
 }
 
-hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
+hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a_in, hipStream_t stream, const SwLaunchEvents *ev)
 {
+    SwPrefillArgs a = a_in;
     if (!sw_prefill_mfma_supported(a)) return hipErrorNotSupported;
     if (a.hp < 1 || a.group % a.hp != 0 || a.qw < 1) return hipErrorInvalidValue;
-    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_qblocks * (a.group / a.hp);
+    bool compact;
+    const long long blocks = sw_prefill_items(a, kQPerWave * a.qw, &compact) * a.n_kvh * (a.group / a.hp);
+    a.compact = compact;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks);
     const int nw = a.hp * a.qw;

@@ -32,20 +32,17 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     __shared__ float sm_m[WAVES][kQPerWave];
     __shared__ float sm_l[WAVES][kQPerWave];
 
-    // blockIdx -> (query block, request, key/value head, query head of the group);
-    // late query blocks see the most positions: they come first in dispatch order
+    // blockIdx -> (item = (request, query block), key/value head, query head of the group)
     const unsigned hh = blockIdx.x % (unsigned)a.group;
     const unsigned rest = blockIdx.x / (unsigned)a.group;
-    const unsigned n_units = (unsigned)a.n_req * (unsigned)a.n_kvh;
-    const unsigned unit = rest % n_units;
-    const int qb = a.n_qblocks - 1 - (int)(rest / n_units);
-    const int r = (int)(unit / (unsigned)a.n_kvh);
-    const int g = (int)(unit - (unsigned)r * (unsigned)a.n_kvh);
-    int L = a.seq_lens[r];
-    const long long q_first = a.q_starts[r];
-    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int Q0 = qb * kQPerWave;
-    if (Q0 >= L) return;
+    const int g = (int)(rest % (unsigned)a.n_kvh);
+    const QItem it = find_item(a, rest / (unsigned)a.n_kvh, kQPerWave);
+    if (!it.valid) return;
+    const int r = it.r, qb = it.qb, L = it.L, NQ = it.NQ;   // NQ: the request's last NQ tokens are its queries
+    const long long q_first = it.q_first;
+    const int Q0 = qb * kQPerWave;               // first query index of the block ...
+    if (Q0 >= NQ) return;
+    const int A0 = L - NQ + Q0;                  // ... and its position
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -67,7 +64,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     for (int c = 0; c < 8 / WAVES; ++c) {
         const int j = wave + WAVES * c;                   // rows 4j .. 4j+3
         const int qi = 4 * j + gq;
-        const int qpos = min(Q0 + qi, L - 1);
+        const int qpos = min(Q0 + qi, NQ - 1);
         long long row = q_first + qpos;
         row = row < 0 ? 0 : (row >= a.n_tokens ? a.n_tokens - 1 : row);
         const uint16_t *src = a.q + (row * a.n_qh + h) * kD + 8 * (n16 ^ (qi & 15));
@@ -77,8 +74,8 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
     const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
 
-    // tiles 0 .. Q0/32 hold every position the block's queries may see; all start inside the prompt
-    const int n_tiles = Q0 / kTile + 1;
+    // the tiles that hold every position the block's queries may see (all start inside the context)
+    const int n_tiles = min(A0 + kQPerWave - 1, L - 1) / kTile + 1;
 
     // Per-lane byte offsets of a tile's load instructions relative to the tile's first row,
     // computed once: instruction n brings rows 4n .. 4n+3 (lane group gq row 4n+gq, lane n16
@@ -164,9 +161,9 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
             __builtin_amdgcn_s_waitcnt(0xc07f);
             issue_k(t0_next);
         }
-        const bool diagonal = t0 + kTile > Q0;
+        const bool diagonal = t0 + kTile > A0;
         Frag p[2];
-        softmax_block(0, sacc, diagonal, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
+        softmax_block(0, sacc, diagonal, A0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         // outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile
         if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
@@ -177,7 +174,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
             issue_v(t0_next);
         }
         pv_block(0, va, p, o);
-        softmax_block(1, sacc, diagonal, Q0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
+        softmax_block(1, sacc, diagonal, A0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         pv_block(1, va, p, o);
     };
 
@@ -228,9 +225,9 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     for (int idx = threadIdx.x; idx < kQPerWave * (kD / 4); idx += 64 * WAVES) {
         const int qi = idx >> 5;
         const int piece = idx & 31;
-        const int qpos = Q0 + qi;
+        const int qpos = Q0 + qi;                   // query index
         const long long row = q_first + qpos;
-        if (qpos >= L || row < 0 || row >= a.n_tokens) continue;
+        if (qpos >= NQ || row < 0 || row >= a.n_tokens) continue;
         float mx = sm_m[0][qi];
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) mx = fmaxf(mx, sm_m[w][qi]);
@@ -257,11 +254,14 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 
 }  // namespace
 
-hipError_t sw_launch_prefill_split(const SwPrefillArgs &a, int waves, hipStream_t stream, const SwLaunchEvents *ev)
+hipError_t sw_launch_prefill_split(const SwPrefillArgs &a_in, int waves, hipStream_t stream, const SwLaunchEvents *ev)
 {
-    if (a.head_dim != kD) return hipErrorNotSupported;
-    const long long blocks = (long long)a.n_req * a.n_qh * a.n_qblocks;
+    if (a_in.head_dim != kD) return hipErrorNotSupported;
+    SwPrefillArgs a = a_in;
+    bool compact;
+    const long long blocks = sw_prefill_items(a, kQPerWave, &compact) * a.n_qh;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    a.compact = compact;
     const dim3 grid((unsigned)blocks);
     if (waves == 8) return sw_launch(sw_prefill_split_kernel<8>, grid, dim3(512), 0, stream, ev, a);
     if (waves == 4) return sw_launch(sw_prefill_split_kernel<4>, grid, dim3(256), 0, stream, ev, a);

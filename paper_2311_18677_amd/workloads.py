@@ -160,6 +160,30 @@ PREFILL_CONFIGS = {
                                n_layers=80, seed_index=15),
 }
 
+# Mixed batches (section 2.4: prompt and token phases of different requests in one forward
+# pass).  name -> (shape and context-length recipe, prompts in the batch, tokens per prompt):
+# the first `prompts` requests are prompts of that many tokens, all of them queries; the
+# others are token-phase requests (one query each) with contexts from the recipe.
+MIXED_CONFIGS = {
+    # the Llama-2-70B decode batch with one coding-median prompt riding along
+    "mixed_llama70b_tp8": (Config("mixed_llama70b_tp8", 64, 8, 1, 128, 4096, ("uniform", 1000, 2600),
+                                  n_layers=80, seed_index=16), 1, 1500),
+    "mixed_tiny": (Config("mixed_tiny", 6, 4, 2, 128, 160, ("uniform", 1, 160),
+                          n_layers=1, seed_index=17), 2, 70),
+}
+
+
+def make_mixed_batch(name, seed=None):
+    """(Batch, q_lens int32 [n_req]) of a MIXED_CONFIGS entry."""
+    cfg, n_prompts, prompt_len = MIXED_CONFIGS[name]
+    drawn = make_batch(cfg, seed=seed)
+    lens = np.array(drawn.seq_lens, dtype=np.int64)
+    lens[:n_prompts] = prompt_len
+    batch = make_batch(cfg, seed=drawn.seed, seq_lens=lens.tolist())
+    q_lens = np.ones(cfg.n_req, dtype=np.int32)
+    q_lens[:n_prompts] = prompt_len
+    return batch, q_lens
+
 
 def make_prefill_queries(batch, seed=None):
     """Queries of every prompt token of a Batch, packed request after request.

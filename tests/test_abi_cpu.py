@@ -219,3 +219,16 @@ def test_kv_handoff_validation():
     assert sp(nb=0) == sw.SW_ERR_SHAPE
     assert sp(n_req=-1) == sw.SW_ERR_SHAPE
     assert sp(n_req=0) == sw.SW_OK
+
+
+def test_mixed_validation():
+    def mcall(q=0x1000, k=0x2000, v=0x3000, lens=0x4000, starts=0x5000, qlens=0x7000, out=0x6000,
+              n_tokens=100, n_req=2, n_qh=8, n_kvh=1, d=128, max_len=256, max_q=64):
+        return sw.sw_mixed_attn(q, k, v, lens, starts, qlens, out, n_tokens, n_req, n_qh, n_kvh, d, max_len,
+                                max_q, None, check=False)
+    assert mcall(qlens=None) == sw.SW_ERR_NULL
+    assert mcall(qlens=0x7002) == sw.SW_ERR_ALIGN
+    assert mcall(max_q=0) == sw.SW_ERR_SHAPE
+    assert mcall(d=64) == sw.SW_ERR_UNSUPPORTED
+    assert mcall(n_tokens=0) == sw.SW_OK
+    assert mcall(n_req=0) == sw.SW_OK

@@ -1,0 +1,170 @@
+"""GPU parity of the mixed-batch attention (prompt and token phases in one call)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_18677_amd import binding as sw
+from paper_2311_18677_amd import workloads as wl
+from helpers import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+NAN_BITS = 0x7E00
+
+
+@pytest.fixture(autouse=True, params=["default", "shared", "split4", "split8"])
+def _kernel(request):
+    which, waves = {"default": (0, 0), "shared": (1, 0), "split4": (2, 4), "split8": (2, 8)}[request.param]
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, which)
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, waves)
+    yield request.param
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 0)
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, 0)
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16).reshape(-1)).to("cuda:0").view(torch.float16)
+
+
+def run_mixed(batch, qt, starts, q_lens, max_q_len, bufs=None, tag=""):
+    import torch
+    cfg = batch.cfg
+    if bufs is None:
+        bufs = sw.upload_batch(batch, pad_bits=NAN_BITS)
+    lay = bufs["layout"]
+    ref = oracle.mixed_attn(qt, bufs["k_host"], bufs["v_host"], batch.seq_lens, starts, q_lens, cfg.n_req,
+                            cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, max_q_len, lay.stride_req,
+                            lay.stride_kvh, lay.stride_tok)
+    out = torch.full((qt.shape[0], cfg.n_qh, cfg.head_dim), float("nan"), dtype=torch.float16, device="cuda:0")
+    print("mixed run", tag, cfg.name, "q_lens", list(q_lens)[:10], "max_q", max_q_len, flush=True)
+    sw.sw_mixed_attn(to_dev(qt), bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"],
+                     torch.from_numpy(np.ascontiguousarray(starts, dtype=np.int32)).to("cuda:0"),
+                     torch.from_numpy(np.ascontiguousarray(q_lens, dtype=np.int32)).to("cuda:0"),
+                     out, qt.shape[0], cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, max_q_len)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), ref, bufs
+
+
+@pytest.mark.parametrize("n_qh,n_kvh", [(8, 1), (4, 4), (6, 2)])
+def test_mixed_batch_matches_oracle(n_qh, n_kvh):
+    lens = [300, 300, 257, 64, 33, 1, 0, 200, 129, 300, 96, 250]
+    qls = [300, 1, 100, 64, 1, 1, 5, 31, 33, 0, 32, 77]          # whole prompts, token phases, pieces
+    cfg = wl.custom_config("mx%d_%d" % (n_qh, n_kvh), len(lens), n_qh, n_kvh, 128, 300)
+    batch = wl.make_batch(cfg, seed=4000 + n_qh, seq_lens=lens)
+    qt, starts, nq = wl.make_mixed_queries(batch, qls)
+    assert nq.tolist() == [300, 1, 100, 64, 1, 1, 0, 31, 33, 0, 32, 77]
+    out, ref, _ = run_mixed(batch, qt, starts, qls, 300, tag="pattern")
+    assert not np.isnan(out.astype(np.float32)).any()
+    assert_parity(out, ref, cfg.name)
+
+
+def test_all_tokens_as_queries_is_the_prompt_call_bit_for_bit():
+    import torch
+    lens = [200, 77, 130]
+    cfg = wl.custom_config("mxp", len(lens), 8, 2, 128, 256)
+    batch = wl.make_batch(cfg, seed=4100, seq_lens=lens)
+    qt, starts = wl.make_prefill_queries(batch)
+    out, ref, bufs = run_mixed(batch, qt, starts, lens, 256, tag="all")
+    assert_parity(out, ref, cfg.name)
+    pre = torch.full_like(to_dev(qt).view(qt.shape), float("nan"))
+    sw.sw_prefill_attn(to_dev(qt), bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"],
+                       torch.from_numpy(starts).to("cuda:0"), pre, qt.shape[0], cfg.n_req, 8, 2, 128, 256)
+    torch.cuda.synchronize()
+    assert np.array_equal(pre.cpu().numpy().view(np.uint16), out.view(np.uint16))
+
+
+def test_one_query_per_request_agrees_with_the_token_phase_call():
+    import torch
+    lens = [257, 64, 1, 300, 31, 150]
+    cfg = wl.custom_config("mxd", len(lens), 8, 1, 128, 320)
+    batch = wl.make_batch(cfg, seed=4200, seq_lens=lens)
+    out, ref, bufs = run_mixed(batch, batch.q, np.arange(len(lens), dtype=np.int32), [1] * len(lens), 1, tag="decode")
+    assert_parity(out, ref, cfg.name)
+    sw.run_batch(bufs, cfg)
+    torch.cuda.synchronize()
+    # a request with one query token is served by the token-phase kernels: the same bits
+    dec = bufs["out"].cpu().numpy().reshape(out.shape)
+    assert np.array_equal(dec.view(np.uint16), out.view(np.uint16))
+
+
+def test_a_prompt_in_pieces_and_the_query_bound():
+    lens = [300, 180]
+    cfg = wl.custom_config("mxc", 2, 8, 1, 128, 320)
+    batch = wl.make_batch(cfg, seed=4300, seq_lens=lens)
+    qt, starts = wl.make_prefill_queries(batch)
+    whole, ref_whole, bufs = run_mixed(batch, qt, starts, lens, 320, tag="whole")
+    # the last 100 / 37 tokens as a second piece: the same rows, up to rounding order
+    q2 = np.concatenate([qt[200:300], qt[300 + 143:300 + 180]])
+    piece, ref_piece, _ = run_mixed(batch, q2, np.array([0, 100], np.int32), [100, 37], 128, bufs=bufs, tag="piece")
+    assert_parity(piece, ref_piece, cfg.name)
+    assert np.array_equal(ref_piece[:100], ref_whole[200:300])
+    assert np.abs(piece[:100].astype(np.float64) - whole[200:300].astype(np.float64)).max() <= 2e-3
+    # q_lens above max_q_len: only the last max_q_len tokens are queries
+    q3 = np.concatenate([qt[236:300], qt[300 + 116:300 + 180]])
+    clamped, ref_c, _ = run_mixed(batch, q3, np.array([0, 64], np.int32), [1000, 90], 64, bufs=bufs, tag="bound")
+    assert_parity(clamped, ref_c, cfg.name)
+    assert np.array_equal(ref_c[:64], ref_whole[236:300]) and np.array_equal(ref_c[64:], ref_whole[300 + 116:300 + 180])
+
+
+def test_mixed_rows_of_no_query_are_untouched():
+    lens = [90, 40, 64]
+    cfg = wl.custom_config("mxu", 3, 4, 2, 128, 96)
+    batch = wl.make_batch(cfg, seed=4400, seq_lens=lens)
+    qt, starts, nq = wl.make_mixed_queries(batch, [10, 0, 33])
+    q2 = np.zeros((80, 4, 128), np.float16)
+    new_starts = np.array([50, 0, 5], np.int32)
+    q2[50:60] = qt[0:10]
+    q2[5:38] = qt[10:43]
+    out, ref, _ = run_mixed(batch, q2, new_starts, [10, 0, 33], 96, tag="gaps")
+    mask = np.zeros(80, bool)
+    mask[50:60] = True
+    mask[5:38] = True
+    assert np.isnan(out[~mask].astype(np.float32)).all()
+    assert_parity(out[mask], ref[mask], cfg.name)
+
+
+@pytest.mark.parametrize("kernel,combine", [(0, 0), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2)])
+def test_token_phase_requests_through_every_decode_variant(kernel, combine, _kernel):
+    if _kernel not in ("default", "shared"):
+        pytest.skip("the prompt kernel is not what varies here")
+    lens = [2600, 1, 700, 0, 3000, 513, 64, 1200]
+    qls = [1, 1, 90, 1, 1, 1, 0, 1]
+    cfg = wl.custom_config("mxv", len(lens), 8, 1, 128, 4096)
+    batch = wl.make_batch(cfg, seed=4500, seq_lens=lens)
+    qt, starts, nq = wl.make_mixed_queries(batch, qls)
+    assert nq.tolist() == [1, 1, 90, 0, 1, 1, 0, 1]
+    # rows in a shuffled order with a gap, so that row != request everywhere
+    order = [5, 0, 3, 6, 1, 7, 2, 4]
+    new_starts = np.zeros(len(lens), np.int32)
+    q2 = np.zeros((qt.shape[0] + 7, 8, 128), np.float16)
+    at = 7
+    for r in order:
+        new_starts[r] = at
+        q2[at:at + nq[r]] = qt[starts[r]:starts[r] + nq[r]]
+        at += int(nq[r])
+    sw.sw_set_param(sw.SW_PARAM_KERNEL, kernel)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, combine)
+    try:
+        out, ref, _ = run_mixed(batch, q2, new_starts, qls, 128, tag="decode variant %d/%d" % (kernel, combine))
+    finally:
+        sw.sw_set_param(sw.SW_PARAM_KERNEL, 0)
+        sw.sw_set_param(sw.SW_PARAM_COMBINE, 0)
+    assert np.isnan(out[:7].astype(np.float32)).all()
+    assert not np.isnan(out[7:].astype(np.float32)).any()
+    assert_parity(out[7:], ref[7:], cfg.name)
+
+
+@pytest.mark.parametrize("n_req", [65, 150, 300])
+def test_many_requests_few_prompts(n_req):
+    # more requests than lanes of a wave: every lane of the length scan holds several
+    rng = np.random.Generator(np.random.Philox(4600 + n_req))
+    lens = rng.integers(0, 201, n_req)
+    kind = rng.integers(0, 8, n_req)
+    qls = np.where(kind == 0, lens, np.where(kind == 1, rng.integers(0, 70, n_req), np.where(kind == 2, 0, 1)))
+    cfg = wl.custom_config("mxm%d" % n_req, n_req, 2, 1, 128, 200)
+    batch = wl.make_batch(cfg, seed=4600 + n_req, seq_lens=lens.tolist())
+    qt, starts, nq = wl.make_mixed_queries(batch, qls.tolist())
+    out, ref, _ = run_mixed(batch, qt, starts, qls.tolist(), 200, tag="many")
+    assert not np.isnan(out.astype(np.float32)).any()
+    assert_parity(out, ref, cfg.name)
