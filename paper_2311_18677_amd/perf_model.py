@@ -44,9 +44,13 @@ def hat_basis(x, knots):
 class PiecewiseLinearModel:
     """time(batch, context): linear inside every cell of (batch knots) x (context knots)."""
 
-    def __init__(self, batch_knots, context_knots):
+    def __init__(self, batch_knots, context_knots, log_time=False):
+        """log_time: fit log2(time) instead of time, i.e. a power law inside every cell; the
+        choice for quantities that grow faster than linearly (prompt attention is quadratic
+        in the prompt length)."""
         self.bk = np.log2(np.asarray(batch_knots, dtype=np.float64))
         self.ck = np.log2(np.asarray(context_knots, dtype=np.float64))
+        self.log_time = bool(log_time)
         self.coef = None
 
     def _design(self, batch, context):
@@ -59,13 +63,15 @@ class PiecewiseLinearModel:
         # a small ridge keeps grid nodes that no training point touches finite
         lam = 1e-9
         ata = a.T @ a + lam * np.eye(a.shape[1])
-        self.coef = np.linalg.solve(ata, a.T @ np.asarray(t, dtype=np.float64))
+        t = np.asarray(t, dtype=np.float64)
+        self.coef = np.linalg.solve(ata, a.T @ (np.log2(t) if self.log_time else t))
         return self
 
     def predict(self, batch, context):
         if self.coef is None:
             raise RuntimeError("fit first")
-        return self._design(batch, context) @ self.coef
+        y = self._design(batch, context) @ self.coef
+        return np.exp2(y) if self.log_time else y
 
 
 class RegimeModel:
@@ -121,7 +127,7 @@ def split_80_20(n, seed=0):
     return np.sort(order[n_test:]), np.sort(order[:n_test])
 
 
-def evaluate(batch, context, t, batch_knots, context_knots, seed=0, regimes=None):
+def evaluate(batch, context, t, batch_knots, context_knots, seed=0, regimes=None, log_time=False):
     """Fit on 80 %, report MAPE on the held-out 20 % and on the training points.
 
     With `regimes` (see RegimeModel) the context axis is cut there and context_knots is unused.
@@ -131,7 +137,7 @@ def evaluate(batch, context, t, batch_knots, context_knots, seed=0, regimes=None
     if regimes is not None:
         m = RegimeModel(batch_knots, regimes)
     else:
-        m = PiecewiseLinearModel(batch_knots, context_knots)
+        m = PiecewiseLinearModel(batch_knots, context_knots, log_time=log_time)
     m.fit(batch[tr], context[tr], t[tr])
     return {"train_mape": mape(m.predict(batch[tr], context[tr]), t[tr]),
             "test_mape": mape(m.predict(batch[te], context[te]), t[te]),
@@ -215,6 +221,88 @@ def sweep(path):
     return 0
 
 
+# ---- the prompt phase: time of one sw_prefill_attn call vs (prompts in the batch, prompt length)
+
+PROMPT_COUNTS = (1, 2, 3, 4, 6, 8, 12, 16)
+PROMPT_LENS = (64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 8192)
+PROMPT_MAX_TOKENS = 32768           # batches above this many tokens are left out of the grid
+PROMPT_COUNT_KNOTS = (1, 2, 4, 8, 16)
+PROMPT_LEN_KNOTS = (64, 128, 256, 512, 1024, 2048, 4096, 8192)
+
+
+def measure_prompt_point(sw, torch, n_req, plen, n_qh=8, n_kvh=1, d=128, calls=960, n_sets=3):
+    """Microseconds per sw_prefill_attn call on n_req prompts of plen tokens each."""
+    dev = torch.device("cuda:0")
+    lay = sw.sw_kv_layout(n_req, n_kvh, d, plen)
+    n_tokens = n_req * plen
+    g = torch.Generator(device=dev)
+    g.manual_seed(7000 * n_req + plen)
+    sets = []
+    for _ in range(n_sets):
+        s = {}
+        for name in ("k", "v"):
+            s[name] = torch.empty(lay.total_elems, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+        s["q"] = torch.empty(n_tokens * n_qh * d, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+        s["out"] = torch.zeros(n_tokens * n_qh * d, dtype=torch.float16, device=dev)
+        sets.append(s)
+    lens = torch.full((n_req,), plen, dtype=torch.int32, device=dev)
+    starts = (torch.arange(n_req, dtype=torch.int32, device=dev) * plen).contiguous()
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_prefill_attn(s["q"], s["k"], s["v"], lens, starts, s["out"], n_tokens, n_req, n_qh, n_kvh, d, plen, st)
+
+    call(sets[0], stream)
+    stream.synchronize()
+    # many calls per graph, so that the cost of starting a replay disappears in them
+    rounds = 16
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for _ in range(rounds):
+            for s in sets:
+                call(s, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    per_replay = rounds * n_sets
+    # long calls need few repetitions: aim at a few tens of milliseconds per point
+    with torch.cuda.stream(stream):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        graph.replay()
+    torch.cuda.synchronize()
+    once = max(time.perf_counter() - t0, 1e-6)
+    reps = int(max(1, min(max(1, calls // per_replay), 0.03 / once)))
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for _ in range(reps):
+            graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (reps * per_replay) * 1e6
+
+
+def sweep_prompt(path):
+    import torch
+    from . import binding as sw
+    if not torch.cuda.is_available():
+        print("perf_model: no GPU visible", file=sys.stderr)
+        return 1
+    sw.load()
+    with open(path, "w") as f:
+        f.write("# sw_prefill_attn, 8 query heads on 1 KV head, head_dim 128, every prompt of the "
+                "given length\n# prompts prompt_tokens microseconds_per_call\n")
+        for b in PROMPT_COUNTS:
+            for c in PROMPT_LENS:
+                if b * c > PROMPT_MAX_TOKENS:
+                    continue
+                us = measure_prompt_point(sw, torch, b, c)
+                f.write("%d %d %.3f\n" % (b, c, us))
+                f.flush()
+            print("prompts", b, "done", flush=True)
+            torch.cuda.empty_cache()
+    return 0
+
+
 def load_points(path):
     rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
     arr = np.array(rows, dtype=np.float64)
@@ -225,8 +313,22 @@ def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--sweep", metavar="FILE", help="measure the grid on the GPU and write it to FILE")
     ap.add_argument("--fit", metavar="FILE", help="fit the model to FILE (80:20 split) and print the errors")
+    ap.add_argument("--sweep-prompt", metavar="FILE", help="the prompt-phase grid: measure and write to FILE")
+    ap.add_argument("--fit-prompt", metavar="FILE", help="fit the prompt-phase model to FILE (80:20 split)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args(argv)
+    if args.sweep_prompt or args.fit_prompt:
+        if args.sweep_prompt:
+            rc = sweep_prompt(args.sweep_prompt)
+            if rc:
+                return rc
+        b, c, t = load_points(args.fit_prompt or args.sweep_prompt)
+        res = evaluate(b, c, t, PROMPT_COUNT_KNOTS, PROMPT_LEN_KNOTS, seed=args.seed, log_time=True)
+        print("prompt phase: points %d (train %d, test %d)  train MAPE %.2f %%  held-out MAPE %.2f %%"
+              % (b.size, res["n_train"], res["n_test"], res["train_mape"], res["test_mape"]))
+        lin = evaluate(b, c, t, PROMPT_COUNT_KNOTS, PROMPT_LEN_KNOTS, seed=args.seed)
+        print("(linear in time inside a cell instead of a power law: held-out MAPE %.2f %%)" % lin["test_mape"])
+        return 0
     if args.sweep:
         rc = sweep(args.sweep)
         if rc:

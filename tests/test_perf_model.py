@@ -73,3 +73,17 @@ def test_regime_model_fits_a_surface_with_steps_at_the_breaks():
     m = res["model"]
     lo, hi = m.predict([8.0, 8.0], [256.0, 257.0])
     assert hi - lo > 1.5                                          # the step is kept, not smeared
+
+
+def test_power_law_cells_reproduce_a_power_law():
+    # with log_time the model is a power law inside every cell: t = a * b^0.5 * c^2 is exact
+    b, c = np.meshgrid([1, 2, 3, 4, 6, 8], [64, 96, 128, 192, 256, 384, 512], indexing="ij")
+    b, c = b.ravel().astype(float), c.ravel().astype(float)
+    t = 0.01 * np.sqrt(b) * c ** 2
+    m = pm.PiecewiseLinearModel((1, 2, 4, 8), (64, 128, 256, 512), log_time=True).fit(b, c, t)
+    assert pm.mape(m.predict(b, c), t) < 1e-6
+    # the time-linear form cannot follow the quadratic half-way between knots
+    lin = pm.PiecewiseLinearModel((1, 2, 4, 8), (64, 128, 256, 512)).fit(b, c, t)
+    assert pm.mape(lin.predict(b, c), t) > 1.0
+    res = pm.evaluate(b, c, t, (1, 2, 4, 8), (64, 128, 256, 512), log_time=True)
+    assert res["test_mape"] < 1e-6
