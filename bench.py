@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: replay a HIP graph of one rotation; eager: one host call per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-read-ceiling", action="store_true",
+                    help="skip the plain streaming-read kernel timed beside the call (same byte count)")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
@@ -155,6 +157,47 @@ def read_traffic(workload):
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
+
+
+def stream_read_ceiling(sw, torch, n_bytes, dev, launches=400):
+    """What a kernel that only reads n_bytes from HBM achieves on this machine: the practical
+    ceiling for a call bound by such a read.  Rotates over buffers worth four times the
+    last-level cache, as the timed path does; returns per-launch figures (HIP-graph replays
+    for the call time, HIP events on the dispatch for the kernel time)."""
+    n_bytes = max(16, int(n_bytes) // 16 * 16)
+    n_bufs = int(max(2, min(64, -(-4 * LLC_BYTES // n_bytes))))
+    bufs = [torch.empty(n_bytes // 4, dtype=torch.int32, device=dev).random_() for _ in range(n_bufs)]
+    sink = torch.zeros(16384, dtype=torch.int32, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+    sw.sw_stream_read(bufs[0], n_bytes, sink, 0, stream)
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for b in bufs:
+            sw.sw_stream_read(b, n_bytes, sink, 0, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    reps = max(2, launches // n_bufs)
+    with torch.cuda.stream(stream):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for _ in range(reps):
+            graph.replay()
+    torch.cuda.synchronize()
+    call_us = (time.perf_counter() - t0) / (reps * n_bufs) * 1e6
+    n_prof = min(launches, 4 * n_bufs)
+    sw.sw_prof_start(n_prof)
+    for i in range(n_prof):
+        sw.sw_stream_read(bufs[i % n_bufs], n_bytes, sink, 0, stream)
+    k_us, _, n_rec = sw.sw_prof_stop()
+    kernel_us = k_us / max(n_rec, 1)
+    del bufs
+    return {"bytes": n_bytes, "buffers": n_bufs, "call_us": call_us, "call_GBps": n_bytes / call_us / 1e3,
+            "kernel_us": kernel_us, "kernel_GBps": n_bytes / kernel_us / 1e3 if kernel_us > 0 else 0.0,
+            "what": "sw_stream_read: one plain kernel that reads this many bytes once (grid-stride, "
+                    "16 B per lane, 8 loads in flight); a reference point, not a proven ceiling"}
 
 
 def main_prefill(args):
@@ -757,6 +800,12 @@ def main():
         "cpu_baseline": cpu_baseline,
         "parity_set0": parity,
     }
+    if not args.no_read_ceiling:
+        # freed first: the rotation of the ceiling measurement needs its own gigabyte
+        ceiling = stream_read_ceiling(sw, torch, mean_bytes, dev)
+        line["roofline"]["stream_read_ceiling"] = ceiling
+        if ceiling["kernel_GBps"] > 0:
+            line["roofline"]["frac_of_stream_read"] = achieved / ceiling["kernel_GBps"]
     print(json.dumps(line))
 
 

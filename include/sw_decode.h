@@ -386,6 +386,21 @@ int sw_get_param(int key, int *value);
 int sw_prof_start(int capacity);
 int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls);
 
+/*
+ * sw_stream_read -- measurement support: one kernel that reads n_bytes of device
+ * memory once and does nothing else worth mentioning, the practical ceiling to hold the
+ * token-phase call against (that phase is bound by reading the KV cache, section 3.5,
+ * Insight V).  Workgroup b XORs the 32-bit words it reads (a grid-stride walk, 16
+ * bytes per lane) and stores the result in sink[b]; the XOR of sink[0 .. workgroups)
+ * is the XOR of all words of src, which is what the test checks.
+ *   src         DEVICE, 16-byte aligned, n_bytes a multiple of 16 (SW_ERR_ALIGN / SW_ERR_SHAPE).
+ *   sink        DEVICE, uint32 [workgroups], 4-byte aligned, written.
+ *   workgroups  1 .. 65536 workgroups of 256 threads; 0 = the library's choice (2048 below
+ *               128 MB, 16384 from there), in which case sink needs 16384 entries.
+ * Enqueues on `stream` and returns; recorded by sw_prof_start/stop as a "partial" time.
+ */
+int sw_stream_read(const void *src, long long n_bytes, void *sink, int workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,7 @@ EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_at
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
            "sw_prefill_attn", "sw_mixed_attn", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release",
-           "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop")
+           "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop", "sw_stream_read")
 
 
 class sw_kv_layout_t(ctypes.Structure):
@@ -111,6 +111,8 @@ def load():
     lib.sw_set_param.argtypes = [ci, ci]
     lib.sw_get_param.restype = ci
     lib.sw_get_param.argtypes = [ci, ctypes.POINTER(ci)]
+    lib.sw_stream_read.restype = ci
+    lib.sw_stream_read.argtypes = [vp, ctypes.c_longlong, vp, ci, vp]
     lib.sw_prof_start.restype = ci
     lib.sw_prof_start.argtypes = [ci]
     lib.sw_prof_stop.restype = ci
@@ -282,6 +284,12 @@ def sw_prof_stop():
     p, c, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
     _check(load().sw_prof_stop(ctypes.byref(p), ctypes.byref(c), ctypes.byref(n)))
     return p.value, c.value, n.value
+
+
+def sw_stream_read(src, n_bytes, sink, workgroups=0, stream=None, check=True):
+    """Measurement support: read n_bytes once; sink[b] = XOR of the words workgroup b read."""
+    rc = load().sw_stream_read(_ptr(src), int(n_bytes), _ptr(sink), int(workgroups), _stream(stream))
+    return _check(rc) if check else rc
 
 
 # ---- device-memory plumbing (PyTorch) ------------------------------------------------

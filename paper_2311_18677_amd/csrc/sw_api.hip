@@ -775,6 +775,31 @@ int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream)
     return SW_OK;
 }
 
+int sw_stream_read(const void *src, long long n_bytes, void *sink, int workgroups, void *stream)
+{
+    if (n_bytes < 0 || (n_bytes & 15)) return fail(SW_ERR_SHAPE, "n_bytes must be a non-negative multiple of 16");
+    if (workgroups < 0 || workgroups > 65536) return fail(SW_ERR_SHAPE, "workgroups must be in [0, 65536]");
+    // measured best: eight workgroups per compute unit up to about 128 MB, 64 beyond
+    if (workgroups == 0) workgroups = n_bytes < (128LL << 20) ? 2048 : 16384;
+    if (!src || !sink) return fail(SW_ERR_NULL, "src and sink must be non-NULL");
+    if ((uintptr_t)src & 15u) return fail(SW_ERR_ALIGN, "src must be 16-byte aligned");
+    if ((uintptr_t)sink & 3u) return fail(SW_ERR_ALIGN, "sink must be 4-byte aligned");
+    bool prof = false;
+    SwLaunchEvents ev = {nullptr, nullptr};
+    ProfRec rec;
+    int prc = prof_begin(rec, false, &prof);
+    if (prc != SW_OK) return prc;
+    if (prof) ev = {rec.ev[0], rec.ev[1]};
+    hipError_t e = sw_launch_stream_read(src, (unsigned long long)n_bytes, (unsigned *)sink, workgroups,
+                                         (hipStream_t)stream, prof ? &ev : nullptr);
+    if (e != hipSuccess) {
+        if (prof) prof_abort(rec);
+        return fail_hip(e, "kernel launch");
+    }
+    if (prof) prof_commit(rec);
+    return SW_OK;
+}
+
 int sw_kv_paged_layout(int n_blocks, int n_kvh, int head_dim, int block_size,
                        sw_kv_paged_layout_t *out)
 {

@@ -166,6 +166,8 @@ hipError_t sw_launch_kv_span_plan(const int32_t *block_table, const int32_t *seq
                                   int32_t *span_first, int32_t *span_blocks, int32_t *n_spans,
                                   int n_req, int block_shift, int max_blocks, int n_blocks,
                                   hipStream_t stream);
+hipError_t sw_launch_stream_read(const void *src, unsigned long long n_bytes, unsigned *sink,
+                                 int workgroups, hipStream_t stream, const SwLaunchEvents *ev);
 hipError_t sw_launch_advance_lens(int32_t *seq_lens, int n_req, int max_len, hipStream_t stream);
 
 // Granularity the chunk length must be a multiple of (all kernels).

@@ -232,3 +232,16 @@ def test_mixed_validation():
     assert mcall(d=64) == sw.SW_ERR_UNSUPPORTED
     assert mcall(n_tokens=0) == sw.SW_OK
     assert mcall(n_req=0) == sw.SW_OK
+
+
+def test_stream_read_validation():
+    def rcall(src=0x1000, n=4096, sink=0x2000, wg=0):
+        return sw.sw_stream_read(src, n, sink, wg, None, check=False)
+    assert rcall(n=-16) == sw.SW_ERR_SHAPE
+    assert rcall(n=100) == sw.SW_ERR_SHAPE
+    assert rcall(wg=-1) == sw.SW_ERR_SHAPE
+    assert rcall(wg=70000) == sw.SW_ERR_SHAPE
+    assert rcall(src=None) == sw.SW_ERR_NULL
+    assert rcall(sink=None) == sw.SW_ERR_NULL
+    assert rcall(src=0x1008) == sw.SW_ERR_ALIGN
+    assert rcall(sink=0x2002) == sw.SW_ERR_ALIGN
