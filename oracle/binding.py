@@ -84,6 +84,13 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+        lib.sw_oracle_mixed_attn_paged.restype = ctypes.c_int
+        lib.sw_oracle_mixed_attn_paged.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
         lib.sw_oracle_half_to_double.restype = ctypes.c_double
         lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
         lib.sw_oracle_max_threads.restype = ctypes.c_int
@@ -174,6 +181,39 @@ def decode_attn_paged(q, k_pool, v_pool, block_table, seq_lens, n_req, n_qh, n_k
         stride_block, stride_kvh, stride_tok, int(n_threads))
     if rc < 0:
         raise ValueError("sw_oracle_decode_attn_paged rejected its arguments (code %d)" % rc)
+    return ref
+
+
+def mixed_attn_paged(q, k_pool, v_pool, block_table, seq_lens, q_starts, q_lens, n_req, n_qh, n_kvh,
+                     head_dim, block_size, max_blocks, n_blocks, max_q_len, stride_block, stride_kvh,
+                     stride_tok, n_threads=0):
+    """Mixed-batch causal attention over a block-table cache (q_lens None: every cached token is a
+    query, i.e. the prompt phase).  Returns ref float64 [n_tokens, n_qh, head_dim]."""
+    lib = _load()
+    q = _as_u16(q, "q")
+    k_pool = _as_u16(k_pool, "k_pool")
+    v_pool = _as_u16(v_pool, "v_pool")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    starts = np.ascontiguousarray(np.asarray(q_starts, dtype=np.int32))
+    table = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    qlens = None if q_lens is None else np.ascontiguousarray(np.asarray(q_lens, dtype=np.int32))
+    if lens.size != n_req or starts.size != n_req or table.size != n_req * max_blocks or \
+            (qlens is not None and qlens.size != n_req):
+        raise ValueError("seq_lens / q_starts / q_lens / block_table have the wrong number of entries")
+    if q.size % (n_qh * head_dim):
+        raise ValueError("q is not a whole number of token rows")
+    n_tokens = q.size // (n_qh * head_dim)
+    need = (n_blocks - 1) * stride_block + (n_kvh - 1) * stride_kvh + (block_size - 1) * stride_tok + head_dim
+    if k_pool.size < need or v_pool.size < need:
+        raise ValueError("pools are smaller than the strides address")
+    ref = np.zeros((n_tokens, n_qh, head_dim), dtype=np.float64)
+    rc = lib.sw_oracle_mixed_attn_paged(
+        q.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data, table.ctypes.data, lens.ctypes.data,
+        starts.ctypes.data, None if qlens is None else qlens.ctypes.data, ref.ctypes.data,
+        n_req, n_qh, n_kvh, head_dim, block_size, max_blocks, n_blocks, max_q_len, n_tokens,
+        stride_block, stride_kvh, stride_tok, int(n_threads))
+    if rc < 0:
+        raise ValueError("sw_oracle_mixed_attn_paged rejected its arguments (code %d)" % rc)
     return ref
 
 

@@ -432,6 +432,96 @@ int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t 
 }
 
 /*
+ * Mixed-batch attention over a block-table cache: sw_oracle_mixed_attn with the
+ * addressing of sw_oracle_decode_attn_paged (positions [i*block_size, (i+1)*block_size)
+ * of request r live in pool block block_table[r*max_blocks + i]; lengths clamp to
+ * [0, max_blocks*block_size], block ids to [0, n_blocks-1]).  q_lens == NULL makes
+ * every cached token a query (the prompt phase).  Each (request, key/value head)
+ * gathers its rows into a dense temporary and the rows of its queries go through the
+ * same two-pass routine.  Pinned: equal, bit for bit, to sw_oracle_mixed_attn on the
+ * dense cache of the same batch (tests/test_oracle_pins.py).
+ */
+int sw_oracle_mixed_attn_paged(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
+                               const int32_t *block_table, const int32_t *seq_lens,
+                               const int32_t *q_starts, const int32_t *q_lens, double *ref,
+                               int n_req, int n_qh, int n_kvh, int head_dim,
+                               int block_size, int max_blocks, int n_blocks, int max_q_len,
+                               int64_t n_tokens,
+                               int64_t stride_block, int64_t stride_kvh, int64_t stride_tok,
+                               int n_threads)
+{
+    if (n_req < 0 || n_qh <= 0 || n_kvh <= 0 || head_dim <= 0 || block_size <= 0 ||
+        max_blocks <= 0 || n_blocks <= 0 || max_q_len <= 0 || n_tokens < 0) return -1;
+    if (n_qh % n_kvh != 0) return -2;
+    if (n_req == 0) return 1;
+    if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !q_starts || !ref) return -3;
+    const int64_t max_len = (int64_t)max_blocks * block_size;
+    for (int r = 0; r < n_req; ++r) {
+        int64_t L64 = seq_lens[r];
+        int L = (int)(L64 < 0 ? 0 : (L64 > max_len ? max_len : L64));
+        int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
+        if (nq > 0 && (q_starts[r] < 0 || (int64_t)q_starts[r] + nq > n_tokens)) return -5;
+    }
+    const int group = n_qh / n_kvh;
+    const int64_t units = (int64_t)n_req * n_kvh;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    if ((int64_t)n_threads > units) n_threads = (int)units;
+    used = n_threads;
+#else
+    (void)n_threads;
+#endif
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(n_threads)
+#endif
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)max_len);
+        uint16_t *kd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
+        uint16_t *vd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
+        if (!scores || !kd || !vd) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t u = 0; u < units; ++u) {
+            if (!scores || !kd || !vd) continue;
+            int r = (int)(u / n_kvh);
+            int g = (int)(u % n_kvh);
+            int64_t L64 = seq_lens[r];
+            int L = (int)(L64 < 0 ? 0 : (L64 > max_len ? max_len : L64));
+            int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
+            int p0 = L - nq;                                 /* position of the first query token */
+            if (nq == 0) continue;
+            for (int t = 0; t < L; ++t) {
+                int b = clampi(block_table[(int64_t)r * max_blocks + t / block_size], 0, n_blocks - 1);
+                int64_t off = (int64_t)b * stride_block + (int64_t)g * stride_kvh +
+                              (int64_t)(t % block_size) * stride_tok;
+                memcpy(kd + (size_t)t * head_dim, k_pool + off, sizeof(uint16_t) * (size_t)head_dim);
+                memcpy(vd + (size_t)t * head_dim, v_pool + off, sizeof(uint16_t) * (size_t)head_dim);
+            }
+            for (int hh = 0; hh < group; ++hh) {
+                int h = g * group + hh;
+                for (int i = 0; i < nq; ++i) {
+                    int64_t row = ((int64_t)q_starts[r] + i) * n_qh + h;
+                    attend_one(q + row * head_dim, kd, vd, p0 + i + 1, head_dim, head_dim, scores,
+                               ref + row * head_dim, NULL, NULL);
+                }
+            }
+        }
+        free(scores);
+        free(kd);
+        free(vd);
+    }
+    return failed ? -4 : used;
+}
+
+/*
  * KV-cache hand-off (sections 4.3 and 5.1: the prompt machine ships each layer's
  * KV cache to the token machine, block by block, merging blocks that are contiguous
  * so that fewer transfers are issued).  Three plain routines cover the part of it

@@ -561,3 +561,40 @@ def test_a_prompt_in_two_pieces_gives_the_rows_of_the_prompt_in_one_piece():
     e = oracle.mixed_attn(qt[:8], k, v, [5, 3], [0, 2], [99, -4], 2, 4, 4, 64, 40, 2, sr, sg, st)
     f = oracle.mixed_attn(qt[:8], k, v, [5, 3], [0, 2], [2, 0], 2, 4, 4, 64, 40, 40, sr, sg, st)
     assert np.array_equal(e, f) and not e[2:].any()
+
+
+@pytest.mark.parametrize("block_size", [4, 8, 16])
+def test_paged_mixed_batch_equals_the_dense_routine_bit_for_bit(block_size):
+    lens = [40, 23, 1, 0, 17]
+    cfg, b, qt, starts, k, v, (sr, sg, st), ref = _prefill_case(4, 2, 64, 40, lens, 110 + block_size)
+    sb, sgp, stp = wl.dense_paged_layout(cfg, block_size)
+    max_blocks = -(-40 // block_size)
+    n_blocks = sum(-(-L // block_size) for L in lens) + 5
+    kp, vp, table = wl.pack_paged(b.k_rows, b.v_rows, cfg, block_size, sb, sgp, stp, n_blocks,
+                                  seed=block_size, pad_bits=0x7E00)
+    # every cached token a query: the prompt phase
+    full = oracle.mixed_attn_paged(qt, kp, vp, table, b.seq_lens, starts, None, 5, 4, 2, 64,
+                                   block_size, max_blocks, n_blocks, 40, sb, sgp, stp)
+    assert np.array_equal(full, ref)
+    # a mixed batch: prompt, piece, token phase, nothing, token phase
+    qls = [40, 9, 1, 0, 1]
+    qm, sm, nq = wl.make_mixed_queries(b, qls)
+    dense = oracle.mixed_attn(qm, k, v, b.seq_lens, sm, qls, 5, 4, 2, 64, 40, 40, sr, sg, st)
+    paged = oracle.mixed_attn_paged(qm, kp, vp, table, b.seq_lens, sm, qls, 5, 4, 2, 64,
+                                    block_size, max_blocks, n_blocks, 40, sb, sgp, stp)
+    assert np.array_equal(paged, dense) and dense.any()
+    # the bound on the queries of a request
+    dense = oracle.mixed_attn(qm, k, v, b.seq_lens, sm, qls, 5, 4, 2, 64, 40, 7, sr, sg, st)
+    paged = oracle.mixed_attn_paged(qm, kp, vp, table, b.seq_lens, sm, qls, 5, 4, 2, 64,
+                                    block_size, max_blocks, n_blocks, 7, sb, sgp, stp)
+    assert np.array_equal(paged, dense)
+    # block ids out of range are clamped into the pool, lengths to the table's reach
+    wild = table.copy()
+    wild[0, 0] = n_blocks + 100
+    ok = table.copy()
+    ok[0, 0] = n_blocks - 1
+    a = oracle.mixed_attn_paged(qm, kp, vp, wild, [99, 23, 1, 0, 17], sm, qls, 5, 4, 2, 64,
+                                block_size, max_blocks, n_blocks, 40, sb, sgp, stp)
+    c = oracle.mixed_attn_paged(qm, kp, vp, ok, [max_blocks * block_size, 23, 1, 0, 17], sm, qls, 5, 4, 2, 64,
+                                block_size, max_blocks, n_blocks, 40, sb, sgp, stp)
+    assert np.array_equal(a, c, equal_nan=True)
