@@ -241,7 +241,10 @@ def main_prefill(args):
             qt = qt0 if i == 0 else wl.make_mixed_queries(b, qlens0)[0]
         else:
             qt = qt0 if i == 0 else wl.make_prefill_queries(b)[0]
-        bufs = sw.upload_batch(b, device="cuda:0", pad_bits=0)
+        if args.paged:
+            bufs = sw.upload_paged_batch(b, args.paged, device="cuda:0", pad_bits=0, seed=i)
+        else:
+            bufs = sw.upload_batch(b, device="cuda:0", pad_bits=0)
         bufs["qt"] = torch.from_numpy(qt.view(np.int16).reshape(-1)).to(dev).view(torch.float16)
         bufs["starts"] = torch.from_numpy(starts0).to(dev)
         if mixed:
@@ -254,7 +257,16 @@ def main_prefill(args):
     stream = torch.cuda.Stream(device=dev)
 
     def call(s, st):
-        if mixed:
+        if args.paged and mixed:
+            sw.sw_mixed_attn_paged(s["qt"], s["k_pool"], s["v_pool"], s["block_table"], s["seq_lens"],
+                                   s["starts"], s["qlens"], s["pout"], n_tokens, cfg.n_req, cfg.n_qh,
+                                   cfg.n_kvh, cfg.head_dim, s["block_size"], s["max_blocks"],
+                                   s["n_blocks"], max_q, st)
+        elif args.paged:
+            sw.sw_prefill_attn_paged(s["qt"], s["k_pool"], s["v_pool"], s["block_table"], s["seq_lens"],
+                                     s["starts"], s["pout"], n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh,
+                                     cfg.head_dim, s["block_size"], s["max_blocks"], s["n_blocks"], st)
+        elif mixed:
             sw.sw_mixed_attn(s["qt"], s["k_cache"], s["v_cache"], s["seq_lens"], s["starts"], s["qlens"],
                              s["pout"], n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
                              cfg.max_len, max_q, st)
@@ -314,28 +326,55 @@ def main_prefill(args):
     if not args.no_cpu_baseline:
         import oracle
         lay = sets[0]["layout"]
+        # A bounded sample of the same workload: the last S query tokens of every request
+        # (the expensive ones), S the largest that keeps the oracle near twenty seconds.
+        nq_all = np.asarray(qlens0 if mixed else np.clip(batch0.seq_lens, 0, cfg.max_len), dtype=np.int64)
+        budget = 2.5e10
+        lo_s, hi_s = 1, int(max(nq_all.max(), 1))
+        while lo_s < hi_s:
+            mid = (lo_s + hi_s + 1) // 2
+            if wl.mixed_flops(cfg, batch0.seq_lens, np.minimum(nq_all, mid)) <= budget:
+                lo_s = mid
+            else:
+                hi_s = mid - 1
+        nq_s = np.minimum(nq_all, lo_s).astype(np.int32)
+        starts_s = (np.asarray(starts0, dtype=np.int64) + nq_all - nq_s).astype(np.int32)
+        flops_s = wl.mixed_flops(cfg, batch0.seq_lens, nq_s)
         c0 = time.perf_counter()
-        if mixed:
-            ref, used = oracle.mixed_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
-                                          starts0, qlens0, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
-                                          cfg.max_len, max_q, lay.stride_req, lay.stride_kvh,
-                                          lay.stride_tok, return_threads=True)
+        if args.paged:
+            s0 = sets[0]
+            pl = s0["layout"]
+            ref = oracle.mixed_attn_paged(qt0, s0["k_host"], s0["v_host"], s0["table_host"],
+                                          batch0.seq_lens, starts_s, nq_s, cfg.n_req,
+                                          cfg.n_qh, cfg.n_kvh, cfg.head_dim, s0["block_size"],
+                                          s0["max_blocks"], s0["n_blocks"], cfg.max_len,
+                                          pl.stride_block, pl.stride_kvh, pl.stride_tok)
+            used = oracle.max_threads()
         else:
-            ref, used = oracle.prefill_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
-                                            starts0, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
-                                            cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok,
-                                            return_threads=True)
+            ref, used = oracle.mixed_attn(qt0, sets[0]["k_host"], sets[0]["v_host"], batch0.seq_lens,
+                                          starts_s, nq_s, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                                          cfg.max_len, cfg.max_len, lay.stride_req, lay.stride_kvh,
+                                          lay.stride_tok, return_threads=True)
         t_cpu = time.perf_counter() - c0
-        cpu_baseline = {"value": flops / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(used),
+        rows = np.zeros(n_tokens, dtype=bool)
+        for r in range(cfg.n_req):
+            rows[starts_s[r]:starts_s[r] + nq_s[r]] = True
+        whole = bool((nq_s == nq_all).all())
+        cpu_baseline = {"value": flops_s / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(used),
                         "kind": "oracle",
-                        "sample": "set 0 of %s, the whole prompt batch once, %.1f s" % (cfg.name, t_cpu)}
+                        "sample": "set 0 of %s, %s (%d of %d query tokens, %.2f of %.2f GFLOP), once, %.1f s"
+                                  % (cfg.name, "the whole batch" if whole else
+                                     "the last %d query tokens of every request" % lo_s,
+                                     int(rows.sum()), n_tokens, flops_s / 1e9, flops / 1e9, t_cpu)}
         call(sets[0], stream)
         stream.synchronize()
-        out = sets[0]["pout"].cpu().numpy().astype(np.float64)
+        out = sets[0]["pout"].cpu().numpy().astype(np.float64)[rows]
+        ref = ref[rows]
         diff = out - ref
         den = np.sqrt((ref ** 2).sum(-1))
         rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
-        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max()),
+                  "rows_checked": int(rows.sum())}
 
     tflops = flops * steps / elapsed / 1e12
     line = {
@@ -348,7 +387,9 @@ def main_prefill(args):
         "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_qh": cfg.n_qh, "n_kvh": cfg.n_kvh,
                    "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
                    "prompt_tokens": n_tokens, "flops_per_step": flops, "cache_sets": n_sets,
-                   "launch": mode, "entry_point": "sw_prefill_attn"},
+                   "launch": mode, "entry_point": "sw_prefill_attn" + ("_paged" if args.paged else ""),
+                   "kv_layout": ("block pools, block_size %d" % args.paged) if args.paged
+                   else "dense, padded to max_len"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
                      "kernel": "sw_prefill_mfma_kernel", "kernel_us": kernel_us,
@@ -367,7 +408,7 @@ def main_prefill(args):
         line["unit"] = "calls/s"
         line.pop("pct_of_peak")
         line.pop("prompt_tokens_per_s_attention_only")
-        line["config"]["entry_point"] = "sw_mixed_attn"
+        line["config"]["entry_point"] = "sw_mixed_attn" + ("_paged" if args.paged else "")
         line["config"]["query_tokens"] = n_tokens
         line["config"]["prompt_requests"] = int((qlens0 > 1).sum())
         line["config"]["algorithmic_bytes_per_step"] = kv
@@ -377,8 +418,8 @@ def main_prefill(args):
                             "kernel_us": kernel_us, "bytes_per_launch": kv, "launches_timed": n_rec,
                             "tflops": achieved}
         if cpu_baseline:
-            cpu_baseline["value"] = 1.0 / t_cpu
-            cpu_baseline["unit"] = "calls/s"
+            cpu_baseline["value"] = flops_s / flops / t_cpu
+            cpu_baseline["unit"] = "calls/s (sample time scaled by its share of the flops)"
     print(json.dumps(line))
 
 

@@ -280,6 +280,27 @@ int sw_mixed_attn(const void *q, const void *k_cache, const void *v_cache,
                   void *stream);
 
 /*
+ * sw_prefill_attn_paged, sw_mixed_attn_paged -- the two calls above over block pools
+ * (the layout of sw_decode_attn_paged: position t of request r is row t % block_size
+ * of pool block block_table[r * max_blocks + t / block_size]; the paper's prototype
+ * keeps the cache in such blocks, section 5.1).  max_len is max_blocks * block_size;
+ * lengths clamp to it, block ids to [0, n_blocks - 1]; table entries past a request's
+ * last block are never followed.  block_size: a power of two in [4, 4096]
+ * (SW_ERR_UNSUPPORTED); max_blocks * block_size at most 2^23 (SW_ERR_SHAPE).
+ * Token-phase requests of a mixed batch give the bits of sw_decode_attn_paged.
+ * Everything else as in sw_prefill_attn / sw_mixed_attn.
+ */
+int sw_prefill_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                          const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_starts,
+                          void *out, long long n_tokens, int n_req, int n_qh, int n_kvh, int head_dim,
+                          int block_size, int max_blocks, int n_blocks, void *stream);
+int sw_mixed_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                        const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_starts,
+                        const int32_t *q_lens, void *out, long long n_tokens,
+                        int n_req, int n_qh, int n_kvh, int head_dim,
+                        int block_size, int max_blocks, int n_blocks, int max_q_len, void *stream);
+
+/*
  * KV-cache hand-off, the part inside one GPU's memory.  A prompt machine ships
  * each layer's KV cache to a token machine block by block, merging blocks that
  * are contiguous so that fewer transfers are issued (section 4.3, "KV-cache

@@ -467,37 +467,42 @@ int sw_oracle_mixed_attn_paged(const uint16_t *q, const uint16_t *k_pool, const 
     int used = 1;
 #ifdef _OPENMP
     if (n_threads <= 0) n_threads = omp_get_max_threads();
-    if ((int64_t)n_threads > units) n_threads = (int)units;
     used = n_threads;
 #else
     (void)n_threads;
 #endif
+    /* one dense temporary per call, filled for one (request, key/value head) at a time;
+       the threads share the gather and then the unit's (head, query) rows */
+    uint16_t *kd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
+    uint16_t *vd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
+    if (!kd || !vd) {
+        free(kd);
+        free(vd);
+        return -4;
+    }
     int failed = 0;
 #ifdef _OPENMP
 #pragma omp parallel num_threads(n_threads)
 #endif
     {
         double *scores = (double *)malloc(sizeof(double) * (size_t)max_len);
-        uint16_t *kd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
-        uint16_t *vd = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)max_len * (size_t)head_dim);
-        if (!scores || !kd || !vd) {
+        if (!scores) {
 #ifdef _OPENMP
 #pragma omp atomic write
 #endif
             failed = 1;
         }
-#ifdef _OPENMP
-#pragma omp for schedule(dynamic, 1)
-#endif
         for (int64_t u = 0; u < units; ++u) {
-            if (!scores || !kd || !vd) continue;
             int r = (int)(u / n_kvh);
             int g = (int)(u % n_kvh);
             int64_t L64 = seq_lens[r];
             int L = (int)(L64 < 0 ? 0 : (L64 > max_len ? max_len : L64));
             int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
             int p0 = L - nq;                                 /* position of the first query token */
-            if (nq == 0) continue;
+            if (nq == 0) continue;                           /* the same decision in every thread */
+#ifdef _OPENMP
+#pragma omp for schedule(static)
+#endif
             for (int t = 0; t < L; ++t) {
                 int b = clampi(block_table[(int64_t)r * max_blocks + t / block_size], 0, n_blocks - 1);
                 int64_t off = (int64_t)b * stride_block + (int64_t)g * stride_kvh +
@@ -505,19 +510,24 @@ int sw_oracle_mixed_attn_paged(const uint16_t *q, const uint16_t *k_pool, const 
                 memcpy(kd + (size_t)t * head_dim, k_pool + off, sizeof(uint16_t) * (size_t)head_dim);
                 memcpy(vd + (size_t)t * head_dim, v_pool + off, sizeof(uint16_t) * (size_t)head_dim);
             }
-            for (int hh = 0; hh < group; ++hh) {
-                int h = g * group + hh;
-                for (int i = 0; i < nq; ++i) {
-                    int64_t row = ((int64_t)q_starts[r] + i) * n_qh + h;
-                    attend_one(q + row * head_dim, kd, vd, p0 + i + 1, head_dim, head_dim, scores,
-                               ref + row * head_dim, NULL, NULL);
-                }
+            /* (the loop above ends with a barrier: the temporary is complete) */
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 4)
+#endif
+            for (int64_t w = 0; w < (int64_t)group * nq; ++w) {
+                if (!scores) continue;
+                int h = g * group + (int)(w / nq);
+                int i = (int)(w % nq);
+                int64_t row = ((int64_t)q_starts[r] + i) * n_qh + h;
+                attend_one(q + row * head_dim, kd, vd, p0 + i + 1, head_dim, head_dim, scores,
+                           ref + row * head_dim, NULL, NULL);
             }
+            /* (and so does this one: nobody refills the temporary while it is read) */
         }
         free(scores);
-        free(kd);
-        free(vd);
     }
+    free(kd);
+    free(vd);
     return failed ? -4 : used;
 }
 

@@ -31,7 +31,7 @@ SW_PARAM_PREFILL_KERNEL = 7
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
-           "sw_prefill_attn", "sw_mixed_attn", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
+           "sw_prefill_attn", "sw_mixed_attn", "sw_prefill_attn_paged", "sw_mixed_attn_paged", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop", "sw_stream_read")
 
@@ -111,6 +111,12 @@ def load():
     lib.sw_set_param.argtypes = [ci, ci]
     lib.sw_get_param.restype = ci
     lib.sw_get_param.argtypes = [ci, ctypes.POINTER(ci)]
+    lib.sw_prefill_attn_paged.restype = ci
+    lib.sw_prefill_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_longlong,
+                                          ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.sw_mixed_attn_paged.restype = ci
+    lib.sw_mixed_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_longlong,
+                                        ci, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.sw_stream_read.restype = ci
     lib.sw_stream_read.argtypes = [vp, ctypes.c_longlong, vp, ci, vp]
     lib.sw_prof_start.restype = ci
@@ -284,6 +290,27 @@ def sw_prof_stop():
     p, c, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
     _check(load().sw_prof_stop(ctypes.byref(p), ctypes.byref(c), ctypes.byref(n)))
     return p.value, c.value, n.value
+
+
+def sw_prefill_attn_paged(q, k_pool, v_pool, block_table, seq_lens, q_starts, out, n_tokens, n_req, n_qh,
+                          n_kvh, head_dim, block_size, max_blocks, n_blocks, stream=None, check=True):
+    """Prompt-phase (causal) attention over block pools + block table."""
+    rc = load().sw_prefill_attn_paged(_ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                      _ptr(seq_lens), _ptr(q_starts), _ptr(out), int(n_tokens), n_req,
+                                      n_qh, n_kvh, head_dim, block_size, max_blocks, n_blocks,
+                                      _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_mixed_attn_paged(q, k_pool, v_pool, block_table, seq_lens, q_starts, q_lens, out, n_tokens, n_req,
+                        n_qh, n_kvh, head_dim, block_size, max_blocks, n_blocks, max_q_len,
+                        stream=None, check=True):
+    """Mixed-batch attention over block pools + block table."""
+    rc = load().sw_mixed_attn_paged(_ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                    _ptr(seq_lens), _ptr(q_starts), _ptr(q_lens), _ptr(out),
+                                    int(n_tokens), n_req, n_qh, n_kvh, head_dim, block_size, max_blocks,
+                                    n_blocks, max_q_len, _stream(stream))
+    return _check(rc) if check else rc
 
 
 def sw_stream_read(src, n_bytes, sink, workgroups=0, stream=None, check=True):

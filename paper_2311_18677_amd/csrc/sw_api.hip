@@ -534,8 +534,15 @@ int sw_decode_attn_append(const void *q, const void *k_new, const void *v_new,
                         n_req, n_qh, n_kvh, head_dim, max_len, stream);
 }
 
-// sw_prefill_attn (q_lens == NULL: every cached token is a query) and sw_mixed_attn
-static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
+// Block-table geometry of the paged entry points (block_table == NULL: dense layout).
+struct PagedGeom {
+    const int32_t *block_table;
+    int block_size, max_blocks, n_blocks;
+};
+
+// sw_prefill_attn (q_lens == NULL: every cached token is a query) and sw_mixed_attn, dense
+// (pg == NULL) or over block pools (then max_len is max_blocks * block_size)
+static int causal_attn(const void *q, const void *k_cache, const void *v_cache, const PagedGeom *pg,
                        const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
                        bool mixed, void *out, long long n_tokens,
                        int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int max_q_len,
@@ -545,6 +552,16 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
     if (n_qh <= 0) return fail(SW_ERR_SHAPE, "n_qh must be > 0");
     if (n_kvh <= 0 || n_qh % n_kvh != 0)
         return fail(SW_ERR_SHAPE, "n_kvh must be > 0 and divide n_qh");
+    if (pg) {
+        if (pg->block_size < 4 || pg->block_size > 4096 || (pg->block_size & (pg->block_size - 1)))
+            return fail(SW_ERR_UNSUPPORTED, "block_size must be a power of two in [4, 4096]");
+        if (pg->max_blocks <= 0 || pg->n_blocks <= 0)
+            return fail(SW_ERR_SHAPE, "max_blocks and n_blocks must be > 0");
+        if ((long long)pg->max_blocks * pg->block_size > (1 << 23))
+            return fail(SW_ERR_SHAPE, "max_blocks * block_size above 2^23");
+        max_len = pg->max_blocks * pg->block_size;
+        if (!mixed) max_q_len = max_len;
+    }
     int rc = check_shape(n_req, n_kvh, head_dim, max_len);
     if (rc != SW_OK) return rc;
     if (n_tokens < 0 || n_tokens > (1LL << 31)) return fail(SW_ERR_SHAPE, "n_tokens must be in [0, 2^31]");
@@ -555,6 +572,8 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
     if (n_req == 0 || n_tokens == 0) return SW_OK;
     if (!q || !k_cache || !v_cache || !seq_lens || !q_starts || !out || (mixed && !q_lens))
         return fail(SW_ERR_NULL, "q, k_cache, v_cache, seq_lens, q_starts, q_lens and out must be non-NULL");
+    if (pg && !pg->block_table) return fail(SW_ERR_NULL, "block_table must be non-NULL");
+    if (pg && ((uintptr_t)pg->block_table & 3u)) return fail(SW_ERR_ALIGN, "block_table must be 4-byte aligned");
     if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u)
         return fail(SW_ERR_ALIGN, "q, k_cache, v_cache and out must be 16-byte aligned");
     if (((uintptr_t)seq_lens | (uintptr_t)q_starts | (uintptr_t)q_lens) & 3u)
@@ -584,6 +603,7 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
     // tile among the heads of a group.
     int which = g_prefill_kernel;
     if (which == 0) which = (a.group > 8 || max_len <= kPrefillSplitMaxLen) ? 2 : 1;
+    if (pg) which = 2;              // the only kernel with block-table addressing
     if (which == 1 && a.group > 8)
         return fail(SW_ERR_UNSUPPORTED, "the shared-tile prompt kernel takes at most 8 query heads per key/value head");
     int split_waves = 4;
@@ -597,8 +617,22 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
         if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
     }
     a.n_qblocks = (max_q_len + 32 * a.qw - 1) / (32 * a.qw);      // the grid covers max_q_len query tokens
-    a.stride_kvh = slab_elems(head_dim, max_len);
-    a.stride_req = a.stride_kvh * n_kvh;
+    if (pg) {
+        a.block_table = pg->block_table;
+        a.block_shift = 0;
+        while ((1 << a.block_shift) < pg->block_size) ++a.block_shift;
+        a.max_blocks = pg->max_blocks;
+        a.n_blocks = pg->n_blocks;
+        a.stride_kvh = (long long)pg->block_size * head_dim;
+        a.stride_block = a.stride_kvh * n_kvh;
+        a.stride_req = 0;
+    } else {
+        a.block_table = nullptr;
+        a.block_shift = a.max_blocks = a.n_blocks = 0;
+        a.stride_block = 0;
+        a.stride_kvh = slab_elems(head_dim, max_len);
+        a.stride_req = a.stride_kvh * n_kvh;
+    }
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     if ((long long)n_req * n_qh * a.n_qblocks > 0x7fffffffLL)
         return fail(SW_ERR_SHAPE, "too many workgroups");
@@ -614,8 +648,10 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache,
         in.seq_lens = seq_lens;
         in.out = out;
         in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
-        in.block_table = nullptr;
-        in.block_size = in.max_blocks = in.n_blocks = 0;
+        in.block_table = pg ? pg->block_table : nullptr;
+        in.block_size = pg ? pg->block_size : 0;
+        in.max_blocks = pg ? pg->max_blocks : 0;
+        in.n_blocks = pg ? pg->n_blocks : 0;
         in.stream = (hipStream_t)stream_v;
         in.q_rows = q_starts; in.q_lens = q_lens; in.n_rows = n_tokens; in.max_q = max_q_len;
         rc = run_step(in);
@@ -645,8 +681,29 @@ int sw_prefill_attn(const void *q, const void *k_cache, const void *v_cache,
                     const int32_t *seq_lens, const int32_t *q_starts, void *out, long long n_tokens,
                     int n_req, int n_qh, int n_kvh, int head_dim, int max_len, void *stream)
 {
-    return causal_attn(q, k_cache, v_cache, seq_lens, q_starts, nullptr, false, out, n_tokens,
+    return causal_attn(q, k_cache, v_cache, nullptr, seq_lens, q_starts, nullptr, false, out, n_tokens,
                        n_req, n_qh, n_kvh, head_dim, max_len, max_len > 0 ? max_len : 1, stream);
+}
+
+int sw_prefill_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                          const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_starts,
+                          void *out, long long n_tokens, int n_req, int n_qh, int n_kvh, int head_dim,
+                          int block_size, int max_blocks, int n_blocks, void *stream)
+{
+    const PagedGeom pg = {block_table, block_size, max_blocks, n_blocks};
+    return causal_attn(q, k_pool, v_pool, &pg, seq_lens, q_starts, nullptr, false, out, n_tokens,
+                       n_req, n_qh, n_kvh, head_dim, 1, 1, stream);
+}
+
+int sw_mixed_attn_paged(const void *q, const void *k_pool, const void *v_pool,
+                        const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_starts,
+                        const int32_t *q_lens, void *out, long long n_tokens,
+                        int n_req, int n_qh, int n_kvh, int head_dim,
+                        int block_size, int max_blocks, int n_blocks, int max_q_len, void *stream)
+{
+    const PagedGeom pg = {block_table, block_size, max_blocks, n_blocks};
+    return causal_attn(q, k_pool, v_pool, &pg, seq_lens, q_starts, q_lens, true, out, n_tokens,
+                       n_req, n_qh, n_kvh, head_dim, 1, max_q_len, stream);
 }
 
 int sw_mixed_attn(const void *q, const void *k_cache, const void *v_cache,
@@ -655,7 +712,7 @@ int sw_mixed_attn(const void *q, const void *k_cache, const void *v_cache,
                   int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int max_q_len,
                   void *stream)
 {
-    return causal_attn(q, k_cache, v_cache, seq_lens, q_starts, q_lens, true, out, n_tokens,
+    return causal_attn(q, k_cache, v_cache, nullptr, seq_lens, q_starts, q_lens, true, out, n_tokens,
                        n_req, n_qh, n_kvh, head_dim, max_len, max_q_len, stream);
 }
 

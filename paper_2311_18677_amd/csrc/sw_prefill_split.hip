@@ -22,7 +22,16 @@ using namespace sw_prefill;
 
 constexpr int kWaveLds = 2 * kTileBytes;     // K tile + V tile; reused for the merge (32 rows x 128 floats)
 
-template <int WAVES>
+// Block-table variant: byte offset of the pool block behind each of a tile's 8 load instructions.
+struct TileBlocks { long long off[8]; };
+
+// The block table is read-only for the whole launch; reading it through the constant
+// address space lets wave-uniform entries come in over the scalar path.
+typedef const __attribute__((address_space(4))) int32_t *const_table_t;
+
+// PAGED: K and V are block pools addressed through the request's row of the block table
+// (position t = row t % block_size of pool block table[t / block_size]).
+template <int WAVES, bool PAGED>
 __global__ __launch_bounds__(64 * WAVES, WAVES >= 4 ? 8 / WAVES : 2)
 void sw_prefill_split_kernel(SwPrefillArgs a)
 {
@@ -71,18 +80,24 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         __builtin_amdgcn_global_load_lds(src, sm_q + j * 1024, 16, 0, 0);
     }
 
-    const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
-    const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    // dense: the (request, head) slab; block table: the head's rows inside pool block 0
+    const long long slab = PAGED ? (long long)g * a.stride_kvh : (long long)r * a.stride_req + (long long)g * a.stride_kvh;
+    const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * slab;
+    const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * slab;
+    const_table_t table = PAGED ? (const_table_t)(a.block_table + (long long)r * a.max_blocks) : nullptr;
+    const int in_block = PAGED ? (1 << a.block_shift) - 1 : ~0;
 
     // the tiles that hold every position the block's queries may see (all start inside the context)
     const int n_tiles = min(A0 + kQPerWave - 1, L - 1) / kTile + 1;
 
     // Per-lane byte offsets of a tile's load instructions relative to the tile's first row,
     // computed once: instruction n brings rows 4n .. 4n+3 (lane group gq row 4n+gq, lane n16
-    // one 16-byte piece; K pieces XOR-swizzled by row).  A tile that lies wholly inside the
-    // prompt then needs no per-tile address arithmetic in the vector unit: a wave-uniform
-    // base plus these offsets.  Only a tile that reaches past the prompt's end (the last
-    // one) takes the slow path that clamps every row.
+    // one 16-byte piece; K pieces XOR-swizzled by row).  A tile that lies wholly inside a
+    // dense context then needs one 32-bit add per instruction in the vector unit: a
+    // wave-uniform slab base plus (tile offset + these offsets).  Only a tile that reaches
+    // past the context's end (the last one) takes the slow path that clamps every row.
+    // (Keeping the whole uniform part in scalar registers was tried: the compiler then
+    // builds 64-bit per-lane pointers and the loads lose their scalar-base form; no gain.)
     unsigned koff[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
@@ -99,8 +114,27 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     unsigned vt_off[2][8];
     vt_offsets(n16, gq, vt_off);
 
-    auto issue_k = [&](int t0) {
-        if (t0 + kTile <= L) {
+    // Block table: byte offset of the pool block that holds row 4n of tile t0 (clamped like
+    // the rows themselves).  The four rows of one load instruction always share a block:
+    // blocks hold a multiple of four positions and tiles start at multiples of 32.  One
+    // wave-uniform table read per instruction; ids are clamped into the pool.
+    auto find_blocks = [&](int t0) {
+        TileBlocks tb;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            tb.off[n] = 0;
+            if (PAGED) {
+                const int tu = min(t0 + 4 * n, L - 1);                // wave-uniform
+                int id = table[tu >> a.block_shift];
+                id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
+                tb.off[n] = 2 * (long long)id * a.stride_block;
+            }
+        }
+        return tb;
+    };
+
+    auto issue_k = [&](int t0, const TileBlocks &tb) {
+        if (!PAGED && t0 + kTile <= L) {
             // slab base (scalar) + one 32-bit add per instruction (a slab is below 4 GiB)
             const unsigned tile = (unsigned)t0 << 8;
 #pragma unroll
@@ -110,14 +144,14 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
                 const int rho = 4 * n + gq;
-                const int t = min(t0 + rho, L - 1);      // rows past the prompt repeat its last row (masked)
-                const char *src = kslab + (((unsigned)t << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
+                const int t = min(t0 + rho, L - 1);      // rows past the context repeat its last row (masked)
+                const char *src = kslab + tb.off[n] + ((((unsigned)t & (unsigned)in_block) << 8) | (unsigned)((n16 ^ (rho & 15)) << 4));
                 __builtin_amdgcn_global_load_lds(src, wlds + n * 1024, 16, 0, 0);
             }
         }
     };
-    auto issue_v = [&](int t0) {
-        if (t0 + kTile <= L) {
+    auto issue_v = [&](int t0, const TileBlocks &tb) {
+        if (!PAGED && t0 + kTile <= L) {
             const unsigned tile = (unsigned)t0 << 8;
 #pragma unroll
             for (int n = 0; n < 8; ++n)
@@ -127,7 +161,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
             for (int n = 0; n < 8; ++n) {
                 const int rho = 4 * n + gq;
                 const int t = min(t0 + rho, L - 1);
-                __builtin_amdgcn_global_load_lds(vslab + (((unsigned)t << 8) | (unsigned)((n16 ^ v_swizzle(rho)) << 4)),
+                __builtin_amdgcn_global_load_lds(vslab + tb.off[n] + ((((unsigned)t & (unsigned)in_block) << 8) | (unsigned)((n16 ^ v_swizzle(rho)) << 4)),
                                                  vlds + n * 1024, 16, 0, 0);
             }
         }
@@ -147,6 +181,9 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     // so that every wait counts exactly which loads are still outstanding.
     auto process_tile = [&](int t0, int t0_next, auto more_c) {
         constexpr bool MORE = decltype(more_c)::value;
+        // block ids of the next tile: requested first, needed only after the first product
+        TileBlocks nb;
+        if (MORE) nb = find_blocks(t0_next);
         // outstanding, oldest first: K(t0) x8, V(t0) x8
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         // The two query blocks are independent: the vector-unit work of one is placed
@@ -159,7 +196,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         if (MORE) {
             // every read of the K tile has returned before its area is refilled
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            issue_k(t0_next);
+            issue_k(t0_next, nb);
         }
         const bool diagonal = t0 + kTile > A0;
         Frag p[2];
@@ -171,7 +208,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         load_vt(vlds, vt_off, va);
         if (MORE) {
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            issue_v(t0_next);
+            issue_v(t0_next, nb);
         }
         pv_block(0, va, p, o);
         softmax_block(1, sacc, diagonal, A0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
@@ -180,8 +217,9 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 
     int ti = wave;
     if (ti < n_tiles) {
-        issue_k(ti * kTile);
-        issue_v(ti * kTile);
+        const TileBlocks tb = find_blocks(ti * kTile);
+        issue_k(ti * kTile, tb);
+        issue_v(ti * kTile, tb);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(16));      // this wave's query rows have landed
     } else {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
@@ -263,8 +301,14 @@ hipError_t sw_launch_prefill_split(const SwPrefillArgs &a_in, int waves, hipStre
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     a.compact = compact;
     const dim3 grid((unsigned)blocks);
-    if (waves == 8) return sw_launch(sw_prefill_split_kernel<8>, grid, dim3(512), 0, stream, ev, a);
-    if (waves == 4) return sw_launch(sw_prefill_split_kernel<4>, grid, dim3(256), 0, stream, ev, a);
-    if (waves == 2) return sw_launch(sw_prefill_split_kernel<2>, grid, dim3(128), 0, stream, ev, a);
+    if (a.block_table) {
+        if (waves == 8) return sw_launch(sw_prefill_split_kernel<8, true>, grid, dim3(512), 0, stream, ev, a);
+        if (waves == 4) return sw_launch(sw_prefill_split_kernel<4, true>, grid, dim3(256), 0, stream, ev, a);
+        if (waves == 2) return sw_launch(sw_prefill_split_kernel<2, true>, grid, dim3(128), 0, stream, ev, a);
+        return hipErrorInvalidValue;
+    }
+    if (waves == 8) return sw_launch(sw_prefill_split_kernel<8, false>, grid, dim3(512), 0, stream, ev, a);
+    if (waves == 4) return sw_launch(sw_prefill_split_kernel<4, false>, grid, dim3(256), 0, stream, ev, a);
+    if (waves == 2) return sw_launch(sw_prefill_split_kernel<2, false>, grid, dim3(128), 0, stream, ev, a);
     return hipErrorInvalidValue;
 }

@@ -245,3 +245,32 @@ def test_stream_read_validation():
     assert rcall(sink=None) == sw.SW_ERR_NULL
     assert rcall(src=0x1008) == sw.SW_ERR_ALIGN
     assert rcall(sink=0x2002) == sw.SW_ERR_ALIGN
+
+
+def test_paged_prompt_and_mixed_validation():
+    def pcall(q=0x1000, k=0x2000, v=0x3000, table=0x8000, lens=0x4000, starts=0x5000, out=0x6000,
+              n_tokens=100, n_req=2, n_qh=8, n_kvh=1, d=128, bs=16, mb=8, nb=20):
+        return sw.sw_prefill_attn_paged(q, k, v, table, lens, starts, out, n_tokens, n_req, n_qh, n_kvh, d,
+                                        bs, mb, nb, None, check=False)
+    assert pcall(table=None) == sw.SW_ERR_NULL
+    assert pcall(table=0x8002) == sw.SW_ERR_ALIGN
+    assert pcall(bs=12) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(bs=2) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(mb=0) == sw.SW_ERR_SHAPE
+    assert pcall(nb=0) == sw.SW_ERR_SHAPE
+    assert pcall(bs=4096, mb=4096) == sw.SW_ERR_SHAPE
+    assert pcall(d=64) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(n_tokens=0) == sw.SW_OK
+
+    def mcall(qlens=0x7000, max_q=64, **kw):
+        a = dict(q=0x1000, k=0x2000, v=0x3000, table=0x8000, lens=0x4000, starts=0x5000, out=0x6000,
+                 n_tokens=100, n_req=2, n_qh=8, n_kvh=1, d=128, bs=16, mb=8, nb=20)
+        a.update(kw)
+        return sw.sw_mixed_attn_paged(a["q"], a["k"], a["v"], a["table"], a["lens"], a["starts"], qlens,
+                                      a["out"], a["n_tokens"], a["n_req"], a["n_qh"], a["n_kvh"], a["d"],
+                                      a["bs"], a["mb"], a["nb"], max_q, None, check=False)
+    assert mcall(qlens=None) == sw.SW_ERR_NULL
+    assert mcall(max_q=0) == sw.SW_ERR_SHAPE
+    assert mcall(table=None) == sw.SW_ERR_NULL
+    assert mcall(bs=3) == sw.SW_ERR_UNSUPPORTED
+    assert mcall(n_req=0) == sw.SW_OK
