@@ -34,10 +34,13 @@ union Frag {
 };
 
 // The running maximum of a query is only raised when a score exceeds it by more than
-// this many binary orders of magnitude: weights then stay below 2^kLazyBits (exact
-// enough in binary16, whose precision is relative) and the accumulators are rescaled
-// rarely instead of every tile.
+// this many binary orders of magnitude, and the accumulators are rescaled rarely instead
+// of every tile.  Whether a raise is due is read off the sum of a lane's eight weights of
+// a tile (no per-tile maximum): a sum of at most kSumBound = 8 * 2^kLazyBits changes
+// nothing, so weights stay below 2^11 (exact enough in binary16, whose precision is
+// relative); a larger sum means some score lies more than 2^kLazyBits above the maximum.
 constexpr float kLazyBits = 8.0f;
+constexpr float kSumBound = 8.0f * 256.0f;
 
 // Query tokens of a request: with L cached positions and nq of them queries (the last
 // nq; nq = L when no q_lens array is given), query index i is the token at position
@@ -288,25 +291,38 @@ __device__ __forceinline__ void softmax_block(int nb, const float4_t (&sacc)[2][
                 for (int i = 0; i < 4; ++i)
                     if (t0 + 16 * tb + 4 * gq + i > qpos) s[4 * tb + i] = -INFINITY;
         }
-        float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
-                         fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-        mt = quad_rows_max(mt);
-        const bool raise = mt > m[nb] + lazy_raw;
-        if (__builtin_amdgcn_ballot_w64(raise) != 0) {       // rare after the first tiles
-            const float m_new = raise ? mt : m[nb];
-            const float alpha = __builtin_amdgcn_exp2f((m[nb] - m_new) * scale_log2e);
-            m[nb] = m_new;
-            l[nb] *= alpha;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[nb][e] *= alpha;
-        }
-        const float neg_m = -m[nb] * scale_log2e;
+        // Optimistic pass: weights against the running maximum as it stands.  While every
+        // lane's eight weights sum to at most 8 * 2^kLazyBits nothing has to change -- no
+        // weight exceeds that bound (fine for binary16, whose precision is relative) and the
+        // tile's own maximum is never needed.  A larger (or infinite, or NaN) sum in any
+        // lane sends the whole wave through the exact pass below; sums above the bound
+        // imply a score more than 2^kLazyBits above the maximum, so that pass raises it.
+        float neg_m = -m[nb] * scale_log2e;
         float pj[8];
         float psum = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             pj[j] = __builtin_amdgcn_exp2f(fmaf(s[j], scale_log2e, neg_m));
             psum += pj[j];
+        }
+        if (__builtin_amdgcn_ballot_w64(!(psum <= kSumBound)) != 0) {       // rare after the first tiles
+            float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
+                             fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+            mt = quad_rows_max(mt);
+            const bool raise = mt > m[nb] + lazy_raw;
+            const float m_new = raise ? mt : m[nb];
+            const float alpha = __builtin_amdgcn_exp2f((m[nb] - m_new) * scale_log2e);
+            m[nb] = m_new;
+            l[nb] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[nb][e] *= alpha;
+            neg_m = -m[nb] * scale_log2e;
+            psum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                pj[j] = __builtin_amdgcn_exp2f(fmaf(s[j], scale_log2e, neg_m));
+                psum += pj[j];
+            }
         }
         l[nb] += psum;
 #pragma unroll
