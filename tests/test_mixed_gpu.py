@@ -168,3 +168,32 @@ def test_many_requests_few_prompts(n_req):
     out, ref, _ = run_mixed(batch, qt, starts, qls.tolist(), 200, tag="many")
     assert not np.isnan(out.astype(np.float32)).any()
     assert_parity(out, ref, cfg.name)
+
+
+def test_a_request_keeps_its_bits_whatever_its_batch():
+    # alone (direct workgroup mapping) and inside larger batches (mapping by a scan of the
+    # lengths, one and several requests per lane): the same tiles in the same order
+    import torch
+    L, nq = 250, 200
+    outs = []
+    for n_req, where in ((1, 0), (9, 4), (140, 77)):
+        lens = [64] * n_req
+        qls = [1] * n_req
+        lens[where], qls[where] = L, nq
+        if n_req > 2:
+            lens[0], qls[0] = 200, 200
+        cfg = wl.custom_config("mxb%d" % n_req, n_req, 8, 1, 128, 256)
+        batch = wl.make_batch(cfg, seed=4700 + n_req, seq_lens=lens)
+        # the request under test gets the same rows in every batch
+        ref_cfg = wl.custom_config("mxb_ref", 1, 8, 1, 128, 256)
+        ref_batch = wl.make_batch(ref_cfg, seed=4700, seq_lens=[L])
+        batch.k_rows[where] = ref_batch.k_rows[0]
+        batch.v_rows[where] = ref_batch.v_rows[0]
+        qt, starts, nqs = wl.make_mixed_queries(batch, qls)
+        q_ref = wl.make_mixed_queries(ref_batch, [nq])[0]
+        qt[starts[where]:starts[where] + nq] = q_ref
+        out, ref, _ = run_mixed(batch, qt, starts, qls, 256, tag="batch of %d" % n_req)
+        assert_parity(out, ref, cfg.name)
+        outs.append(out[starts[where]:starts[where] + nq].copy())
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+    assert np.array_equal(outs[0].view(np.uint16), outs[2].view(np.uint16))
