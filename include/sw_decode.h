@@ -240,7 +240,10 @@ int sw_advance_lens(int32_t *seq_lens, int n_req, int max_len, void *stream);
  *   n_tokens   rows of q and out (0 returns SW_OK without touching the device).
  *   head_dim must be 128 (SW_ERR_UNSUPPORTED otherwise); n_qh / n_kvh at most 64.
  * One kernel, no workspace; asynchrony, ownership and the other errors as in
- * sw_decode_attn.  The launch is sized by the smaller of n_req * max_len and about
+ * sw_decode_attn.  Which of the library's two prompt kernels runs depends on the call's
+ * size (n_tokens, n_req, the head counts); they sum in different orders, so a prompt's
+ * result may differ in the last bits between a small and a large batch.  Under either
+ * kernel it does not depend on the other requests of the batch.  The launch is sized by the smaller of n_req * max_len and about
  * n_tokens + 64 * n_req query tokens, so a batch of a few long and many short prompts
  * costs what its tokens cost.  Weights enter the second matrix product rounded to binary16 (the
  * normaliser sums them in binary32 before that rounding); results differ from the fp64

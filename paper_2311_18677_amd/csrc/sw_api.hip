@@ -5,6 +5,7 @@
 #include "sw_decode.h"
 #include "sw_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -19,7 +20,8 @@ namespace {
 constexpr int kVersion = 200;   // 0.2.0
 
 // prompts up to this many positions go to the key-split prompt kernel by default
-constexpr int kPrefillSplitMaxLen = 16384;
+// Workgroups of eight waves from which the shared-tile prompt kernel is the faster of the two.
+constexpr long long kPrefillSharedMinGroups = 300;
 
 thread_local std::string t_last_error = "";
 
@@ -597,12 +599,24 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     a.group = n_qh / n_kvh;
     a.head_dim = head_dim;
     a.max_len = max_len;
-    // Two kernels.  Short and medium prompts are chains of dependent tiles on a mostly
-    // idle chip: the key-split kernel gives every (32 queries, head) pair a whole
-    // workgroup.  Long prompts fill the chip anyway and gain from sharing each staged
-    // tile among the heads of a group.
+    // Two kernels.  The shared-tile kernel stages every K/V tile once for the eight waves of
+    // a workgroup (the heads of a group, or more query positions of one head) and runs at a
+    // steady 36-38 % of the matrix peak once its workgroups fill the chip more than once;
+    // with fewer its time is that of the longest prompt's last block.  The key-split kernel
+    // gives every (32 queries, head) pair a workgroup of its own and splits its keys among
+    // the waves: four times the workgroups, each a quarter as long, but no tile is shared.
+    // Measured crossover: about 300 eight-wave workgroups, i.e. query tokens x heads of
+    // about 77000 (one 12288-token prompt or ten 1024-token prompts at 8 heads).  The choice
+    // looks at the call's number of query tokens, which the host knows; inside either kernel
+    // a request's result does not depend on the rest of its batch.
+    int shared_hp, shared_qw;
+    sw_prefill_shape(n_req, n_kvh, a.group, max_q_len, &shared_hp, &shared_qw);
     int which = g_prefill_kernel;
-    if (which == 0) which = (a.group > 8 || max_len <= kPrefillSplitMaxLen) ? 2 : 1;
+    if (which == 0) {
+        const long long q_bound = std::min<long long>(n_tokens, (long long)n_req * max_q_len);
+        const long long groups = (q_bound / (32 * shared_qw)) * n_kvh * (a.group / shared_hp);
+        which = (a.group <= 8 && groups >= kPrefillSharedMinGroups) ? 1 : 2;
+    }
     if (pg) which = 2;              // the only kernel with block-table addressing
     if (which == 1 && a.group > 8)
         return fail(SW_ERR_UNSUPPORTED, "the shared-tile prompt kernel takes at most 8 query heads per key/value head");
@@ -612,8 +626,12 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
         a.qw = 1;
         if (g_prefill_qw == 2 || g_prefill_qw == 4 || g_prefill_qw == 8) split_waves = g_prefill_qw;
     } else {
-        sw_prefill_shape(n_req, n_kvh, a.group, max_q_len, &a.hp, &a.qw);
-        if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) a.hp = g_prefill_hp;
+        a.hp = shared_hp;
+        a.qw = shared_qw;
+        if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) {
+            a.hp = g_prefill_hp;
+            a.qw = 8 / a.hp > 0 ? 8 / a.hp : 1;
+        }
         if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
     }
     a.n_qblocks = (max_q_len + 32 * a.qw - 1) / (32 * a.qw);      // the grid covers max_q_len query tokens

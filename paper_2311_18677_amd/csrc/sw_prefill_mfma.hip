@@ -167,19 +167,17 @@ bool sw_prefill_mfma_supported(const SwPrefillArgs &a)
 }
 
 // How a workgroup is shaped: hp query heads of one group, qw waves (32 query positions
-// each) per head.  Large problems share each staged K/V tile among all heads of the group
-// (8 waves); small ones are cut into more, smaller workgroups so that the chip fills.
+// each) per head, eight waves in all where the group size allows: hp is the largest
+// divisor of the group size that is at most 8.  (Cutting small problems into smaller
+// workgroups was tried and measured slower: half the waves per staged tile, same chain of
+// dependent tiles.)
 void sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw)
 {
-    int h = group, w = group >= 8 ? 1 : 8 / group;
-    auto groups = [&](int hh, int ww) {
-        return (long long)n_req * n_kvh * (group / hh) * ((max_len + 32 * ww - 1) / (32 * ww));
-    };
-    // first fewer positions per workgroup, then fewer heads
-    while (w > 1 && groups(h, w) < 512) w /= 2;
-    while (h > 1 && h % 2 == 0 && groups(h, w) < 512) h /= 2;
+    (void)n_req; (void)n_kvh; (void)max_len;
+    int h = group < 8 ? group : 8;
+    while (h > 1 && group % h != 0) --h;
     *hp = h;
-    *qw = w;
+    *qw = 8 / h > 0 ? 8 / h : 1;
 }
 
 hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a_in, hipStream_t stream, const SwLaunchEvents *ev)
