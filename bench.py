@@ -751,6 +751,11 @@ def main():
     combine_us = c_us / max(n_rec, 1)
     achieved = prof_bytes / (partial_us * 1e-6) / 1e9 if partial_us > 0 else 0.0
 
+    # ---- the plain streaming read of the same byte count, timed the same way and at the same
+    # point of the run as the kernel above (single launches time differently once the host
+    # has been busy with the CPU baseline)
+    ceiling = None if args.no_read_ceiling else stream_read_ceiling(sw, torch, mean_bytes, dev)
+
     # ---- parity of set 0 and the CPU baseline (the oracle as it stands, on the host cores)
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -841,9 +846,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "parity_set0": parity,
     }
-    if not args.no_read_ceiling:
-        # freed first: the rotation of the ceiling measurement needs its own gigabyte
-        ceiling = stream_read_ceiling(sw, torch, mean_bytes, dev)
+    if ceiling is not None:
         line["roofline"]["stream_read_ceiling"] = ceiling
         if ceiling["kernel_GBps"] > 0:
             line["roofline"]["frac_of_stream_read"] = achieved / ceiling["kernel_GBps"]
