@@ -120,6 +120,27 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     // wave-uniform table read per instruction; ids are clamped into the pool.
     auto find_blocks = [&](int t0) {
         TileBlocks tb;
+        if (PAGED && a.block_shift >= 5) {
+            // blocks of 32 positions or more hold the whole tile: one table read
+            int id = table[min(t0, L - 1) >> a.block_shift];
+            id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
+            const long long off = 2 * (long long)id * a.stride_block;
+#pragma unroll
+            for (int n = 0; n < 8; ++n) tb.off[n] = off;
+            return tb;
+        }
+        if (PAGED && a.block_shift == 4) {
+            // blocks of 16 positions: one read per half tile
+            int id0 = table[min(t0, L - 1) >> 4];
+            int id1 = table[min(t0 + 16, L - 1) >> 4];
+            id0 = id0 < 0 ? 0 : (id0 >= a.n_blocks ? a.n_blocks - 1 : id0);
+            id1 = id1 < 0 ? 0 : (id1 >= a.n_blocks ? a.n_blocks - 1 : id1);
+            const long long off0 = 2 * (long long)id0 * a.stride_block;
+            const long long off1 = 2 * (long long)id1 * a.stride_block;
+#pragma unroll
+            for (int n = 0; n < 8; ++n) tb.off[n] = n < 4 ? off0 : off1;
+            return tb;
+        }
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
             tb.off[n] = 0;
