@@ -613,7 +613,10 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     sw_prefill_shape(n_req, n_kvh, a.group, max_q_len, &shared_hp, &shared_qw);
     int which = g_prefill_kernel;
     if (which == 0) {
-        const long long q_bound = std::min<long long>(n_tokens, (long long)n_req * max_q_len);
+        // (in a mixed batch most requests are usually token-phase requests, one row each,
+        // which the prompt kernel never sees: leave one row per request out of the estimate)
+        long long q_bound = std::min<long long>(n_tokens, (long long)n_req * max_q_len);
+        if (mixed) q_bound = std::max<long long>(0, q_bound - n_req);
         const long long groups = (q_bound / (32 * shared_qw)) * n_kvh * (a.group / shared_hp);
         which = (a.group <= 8 && groups >= kPrefillSharedMinGroups) ? 1 : 2;
     }

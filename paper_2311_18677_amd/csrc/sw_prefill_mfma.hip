@@ -127,13 +127,17 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
         const unsigned char *vb = kb + kTileBytes;
         const int t0 = ti * kTile;
 
+        // The two query blocks are independent: the second block's vector work is placed
+        // behind the first block's matrix work so that the two units overlap within the wave.
         float4_t sacc[2][2];
         qk_tile(kb, qreg, n16, gq, sacc);
+        const bool diagonal = t0 + kTile > aw0;
+        Frag p[2];
+        softmax_block(0, sacc, diagonal, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         Frag va[8];
         load_vt(vb, vt_off, va);
-        Frag p[2];
-        softmax_tile(sacc, t0 + kTile > aw0, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         pv_block(0, va, p, o);
+        softmax_block(1, sacc, diagonal, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         pv_block(1, va, p, o);
     }
 
