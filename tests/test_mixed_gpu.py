@@ -197,3 +197,46 @@ def test_a_request_keeps_its_bits_whatever_its_batch():
         outs.append(out[starts[where]:starts[where] + nq].copy())
     assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
     assert np.array_equal(outs[0].view(np.uint16), outs[2].view(np.uint16))
+
+
+def test_mixed_call_in_a_replayed_graph():
+    # the call enqueues several kernels; captured in a graph and replayed with eager work in
+    # between, every replay must give the eager result
+    import torch
+    lens = [300, 257, 64, 200, 129, 300, 96, 250]
+    qls = [300, 1, 1, 31, 1, 1, 32, 1]
+    cfg = wl.custom_config("mxg", len(lens), 8, 1, 128, 320)
+    batch = wl.make_batch(cfg, seed=4800, seq_lens=lens)
+    qt, starts, nq = wl.make_mixed_queries(batch, qls)
+    bufs = sw.upload_batch(batch, pad_bits=NAN_BITS)
+    q_dev, s_dev, l_dev = to_dev(qt), None, None
+    s_dev = torch.from_numpy(starts).to("cuda:0")
+    l_dev = torch.from_numpy(np.asarray(qls, np.int32)).to("cuda:0")
+    n_tok = qt.shape[0]
+
+    def call(out, stream):
+        sw.sw_mixed_attn(q_dev, bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], s_dev, l_dev, out,
+                         n_tok, cfg.n_req, 8, 1, 128, 320, 300, stream)
+
+    eager = torch.full((n_tok, 8, 128), float("nan"), dtype=torch.float16, device="cuda:0")
+    stream = torch.cuda.Stream()
+    call(eager, stream)              # the first call allocates the workspace, outside any capture
+    stream.synchronize()
+    want = eager.cpu().numpy().view(np.uint16)
+    assert not np.isnan(eager.cpu().numpy().astype(np.float32)).any()
+    out = torch.full_like(eager, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call(out, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(4):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        print("replay", rep, flush=True)
+        with torch.cuda.stream(stream):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), want), rep
+        call(eager, stream)          # eager work between the replays
+        stream.synchronize()
+        assert np.array_equal(eager.cpu().numpy().view(np.uint16), want)
