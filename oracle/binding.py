@@ -91,6 +91,13 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int, ctypes.c_int,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+        lib.sw_oracle_kv_store.restype = ctypes.c_int
+        lib.sw_oracle_kv_store.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
         lib.sw_oracle_half_to_double.restype = ctypes.c_double
         lib.sw_oracle_half_to_double.argtypes = [ctypes.c_uint16]
         lib.sw_oracle_max_threads.restype = ctypes.c_int
@@ -215,6 +222,45 @@ def mixed_attn_paged(q, k_pool, v_pool, block_table, seq_lens, q_starts, q_lens,
     if rc < 0:
         raise ValueError("sw_oracle_mixed_attn_paged rejected its arguments (code %d)" % rc)
     return ref
+
+
+def kv_store(k_rows, v_rows, k, v, seq_lens, q_starts, q_lens, n_req, n_kvh, head_dim, max_len, max_q_len,
+             stride_req, stride_kvh, stride_tok, block_table=None, block_size=0, max_blocks=0, n_blocks=0):
+    """Store the K/V rows of every request's query tokens at their positions, IN PLACE in k and v.
+
+    k_rows, v_rows: [n_tokens, n_kvh, head_dim] binary16 (bits or float16).  Dense caches by default;
+    with block_table, k and v are block pools and stride_req is their block stride.  q_lens None:
+    every cached token of a request is new (a whole prompt).
+    """
+    lib = _load()
+    k_rows = _as_u16(k_rows, "k_rows")
+    v_rows = _as_u16(v_rows, "v_rows")
+    k = _writable_u16(k, "k")
+    v = _writable_u16(v, "v")
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    starts = np.ascontiguousarray(np.asarray(q_starts, dtype=np.int32))
+    qlens = None if q_lens is None else np.ascontiguousarray(np.asarray(q_lens, dtype=np.int32))
+    table = None if block_table is None else np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    if lens.size != n_req or starts.size != n_req or (qlens is not None and qlens.size != n_req):
+        raise ValueError("seq_lens / q_starts / q_lens need n_req entries")
+    if k_rows.size != v_rows.size or k_rows.size % (n_kvh * head_dim):
+        raise ValueError("k_rows / v_rows are not whole token rows of the same count")
+    n_tokens = k_rows.size // (n_kvh * head_dim)
+    if table is None:
+        need = ((n_req - 1) * stride_req + (n_kvh - 1) * stride_kvh + (max_len - 1) * stride_tok + head_dim) if n_req else 0
+    else:
+        if table.size != n_req * max_blocks:
+            raise ValueError("block_table has the wrong number of entries")
+        need = (n_blocks - 1) * stride_req + (n_kvh - 1) * stride_kvh + (block_size - 1) * stride_tok + head_dim
+    if k.size < need or v.size < need:
+        raise ValueError("k/v buffers are smaller than the strides address")
+    rc = lib.sw_oracle_kv_store(k_rows.ctypes.data, v_rows.ctypes.data, k.ctypes.data, v.ctypes.data,
+                                None if table is None else table.ctypes.data, lens.ctypes.data,
+                                starts.ctypes.data, None if qlens is None else qlens.ctypes.data,
+                                n_req, n_kvh, head_dim, max_len, max_q_len, n_tokens,
+                                block_size, max_blocks, n_blocks, stride_req, stride_kvh, stride_tok)
+    if rc < 0:
+        raise ValueError("sw_oracle_kv_store rejected its arguments (code %d)" % rc)
 
 
 def _writable_u16(a, name):

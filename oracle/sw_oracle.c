@@ -532,6 +532,69 @@ int sw_oracle_mixed_attn_paged(const uint16_t *q, const uint16_t *k_pool, const 
 }
 
 /*
+ * The cache side of a prompt or mixed pass (section 2.2: the prompt phase processes all
+ * prompt tokens in one forward pass, which produces the KV cache; section 2.4: mixed
+ * batches).  The pass computes one K row and one V row per query token and key/value
+ * head; they belong at the positions of those tokens.  With L = clamp(seq_lens[r], 0,
+ * max_len) cached positions INCLUDING the new tokens and nq = clamp(q_lens[r], 0,
+ * min(L, max_q_len)) of them new (q_lens == NULL: all L), rows
+ * k_rows[q_starts[r] + i, g, :] and v_rows[...] are copied, bit for bit, to position
+ * L - nq + i of head g, i < nq.  k_rows, v_rows: dense [n_tokens][n_kvh][head_dim]; a
+ * request whose rows would leave [0, n_tokens) returns -5.  Nothing else is written.
+ * block_table == NULL: dense caches addressed by (stride_req, stride_kvh, stride_tok);
+ * else block pools: position t of request r is row t % block_size of pool block
+ * clamp(block_table[r*max_blocks + t/block_size], 0, n_blocks-1), max_len =
+ * max_blocks*block_size, and stride_req is the pools' block stride.
+ * With nq = 1 this is sw_oracle_kv_append seen from the lengths after the append.
+ * Pinned by array slicing, by that equivalence, by paged = dense and by "store a prompt,
+ * then attend = attend over a cache that was built directly" (tests/test_oracle_pins.py).
+ */
+int sw_oracle_kv_store(const uint16_t *k_rows, const uint16_t *v_rows, uint16_t *k, uint16_t *v,
+                       const int32_t *block_table, const int32_t *seq_lens,
+                       const int32_t *q_starts, const int32_t *q_lens,
+                       int n_req, int n_kvh, int head_dim, int max_len, int max_q_len,
+                       int64_t n_tokens,
+                       int block_size, int max_blocks, int n_blocks,
+                       int64_t stride_req, int64_t stride_kvh, int64_t stride_tok)
+{
+    if (n_req < 0 || n_kvh <= 0 || head_dim <= 0 || max_q_len <= 0 || n_tokens < 0) return -1;
+    if (block_table) {
+        if (block_size <= 0 || max_blocks <= 0 || n_blocks <= 0) return -1;
+        max_len = (int)((int64_t)max_blocks * block_size);
+    }
+    if (max_len <= 0) return -1;
+    if (n_req == 0) return 0;
+    if (!k_rows || !v_rows || !k || !v || !seq_lens || !q_starts) return -3;
+    for (int r = 0; r < n_req; ++r) {
+        int L = clampi(seq_lens[r], 0, max_len);
+        int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
+        if (nq > 0 && (q_starts[r] < 0 || (int64_t)q_starts[r] + nq > n_tokens)) return -5;
+    }
+    for (int r = 0; r < n_req; ++r) {
+        int L = clampi(seq_lens[r], 0, max_len);
+        int nq = q_lens ? clampi(q_lens[r], 0, L < max_q_len ? L : max_q_len) : L;
+        for (int i = 0; i < nq; ++i) {
+            int64_t t = (int64_t)L - nq + i;                 /* position of query token i */
+            for (int g = 0; g < n_kvh; ++g) {
+                int64_t dst;
+                if (block_table) {
+                    int b = clampi(block_table[(int64_t)r * max_blocks + t / block_size], 0, n_blocks - 1);
+                    dst = (int64_t)b * stride_req + (int64_t)g * stride_kvh + (t % block_size) * stride_tok;
+                } else {
+                    dst = (int64_t)r * stride_req + (int64_t)g * stride_kvh + t * stride_tok;
+                }
+                int64_t src = (((int64_t)q_starts[r] + i) * n_kvh + g) * head_dim;
+                for (int j = 0; j < head_dim; ++j) {
+                    k[dst + j] = k_rows[src + j];
+                    v[dst + j] = v_rows[src + j];
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
  * KV-cache hand-off (sections 4.3 and 5.1: the prompt machine ships each layer's
  * KV cache to the token machine, block by block, merging blocks that are contiguous
  * so that fewer transfers are issued).  Three plain routines cover the part of it

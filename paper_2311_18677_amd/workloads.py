@@ -218,6 +218,27 @@ def make_mixed_queries(batch, q_lens, seed=None):
     return q, starts, nq.astype(np.int32)
 
 
+def token_rows(batch, q_lens=None):
+    """K and V rows of every request's last q_lens[r] tokens (all of them when q_lens is None),
+    packed request after request the way a forward pass produces them.
+
+    Returns (k_tok, v_tok float16 [n_tokens, n_kvh, head_dim], q_starts int32, nq int32 as clamped).
+    """
+    cfg = batch.cfg
+    lens = batch.valid_lens.astype(np.int64)
+    nq = lens if q_lens is None else np.minimum(np.clip(np.asarray(q_lens, dtype=np.int64), 0, None), lens)
+    starts = np.concatenate([[0], np.cumsum(nq)[:-1]]).astype(np.int32)
+    n_tokens = int(nq.sum())
+    k_tok = np.zeros((n_tokens, cfg.n_kvh, cfg.head_dim), dtype=np.float16)
+    v_tok = np.zeros((n_tokens, cfg.n_kvh, cfg.head_dim), dtype=np.float16)
+    for r in range(cfg.n_req):
+        L, n = int(lens[r]), int(nq[r])
+        if n:
+            k_tok[starts[r]:starts[r] + n] = batch.k_rows[r][:, L - n:L, :].transpose(1, 0, 2)
+            v_tok[starts[r]:starts[r] + n] = batch.v_rows[r][:, L - n:L, :].transpose(1, 0, 2)
+    return k_tok, v_tok, starts, nq.astype(np.int32)
+
+
 def mixed_flops(cfg, lens, q_lens):
     """Algorithmic flops of a mixed batch: 4*head_dim per (query, visible key) pair and head."""
     lens = np.clip(np.asarray(lens, dtype=np.int64), 0, cfg.max_len)

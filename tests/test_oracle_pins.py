@@ -598,3 +598,119 @@ def test_paged_mixed_batch_equals_the_dense_routine_bit_for_bit(block_size):
     c = oracle.mixed_attn_paged(qm, kp, vp, ok, [max_blocks * block_size, 23, 1, 0, 17], sm, qls, 5, 4, 2, 64,
                                 block_size, max_blocks, n_blocks, 40, sb, sgp, stp)
     assert np.array_equal(a, c, equal_nan=True)
+
+
+def _store_case(n_kvh, d, max_len, lens, seed, pad=0x7E00):
+    cfg = wl.custom_config("st", len(lens), n_kvh, n_kvh, d, max_len)
+    b = wl.make_batch(cfg, seed=seed, seq_lens=lens)
+    sr, sg, st, tot = wl.dense_layout(cfg)
+    full_k = wl.pack_cache(b.k_rows, cfg, sr, sg, st, tot, pad)
+    full_v = wl.pack_cache(b.v_rows, cfg, sr, sg, st, tot, pad)
+    return cfg, b, (sr, sg, st, tot), full_k, full_v
+
+
+def test_store_of_whole_prompts_builds_the_cache_and_touches_nothing_else():
+    lens = [24, 1, 0, 9, 17]
+    cfg, b, (sr, sg, st, tot), full_k, full_v = _store_case(2, 64, 24, lens, 120)
+    k_tok, v_tok, starts, nq = wl.token_rows(b)
+    k = np.full(tot, 0x7E00, np.uint16)
+    v = np.full(tot, 0x7E00, np.uint16)
+    oracle.kv_store(k_tok, v_tok, k, v, b.seq_lens, starts, None, 5, 2, 64, 24, 24, sr, sg, st)
+    assert np.array_equal(k, full_k) and np.array_equal(v, full_v)
+    # by slicing, on strides with padding everywhere (token stride 80, head and request gaps)
+    st2, sg2, sr2 = 80, 24 * 80 + 16, 2 * (24 * 80 + 16) + 48
+    tot2 = 5 * sr2
+    k2 = np.full(tot2, 0x1234, np.uint16)
+    v2 = np.full(tot2, 0x4321, np.uint16)
+    oracle.kv_store(k_tok, v_tok, k2, v2, b.seq_lens, starts, None, 5, 2, 64, 24, 24, sr2, sg2, st2)
+    want_k = np.full(tot2, 0x1234, np.uint16)
+    want_v = np.full(tot2, 0x4321, np.uint16)
+    for r, L in enumerate(lens):
+        for g in range(2):
+            for t in range(L):
+                o = r * sr2 + g * sg2 + t * st2
+                want_k[o:o + 64] = b.k_rows[r][g, t].view(np.uint16)
+                want_v[o:o + 64] = b.v_rows[r][g, t].view(np.uint16)
+    assert np.array_equal(k2, want_k) and np.array_equal(v2, want_v)
+
+
+def test_store_of_the_last_tokens_and_its_clamps():
+    lens = [24, 5, 0, 9, 17]
+    cfg, b, (sr, sg, st, tot), full_k, full_v = _store_case(2, 64, 24, lens, 121)
+    qls = [7, 1, 3, 99, 0]                       # piece, token phase, nothing cached, more than cached, none
+    k_tok, v_tok, starts, nq = wl.token_rows(b, qls)
+    assert nq.tolist() == [7, 1, 0, 9, 0]
+    # a cache that holds everything but the new rows (NaN there): the store completes it
+    k, v = full_k.copy(), full_v.copy()
+    kk = np.lib.stride_tricks.as_strided(k, shape=(5, 2, 24, 64), strides=(2 * sr, 2 * sg, 2 * st, 2), writeable=True)
+    vv = np.lib.stride_tricks.as_strided(v, shape=(5, 2, 24, 64), strides=(2 * sr, 2 * sg, 2 * st, 2), writeable=True)
+    for r, (L, n) in enumerate(zip(lens, nq)):
+        kk[r, :, L - n:L, :] = 0x7E00
+        vv[r, :, L - n:L, :] = 0x7E00
+    before_k = k.copy()
+    oracle.kv_store(k_tok, v_tok, k, v, b.seq_lens, starts, qls, 5, 2, 64, 24, 24, sr, sg, st)
+    assert np.array_equal(k, full_k) and np.array_equal(v, full_v) and not np.array_equal(before_k, full_k)
+    # the bound on new tokens per request: only the last max_q_len are stored
+    k3, v3 = before_k.copy(), v.copy()
+    kt3, vt3, s3, n3 = wl.token_rows(b, [3, 1, 0, 3, 0])
+    oracle.kv_store(kt3, vt3, k3, v3, b.seq_lens, s3, qls, 5, 2, 64, 24, 3, sr, sg, st)
+    k3v = np.lib.stride_tricks.as_strided(k3, shape=(5, 2, 24, 64), strides=(2 * sr, 2 * sg, 2 * st, 2))
+    fkv = np.lib.stride_tricks.as_strided(full_k, shape=(5, 2, 24, 64), strides=(2 * sr, 2 * sg, 2 * st, 2))
+    assert np.array_equal(k3v[0, :, 21:24], fkv[0, :, 21:24]) and (k3v[0, :, 17:21] == 0x7E00).all()
+    # lengths above max_len count as max_len
+    k4, v4 = before_k.copy(), v.copy()
+    oracle.kv_store(k_tok, v_tok, k4, v4, [99, 5, 0, 9, 17], starts, qls, 5, 2, 64, 24, 24, sr, sg, st)
+    assert np.array_equal(k4, full_k)
+    # rows that would leave the token arrays are refused
+    with pytest.raises(ValueError):
+        oracle.kv_store(k_tok, v_tok, k4, v4, b.seq_lens, [0, 7, 8, 9, 17], qls, 5, 2, 64, 24, 24, sr, sg, st)
+
+
+def test_store_of_one_token_is_the_append_routine():
+    lens = [10, 1, 24, 7]
+    cfg, b, (sr, sg, st, tot), full_k, full_v = _store_case(3, 64, 24, lens, 122)
+    k_new, v_new = wl.make_new_rows(cfg, 122)
+    before = np.array([9, 0, 23, 6], np.int32)
+    ka, va = full_k.copy(), full_v.copy()
+    after = oracle.kv_append(k_new, v_new, ka, va, before, 4, 3, 64, 24, sr, sg, st)
+    assert after.tolist() == lens
+    ks, vs = full_k.copy(), full_v.copy()
+    oracle.kv_store(k_new, v_new, ks, vs, after, [0, 1, 2, 3], [1, 1, 1, 1], 4, 3, 64, 24, 1, sr, sg, st)
+    assert np.array_equal(ka, ks) and np.array_equal(va, vs) and not np.array_equal(ks, full_k)
+
+
+@pytest.mark.parametrize("block_size", [4, 16])
+def test_store_into_block_pools_equals_the_dense_store(block_size):
+    lens = [24, 5, 0, 9, 17]
+    cfg, b, (sr, sg, st, tot), full_k, full_v = _store_case(2, 64, 24, lens, 123)
+    qls = [7, 1, 3, 99, 17]
+    k_tok, v_tok, starts, nq = wl.token_rows(b, qls)
+    sb, sgp, stp = wl.dense_paged_layout(cfg, block_size)
+    max_blocks = -(-24 // block_size)
+    n_blocks = sum(-(-L // block_size) for L in lens) + 4
+    # pools that hold the batch; wipe the new rows, store them again, compare with the pools as packed
+    kp, vp, table = wl.pack_paged(b.k_rows, b.v_rows, cfg, block_size, sb, sgp, stp, n_blocks, seed=5, pad_bits=0x7E00)
+    kp0, vp0 = kp.copy(), vp.copy()
+    kv = np.lib.stride_tricks.as_strided(kp, shape=(n_blocks, 2, block_size, 64), strides=(2 * sb, 2 * sgp, 2 * stp, 2), writeable=True)
+    vv = np.lib.stride_tricks.as_strided(vp, shape=(n_blocks, 2, block_size, 64), strides=(2 * sb, 2 * sgp, 2 * stp, 2), writeable=True)
+    for r, (L, n) in enumerate(zip(lens, nq)):
+        for t in range(L - n, L):
+            kv[table[r, t // block_size], :, t % block_size, :] = 0
+            vv[table[r, t // block_size], :, t % block_size, :] = 0
+    assert not np.array_equal(kp, kp0)
+    oracle.kv_store(k_tok, v_tok, kp, vp, b.seq_lens, starts, qls, 5, 2, 64, 24, 24, sb, sgp, stp,
+                    block_table=table, block_size=block_size, max_blocks=max_blocks, n_blocks=n_blocks)
+    assert np.array_equal(kp, kp0) and np.array_equal(vp, vp0)
+
+
+def test_store_then_attend_is_attention_over_the_cache_built_directly():
+    lens = [24, 9, 17]
+    cfg, b, (sr, sg, st, tot), full_k, full_v = _store_case(2, 64, 24, lens, 124, pad=0)
+    qt, qs = wl.make_prefill_queries(b)
+    k_tok, v_tok, starts, nq = wl.token_rows(b)
+    k = np.zeros(tot, np.uint16)
+    v = np.zeros(tot, np.uint16)
+    oracle.kv_store(k_tok, v_tok, k, v, b.seq_lens, starts, None, 3, 2, 64, 24, 24, sr, sg, st)
+    a = oracle.prefill_attn(qt, k, v, b.seq_lens, qs, 3, 2, 2, 64, 24, sr, sg, st)
+    c = oracle.prefill_attn(qt, full_k, full_v, b.seq_lens, qs, 3, 2, 2, 64, 24, sr, sg, st)
+    assert np.array_equal(a, c) and a.any()
