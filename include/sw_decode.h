@@ -304,6 +304,34 @@ int sw_mixed_attn_paged(const void *q, const void *k_pool, const void *v_pool,
                         int block_size, int max_blocks, int n_blocks, int max_q_len, void *stream);
 
 /*
+ * sw_kv_store, sw_kv_store_paged -- the cache side of a prompt or mixed pass (section
+ * 2.2: the prompt phase processes all prompt tokens in one pass, which produces the KV
+ * cache).  The pass has computed one K row and one V row per new token and key/value
+ * head; this call puts them where they belong, after which sw_prefill_attn /
+ * sw_mixed_attn (same seq_lens, q_starts, q_lens) attend over them.  With L_r =
+ * clamp(seq_lens[r], 0, max_len) cached positions INCLUDING the new tokens and nq_r =
+ * clamp(q_lens[r], 0, min(L_r, max_q_len)) of them new (q_lens == NULL: all L_r, a whole
+ * prompt), rows k_rows[q_starts[r] + i, g, :] and v_rows[...] go, bit for bit, to
+ * position L_r - nq_r + i of head g of request r, for i < nq_r.  Nothing else is written.
+ *   k_rows, v_rows   DEVICE, binary16, [n_tokens][n_kvh][head_dim], 16-byte aligned; rows
+ *                    outside [0, n_tokens) do not exist and are skipped; the requests'
+ *                    row ranges must not overlap (as in sw_mixed_attn).
+ *   k_cache, v_cache the dense caches of sw_kv_layout (sw_kv_store) or the block pools of
+ *                    sw_kv_paged_layout with their table (sw_kv_store_paged, where max_len is
+ *                    max_blocks * block_size); written.
+ *   head_dim 64 or 128; n_kvh at most 65535.  n_req == 0 or n_tokens == 0 returns SW_OK.
+ * One kernel, no workspace; asynchrony, ownership and the other errors as in sw_mixed_attn.
+ */
+int sw_kv_store(const void *k_rows, const void *v_rows, void *k_cache, void *v_cache,
+                const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                long long n_tokens, int n_req, int n_kvh, int head_dim, int max_len, int max_q_len,
+                void *stream);
+int sw_kv_store_paged(const void *k_rows, const void *v_rows, void *k_pool, void *v_pool,
+                      const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_starts,
+                      const int32_t *q_lens, long long n_tokens, int n_req, int n_kvh, int head_dim,
+                      int block_size, int max_blocks, int n_blocks, int max_q_len, void *stream);
+
+/*
  * KV-cache hand-off, the part inside one GPU's memory.  A prompt machine ships
  * each layer's KV cache to a token machine block by block, merging blocks that
  * are contiguous so that fewer transfers are issued (section 4.3, "KV-cache

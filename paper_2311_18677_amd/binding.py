@@ -31,7 +31,7 @@ SW_PARAM_PREFILL_KERNEL = 7
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
-           "sw_prefill_attn", "sw_mixed_attn", "sw_prefill_attn_paged", "sw_mixed_attn_paged", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
+           "sw_prefill_attn", "sw_mixed_attn", "sw_prefill_attn_paged", "sw_mixed_attn_paged", "sw_kv_store", "sw_kv_store_paged", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop", "sw_stream_read")
 
@@ -117,6 +117,11 @@ def load():
     lib.sw_mixed_attn_paged.restype = ci
     lib.sw_mixed_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_longlong,
                                         ci, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.sw_kv_store.restype = ci
+    lib.sw_kv_store.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_longlong, ci, ci, ci, ci, ci, vp]
+    lib.sw_kv_store_paged.restype = ci
+    lib.sw_kv_store_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_longlong,
+                                      ci, ci, ci, ci, ci, ci, ci, vp]
     lib.sw_stream_read.restype = ci
     lib.sw_stream_read.argtypes = [vp, ctypes.c_longlong, vp, ci, vp]
     lib.sw_prof_start.restype = ci
@@ -310,6 +315,26 @@ def sw_mixed_attn_paged(q, k_pool, v_pool, block_table, seq_lens, q_starts, q_le
                                     _ptr(seq_lens), _ptr(q_starts), _ptr(q_lens), _ptr(out),
                                     int(n_tokens), n_req, n_qh, n_kvh, head_dim, block_size, max_blocks,
                                     n_blocks, max_q_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_kv_store(k_rows, v_rows, k_cache, v_cache, seq_lens, q_starts, q_lens, n_tokens, n_req, n_kvh,
+                head_dim, max_len, max_q_len, stream=None, check=True):
+    """Store the new tokens' K/V rows at their positions in the dense caches (q_lens None: all)."""
+    rc = load().sw_kv_store(_ptr(k_rows), _ptr(v_rows), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens),
+                            _ptr(q_starts), _ptr(q_lens), int(n_tokens), n_req, n_kvh, head_dim, max_len,
+                            max_q_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_kv_store_paged(k_rows, v_rows, k_pool, v_pool, block_table, seq_lens, q_starts, q_lens, n_tokens,
+                      n_req, n_kvh, head_dim, block_size, max_blocks, n_blocks, max_q_len,
+                      stream=None, check=True):
+    """The same into block pools + block table."""
+    rc = load().sw_kv_store_paged(_ptr(k_rows), _ptr(v_rows), _ptr(k_pool), _ptr(v_pool),
+                                  _ptr(block_table), _ptr(seq_lens), _ptr(q_starts), _ptr(q_lens),
+                                  int(n_tokens), n_req, n_kvh, head_dim, block_size, max_blocks,
+                                  n_blocks, max_q_len, _stream(stream))
     return _check(rc) if check else rc
 
 

@@ -739,6 +739,111 @@ int sw_mixed_attn(const void *q, const void *k_cache, const void *v_cache,
                        n_req, n_qh, n_kvh, head_dim, max_len, max_q_len, stream);
 }
 
+// sw_kv_store / sw_kv_store_paged
+static int kv_store(const void *k_rows, const void *v_rows, void *k_cache, void *v_cache, const PagedGeom *pg,
+                    const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                    long long n_tokens, int n_req, int n_kvh, int head_dim, int max_len, int max_q_len,
+                    void *stream_v)
+{
+    if (pg) {
+        if (pg->block_size < 4 || pg->block_size > 4096 || (pg->block_size & (pg->block_size - 1)))
+            return fail(SW_ERR_UNSUPPORTED, "block_size must be a power of two in [4, 4096]");
+        if (pg->max_blocks <= 0 || pg->n_blocks <= 0)
+            return fail(SW_ERR_SHAPE, "max_blocks and n_blocks must be > 0");
+        if ((long long)pg->max_blocks * pg->block_size > (1 << 23))
+            return fail(SW_ERR_SHAPE, "max_blocks * block_size above 2^23");
+        max_len = pg->max_blocks * pg->block_size;
+    }
+    int rc = check_shape(n_req, n_kvh, head_dim, max_len);
+    if (rc != SW_OK) return rc;
+    if (n_kvh > 65535) return fail(SW_ERR_SHAPE, "n_kvh above 65535");
+    if (n_tokens < 0 || n_tokens > (1LL << 31)) return fail(SW_ERR_SHAPE, "n_tokens must be in [0, 2^31]");
+    if (max_q_len <= 0) return fail(SW_ERR_SHAPE, "max_q_len must be > 0");
+    if (max_q_len > max_len) max_q_len = max_len;
+    if (n_req == 0 || n_tokens == 0) return SW_OK;
+    if (!k_rows || !v_rows || !k_cache || !v_cache || !seq_lens || !q_starts)
+        return fail(SW_ERR_NULL, "k_rows, v_rows, the caches, seq_lens and q_starts must be non-NULL");
+    if (pg && !pg->block_table) return fail(SW_ERR_NULL, "block_table must be non-NULL");
+    if (((uintptr_t)k_rows | (uintptr_t)v_rows | (uintptr_t)k_cache | (uintptr_t)v_cache) & 15u)
+        return fail(SW_ERR_ALIGN, "k_rows, v_rows and the caches must be 16-byte aligned");
+    if (((uintptr_t)seq_lens | (uintptr_t)q_starts | (uintptr_t)q_lens | (uintptr_t)(pg ? pg->block_table : nullptr)) & 3u)
+        return fail(SW_ERR_ALIGN, "seq_lens, q_starts, q_lens and block_table must be 4-byte aligned");
+
+    SwPrefillArgs a;
+    a.q = nullptr;
+    a.k = (const uint16_t *)k_cache;
+    a.v = (const uint16_t *)v_cache;
+    a.seq_lens = seq_lens;
+    a.q_starts = q_starts;
+    a.q_lens = q_lens;
+    a.out = nullptr;
+    a.n_tokens = n_tokens;
+    a.n_req = n_req;
+    a.n_qh = n_kvh;
+    a.n_kvh = n_kvh;
+    a.group = 1;
+    a.head_dim = head_dim;
+    a.max_len = max_len;
+    a.max_q = max_q_len;
+    a.skip_single = 0;
+    a.compact = 0;
+    a.hp = a.qw = 1;
+    a.n_qblocks = (max_q_len + 31) / 32;
+    if (pg) {
+        a.block_table = pg->block_table;
+        a.block_shift = 0;
+        while ((1 << a.block_shift) < pg->block_size) ++a.block_shift;
+        a.max_blocks = pg->max_blocks;
+        a.n_blocks = pg->n_blocks;
+        a.stride_kvh = (long long)pg->block_size * head_dim;
+        a.stride_block = a.stride_kvh * n_kvh;
+        a.stride_req = 0;
+    } else {
+        a.block_table = nullptr;
+        a.block_shift = a.max_blocks = a.n_blocks = 0;
+        a.stride_block = 0;
+        a.stride_kvh = slab_elems(head_dim, max_len);
+        a.stride_req = a.stride_kvh * n_kvh;
+    }
+    a.scale_log2e = 0.f;
+    if ((long long)n_req * a.n_qblocks > 0x7fffffffLL) return fail(SW_ERR_SHAPE, "too many workgroups");
+
+    bool prof = false;
+    SwLaunchEvents ev = {nullptr, nullptr};
+    ProfRec rec;
+    int prc = prof_begin(rec, false, &prof);
+    if (prc != SW_OK) return prc;
+    if (prof) ev = {rec.ev[0], rec.ev[1]};
+    hipError_t e = sw_launch_kv_store(a, (const uint16_t *)k_rows, (const uint16_t *)v_rows,
+                                      (uint16_t *)k_cache, (uint16_t *)v_cache, (hipStream_t)stream_v,
+                                      prof ? &ev : nullptr);
+    if (e != hipSuccess) {
+        if (prof) prof_abort(rec);
+        return fail_hip(e, "kernel launch");
+    }
+    if (prof) prof_commit(rec);
+    return SW_OK;
+}
+
+int sw_kv_store(const void *k_rows, const void *v_rows, void *k_cache, void *v_cache,
+                const int32_t *seq_lens, const int32_t *q_starts, const int32_t *q_lens,
+                long long n_tokens, int n_req, int n_kvh, int head_dim, int max_len, int max_q_len,
+                void *stream)
+{
+    return kv_store(k_rows, v_rows, k_cache, v_cache, nullptr, seq_lens, q_starts, q_lens, n_tokens,
+                    n_req, n_kvh, head_dim, max_len, max_q_len, stream);
+}
+
+int sw_kv_store_paged(const void *k_rows, const void *v_rows, void *k_pool, void *v_pool,
+                      const int32_t *block_table, const int32_t *seq_lens, const int32_t *q_starts,
+                      const int32_t *q_lens, long long n_tokens, int n_req, int n_kvh, int head_dim,
+                      int block_size, int max_blocks, int n_blocks, int max_q_len, void *stream)
+{
+    const PagedGeom pg = {block_table, block_size, max_blocks, n_blocks};
+    return kv_store(k_rows, v_rows, k_pool, v_pool, &pg, seq_lens, q_starts, q_lens, n_tokens,
+                    n_req, n_kvh, head_dim, 1, max_q_len, stream);
+}
+
 // sw_kv_pack / sw_kv_unpack
 static int kv_copy(void *k_pool, void *v_pool, const int32_t *block_table, const int32_t *seq_lens,
                    void *k_dense, void *v_dense, bool to_dense,

@@ -171,6 +171,8 @@ hipError_t sw_launch_kv_span_plan(const int32_t *block_table, const int32_t *seq
                                   int32_t *span_first, int32_t *span_blocks, int32_t *n_spans,
                                   int n_req, int block_shift, int max_blocks, int n_blocks,
                                   hipStream_t stream);
+hipError_t sw_launch_kv_store(const SwPrefillArgs &a, const uint16_t *k_rows, const uint16_t *v_rows,
+                              uint16_t *k_out, uint16_t *v_out, hipStream_t stream, const SwLaunchEvents *ev);
 hipError_t sw_launch_stream_read(const void *src, unsigned long long n_bytes, unsigned *sink,
                                  int workgroups, hipStream_t stream, const SwLaunchEvents *ev);
 hipError_t sw_launch_advance_lens(int32_t *seq_lens, int n_req, int max_len, hipStream_t stream);

@@ -274,3 +274,35 @@ def test_paged_prompt_and_mixed_validation():
     assert mcall(table=None) == sw.SW_ERR_NULL
     assert mcall(bs=3) == sw.SW_ERR_UNSUPPORTED
     assert mcall(n_req=0) == sw.SW_OK
+
+
+def test_kv_store_validation():
+    def scall(kr=0x1000, vr=0x2000, k=0x3000, v=0x4000, lens=0x5000, starts=0x6000, qlens=0x7000,
+              n_tokens=100, n_req=2, n_kvh=2, d=128, max_len=256, max_q=64):
+        return sw.sw_kv_store(kr, vr, k, v, lens, starts, qlens, n_tokens, n_req, n_kvh, d, max_len, max_q,
+                              None, check=False)
+    assert scall(kr=None) == sw.SW_ERR_NULL
+    assert scall(k=None) == sw.SW_ERR_NULL
+    assert scall(starts=None) == sw.SW_ERR_NULL
+    assert scall(vr=0x2008) == sw.SW_ERR_ALIGN
+    assert scall(qlens=0x7002) == sw.SW_ERR_ALIGN
+    assert scall(d=96) == sw.SW_ERR_UNSUPPORTED
+    assert scall(max_q=0) == sw.SW_ERR_SHAPE
+    assert scall(n_kvh=70000) == sw.SW_ERR_SHAPE
+    assert scall(n_tokens=-1) == sw.SW_ERR_SHAPE
+    assert scall(n_tokens=0) == sw.SW_OK
+    assert scall(n_req=0) == sw.SW_OK
+
+    def pcall(table=0x8000, bs=16, mb=8, nb=20, **kw):
+        a = dict(kr=0x1000, vr=0x2000, k=0x3000, v=0x4000, lens=0x5000, starts=0x6000, qlens=None,
+                 n_tokens=100, n_req=2, n_kvh=2, d=128, max_q=64)
+        a.update(kw)
+        return sw.sw_kv_store_paged(a["kr"], a["vr"], a["k"], a["v"], table, a["lens"], a["starts"], a["qlens"],
+                                    a["n_tokens"], a["n_req"], a["n_kvh"], a["d"], bs, mb, nb, a["max_q"],
+                                    None, check=False)
+    assert pcall(table=None) == sw.SW_ERR_NULL
+    assert pcall(table=0x8001) == sw.SW_ERR_ALIGN
+    assert pcall(bs=24) == sw.SW_ERR_UNSUPPORTED
+    assert pcall(mb=0) == sw.SW_ERR_SHAPE
+    assert pcall(nb=-1) == sw.SW_ERR_SHAPE
+    assert pcall(n_tokens=0) == sw.SW_OK
