@@ -410,8 +410,7 @@ int sw_release(void);
  *                      waves would exceed 8).  For the key-split kernel: waves per
  *                      workgroup, 2, 4 or 8.
  *   SW_PARAM_PREFILL_KERNEL  0 = library default, 1 = the kernel that shares staged
- *                      K/V tiles among the heads of a group (at most 8 query heads per
- *                      key/value head, SW_ERR_UNSUPPORTED at call time otherwise),
+ *                      K/V tiles among the waves of a workgroup (up to 8 heads of a group),
  *                      2 = the kernel that splits a query block's key range over the
  *                      waves of a workgroup.  The two differ by rounding only.
  */

@@ -618,11 +618,9 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
         long long q_bound = std::min<long long>(n_tokens, (long long)n_req * max_q_len);
         if (mixed) q_bound = std::max<long long>(0, q_bound - n_req);
         const long long groups = (q_bound / (32 * shared_qw)) * n_kvh * (a.group / shared_hp);
-        which = (a.group <= 8 && groups >= kPrefillSharedMinGroups) ? 1 : 2;
+        which = groups >= kPrefillSharedMinGroups ? 1 : 2;
     }
     if (pg) which = 2;              // the only kernel with block-table addressing
-    if (which == 1 && a.group > 8)
-        return fail(SW_ERR_UNSUPPORTED, "the shared-tile prompt kernel takes at most 8 query heads per key/value head");
     int split_waves = 4;
     if (which == 2) {
         a.hp = 1;

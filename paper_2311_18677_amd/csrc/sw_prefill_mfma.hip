@@ -1,5 +1,5 @@
 // Prompt-phase (causal) attention on the matrix cores (gfx950, wave64),
-// head_dim 128, up to 8 query heads per key/value head.
+// head_dim 128, any number of query heads per key/value head (up to 8 of them share a workgroup).
 //
 // The prompt phase processes all tokens of a prompt in one pass (paper section
 // 2.2) and is compute bound (section 3.5, Insight V): prompt token i attends to
@@ -167,7 +167,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 
 bool sw_prefill_mfma_supported(const SwPrefillArgs &a)
 {
-    return a.head_dim == kD && a.group >= 1 && a.group <= 8;
+    return a.head_dim == kD && a.group >= 1 && a.hp >= 1 && a.hp <= 8 && a.group % a.hp == 0;
 }
 
 // How a workgroup is shaped: hp query heads of one group, qw waves (32 query positions

@@ -42,13 +42,8 @@ def run_prefill(batch, qt, starts, n_tokens=None, pad_bits=NAN_BITS, tag=""):
     out = torch.full((n_tokens, cfg.n_qh, cfg.head_dim), float("nan"), dtype=torch.float16, device="cuda:0")
     starts_d = torch.from_numpy(np.ascontiguousarray(starts, dtype=np.int32)).to("cuda:0")
     print("prefill run", tag, cfg.name, "lens", list(batch.seq_lens)[:8], "n_tokens", n_tokens, flush=True)
-    try:
-        sw.sw_prefill_attn(to_dev(qt), bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], starts_d, out,
-                           n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len)
-    except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and sw.sw_get_param(sw.SW_PARAM_PREFILL_KERNEL) == 1:
-            pytest.skip("the shared-tile kernel takes at most 8 query heads per key/value head")
-        raise
+    sw.sw_prefill_attn(to_dev(qt), bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], starts_d, out,
+                       n_tokens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len)
     torch.cuda.synchronize()
     return out.cpu().numpy(), ref
 
