@@ -620,7 +620,6 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
         const long long groups = (q_bound / (32 * shared_qw)) * n_kvh * (a.group / shared_hp);
         which = groups >= kPrefillSharedMinGroups ? 1 : 2;
     }
-    if (pg) which = 2;              // the only kernel with block-table addressing
     int split_waves = 4;
     if (which == 2) {
         a.hp = 1;

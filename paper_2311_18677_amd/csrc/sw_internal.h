@@ -69,7 +69,7 @@ struct SwPrefillArgs {
     int   qw;                           // waves per query head in a workgroup
     int   n_qblocks;                    // query blocks (of 32 * qw positions) that cover max_len
     long long stride_req, stride_kvh;   // in elements
-    // block-table variant (key-split kernel only): k, v are pools, row t of request r is row
+    // block-table variant: k, v are pools, row t of request r is row
     // t % block_size of pool block block_table[r*max_blocks + t / block_size]; stride_req unused
     const int32_t *block_table;         // null for the dense layout
     long long stride_block;

@@ -25,8 +25,14 @@ using namespace sw_prefill;
 constexpr int kBufBytes = 2 * kTileBytes;          // K tile, then V tile
 constexpr int kBufs     = 3;
 
+// The block table is read-only for the whole launch; reading it through the constant
+// address space lets wave-uniform entries come in over the scalar path.
+typedef const __attribute__((address_space(4))) int32_t *const_table_t;
+
 // NW = waves per workgroup = (query heads per workgroup) * (waves per head).
-template <int NW>
+// PAGED: K and V are block pools addressed through the request's row of the block table
+// (position t = row t % block_size of pool block table[t / block_size]).
+template <int NW, bool PAGED>
 __global__ __launch_bounds__(64 * NW, 1)
 void sw_prefill_mfma_kernel(SwPrefillArgs a)
 {
@@ -65,8 +71,12 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0): the store is done before any load lands
     __builtin_amdgcn_s_barrier();
 
-    const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
-    const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * ((long long)r * a.stride_req + (long long)g * a.stride_kvh);
+    // dense: the (request, head) slab; block table: the head's rows inside pool block 0
+    const long long slab = PAGED ? (long long)g * a.stride_kvh : (long long)r * a.stride_req + (long long)g * a.stride_kvh;
+    const char *kslab = reinterpret_cast<const char *>(a.k) + 2 * slab;
+    const char *vslab = reinterpret_cast<const char *>(a.v) + 2 * slab;
+    const_table_t table = PAGED ? (const_table_t)(a.block_table + (long long)r * a.max_blocks) : nullptr;
+    const int in_block = PAGED ? (1 << a.block_shift) - 1 : ~0;
 
     // tiles the workgroup walks: up to the position of its last query
     const int last_pos = P0 + min(Q0 + q_block, NQ) - 1;
@@ -88,7 +98,18 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
             const int rho = 4 * n + gq;
             const int t = min(t0 + rho, L - 1);                      // rows past the prompt repeat its last row
             const int piece = is_v ? (n16 ^ v_swizzle(rho)) : (n16 ^ (rho & 15));
-            const char *src = (is_v ? vslab : kslab) + (((unsigned)t << 8) | (unsigned)(piece << 4));
+            // block table: the four rows of an instruction share a pool block (blocks hold a
+            // multiple of four positions, tiles start at multiples of 32): one wave-uniform
+            // table read, the id clamped into the pool
+            long long block_off = 0;
+            if (PAGED) {
+                const int tu = min(t0 + 4 * n, L - 1);
+                int id = table[tu >> a.block_shift];
+                id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
+                block_off = 2 * (long long)id * a.stride_block;
+            }
+            const char *src = (is_v ? vslab : kslab) + block_off +
+                              ((((unsigned)t & (unsigned)in_block) << 8) | (unsigned)(piece << 4));
             __builtin_amdgcn_global_load_lds(src, buf + (is_v ? kTileBytes : 0) + n * 1024, 16, 0, 0);
         }
     };
@@ -196,7 +217,8 @@ hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a_in, hipStream_t stream,
     const dim3 grid((unsigned)blocks);
     const int nw = a.hp * a.qw;
 #define SW_PREFILL_CASE(W) \
-    if (nw == W) return sw_launch(sw_prefill_mfma_kernel<W>, grid, dim3(64 * W), 0, stream, ev, a);
+    if (nw == W) return a.block_table ? sw_launch(sw_prefill_mfma_kernel<W, true>, grid, dim3(64 * W), 0, stream, ev, a) \
+                                      : sw_launch(sw_prefill_mfma_kernel<W, false>, grid, dim3(64 * W), 0, stream, ev, a);
     SW_PREFILL_CASE(8) SW_PREFILL_CASE(7) SW_PREFILL_CASE(6) SW_PREFILL_CASE(5)
     SW_PREFILL_CASE(4) SW_PREFILL_CASE(3) SW_PREFILL_CASE(2) SW_PREFILL_CASE(1)
 #undef SW_PREFILL_CASE

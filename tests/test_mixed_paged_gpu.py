@@ -12,6 +12,13 @@ pytestmark = pytest.mark.gpu
 NAN_BITS = 0x7E00
 
 
+@pytest.fixture(autouse=True, params=["default", "shared", "split"])
+def _kernel(request):
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, {"default": 0, "shared": 1, "split": 2}[request.param])
+    yield request.param
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 0)
+
+
 def to_dev(a):
     import torch
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16).reshape(-1)).to("cuda:0").view(torch.float16)
@@ -47,7 +54,7 @@ def run_paged(batch, pb, qt, starts, q_lens, max_q_len, tag):
 
 @pytest.mark.parametrize("block_size", [4, 16, 32, 128])
 @pytest.mark.parametrize("n_qh,n_kvh", [(8, 1), (4, 4)])
-def test_prompts_over_block_pools(block_size, n_qh, n_kvh):
+def test_prompts_over_block_pools(block_size, n_qh, n_kvh, _kernel):
     import torch
     lens = [300, 77, 1, 0, 130, 256]
     cfg = wl.custom_config("pp%d" % block_size, len(lens), n_qh, n_kvh, 128, 384)
@@ -60,13 +67,9 @@ def test_prompts_over_block_pools(block_size, n_qh, n_kvh):
     # the same prompts on the dense cache: the same tiles in the same order, the same bits
     db = sw.upload_batch(batch, pad_bits=NAN_BITS)
     dense = torch.full_like(to_dev(qt).view(qt.shape), float("nan"))
-    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 2)
-    try:
-        sw.sw_prefill_attn(to_dev(qt), db["k_cache"], db["v_cache"], db["seq_lens"], i32(starts), dense,
-                           qt.shape[0], cfg.n_req, n_qh, n_kvh, 128, 384)
-        torch.cuda.synchronize()
-    finally:
-        sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 0)
+    sw.sw_prefill_attn(to_dev(qt), db["k_cache"], db["v_cache"], db["seq_lens"], i32(starts), dense,
+                       qt.shape[0], cfg.n_req, n_qh, n_kvh, 128, 384)
+    torch.cuda.synchronize()
     assert np.array_equal(dense.cpu().numpy().view(np.uint16), out.view(np.uint16))
 
 

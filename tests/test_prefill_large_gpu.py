@@ -96,6 +96,31 @@ def test_prompt_batches_at_bench_sizes_on_sampled_rows(name, shape):
     print(name, "sampled rows: max_abs %.3e row_rel_l2 %.3e over %d rows" % worst)
 
 
+def test_large_prompt_batch_over_block_pools_equals_the_dense_layout():
+    # 16 prompts of 1024 tokens: the shared-tile kernel, with block-table addressing
+    import torch
+    cfg = wl.custom_config("paged_16x1024", 16, 8, 1, 128, 1024)
+    batch = wl.make_batch(cfg, seed=7800, seq_lens=[1024] * 15 + [1000])
+    qt, starts = wl.make_prefill_queries(batch)
+    db = sw.upload_batch(batch, pad_bits=0x7E00)
+    dense = torch.full((qt.shape[0], 8, 128), float("nan"), dtype=torch.float16, device="cuda:0")
+    sw.sw_prefill_attn(to_dev(qt), db["k_cache"], db["v_cache"], db["seq_lens"], i32(starts), dense,
+                       qt.shape[0], 16, 8, 1, 128, 1024)
+    rng = np.random.Generator(np.random.Philox(7800))
+    torch.cuda.synchronize()
+    got = dense.cpu().numpy()
+    worst = check_sampled(batch, db, qt, starts, batch.valid_lens, got, rng, 10)
+    print("dense 16x1024 sampled rows: max_abs %.3e row_rel_l2 %.3e over %d rows" % worst)
+    for bs in (16, 64):
+        pb = sw.upload_paged_batch(batch, bs, pad_bits=0x7E00, seed=bs)
+        out = torch.full_like(dense, float("nan"))
+        print("paged large run, block", bs, flush=True)
+        sw.sw_prefill_attn_paged(to_dev(qt), pb["k_pool"], pb["v_pool"], pb["block_table"], pb["seq_lens"],
+                                 i32(starts), out, qt.shape[0], 16, 8, 1, 128, bs, pb["max_blocks"], pb["n_blocks"])
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), got.view(np.uint16))
+
+
 @pytest.mark.parametrize("name", ["mixed_tiny", "mixed_llama70b_tp8"])
 def test_mixed_configs_match_oracle(name):
     import torch
