@@ -392,7 +392,8 @@ def main_prefill(args):
                    else "dense, padded to max_len"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "sw_prefill_mfma_kernel", "kernel_us": kernel_us,
+                     "kernel": "prompt kernel (sw_prefill_split_kernel below about 77000 query tokens x heads, "
+                               "sw_prefill_mfma_kernel from there)", "kernel_us": kernel_us,
                      "flops_per_launch": flops, "launches_timed": n_rec},
         "cpu_baseline": cpu_baseline,
         "parity_set0": parity,
