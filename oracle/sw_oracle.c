@@ -29,7 +29,12 @@
  *
  * sw_oracle_decode_attn_paged is the same step over a block-table cache
  * (pinned against the dense routine: identity and shuffled block tables must
- * give bit-equal results).
+ * give bit-equal results).  Further down: the cache side of an iteration
+ * (sw_oracle_kv_append), the prompt phase and mixed batches (sw_oracle_mixed_attn,
+ * of which sw_oracle_prefill_attn is the all-tokens case; _paged over block
+ * pools), the cache side of such a pass (sw_oracle_kv_store) and the in-GPU part
+ * of the KV hand-off (sw_oracle_kv_pack, sw_oracle_kv_span_plan); each states its
+ * own definition and pins in the comment above it.
  *
  * Pins: closed forms (one token, identical keys, a dominant key), brute force
  * against a dense matrix formulation, shift / permutation invariance,
