@@ -18,6 +18,8 @@
 // from the accumulators.
 #include "sw_prefill_common.h"
 
+#include <type_traits>
+
 namespace {
 
 using namespace sw_prefill;
@@ -86,8 +88,13 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 
     // this wave's share of tile ti's loads -> buffer ti % 3.  Instruction j < 8 is K rows
     // 4j .. 4j+3 (16-byte pieces XOR-swizzled by row), j >= 8 is V rows 4(j-8) .. +3.
-    auto issue_tile = [&](int ti) {
-        unsigned char *buf = lds + (ti % kBufs) * kBufBytes;
+    // (the buffer index is a compile-time constant everywhere: LDS addresses are then a
+    // per-lane value computed once plus an immediate offset, instead of two vector
+    // instructions per LDS read to add the rotating buffer's offset)
+    auto issue_tile = [&](int ti, auto buf_c) {
+        constexpr int B = decltype(buf_c)::value;
+        static_assert(B >= 0 && B < kBufs, "buffer index");
+        unsigned char *buf = lds + B * kBufBytes;
         const int t0 = ti * kTile;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -124,8 +131,8 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[nb][e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    issue_tile(0);
-    if (n_tiles > 1) issue_tile(1);
+    issue_tile(0, std::integral_constant<int, 0>{});
+    if (n_tiles > 1) issue_tile(1, std::integral_constant<int, 1>{});
 
     // ---- Q^T operands.  Requested after the first tiles so that both latencies overlap;
     // awaited here, once, so that no wait inside the loop has to cover them.
@@ -134,17 +141,19 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 
-    for (int ti = 0; ti < n_tiles; ++ti) {
+    // One tile, staged in buffer B (= ti % kBufs, as a compile-time constant).
+    auto step = [&](int ti, auto buf_c) {
+        constexpr int B = decltype(buf_c)::value;
         // this wave's loads of tile ti have landed (those of tile ti + 1 may be in flight) ...
         if (ti + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C) & 0xc07f);
         else                  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & 0xc07f);
         // ... and so have everyone's; every wave has also finished reading tile ti - 1,
         // whose buffer tile ti + 2 may now overwrite
         __builtin_amdgcn_s_barrier();
-        if (ti + 2 < n_tiles) issue_tile(ti + 2);
-        if (ti >= my_tiles) continue;
+        if (ti + 2 < n_tiles) issue_tile(ti + 2, std::integral_constant<int, (B + 2) % kBufs>{});
+        if (ti >= my_tiles) return;
 
-        const unsigned char *kb = lds + (ti % kBufs) * kBufBytes;
+        const unsigned char *kb = lds + B * kBufBytes;
         const unsigned char *vb = kb + kTileBytes;
         const int t0 = ti * kTile;
 
@@ -160,6 +169,12 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
         pv_block(0, va, p, o);
         softmax_block(1, sacc, diagonal, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         pv_block(1, va, p, o);
+    };
+    static_assert(kBufs == 3, "the loop below is unrolled by the number of buffers");
+    for (int ti = 0; ti < n_tiles; ti += kBufs) {
+        step(ti, std::integral_constant<int, 0>{});
+        if (ti + 1 < n_tiles) step(ti + 1, std::integral_constant<int, 1>{});
+        if (ti + 2 < n_tiles) step(ti + 2, std::integral_constant<int, 2>{});
     }
 
     // ---- this lane's query rows: dims 16e + 4gq + i
