@@ -237,16 +237,15 @@ __device__ __forceinline__ int v_swizzle(int rho) { return (rho & 7) << 1; }
 // Byte offsets, inside a staged V tile, of this lane's sixteen transposing reads: entry
 // [hk][e] serves keys 16hk + 4gq .. +3 and dims 16e .. 16e+15.  They depend on the lane
 // only, so a kernel computes them once.
-__device__ __forceinline__ void vt_offsets(int n16, int gq, unsigned (&off)[2][8])
+__device__ __forceinline__ void vt_offsets(int n16, int gq, unsigned (&off)[8])
 {
+    // rows 4gq + n16/4 (keys 0..15 of the tile); the rows 16 further on (keys 16..31) share
+    // the swizzle and lie exactly 16 rows = 4096 bytes behind: an immediate offset of the read
+    const int rho = 4 * gq + (n16 >> 2);                      // the row whose 8 bytes this lane addresses
 #pragma unroll
-    for (int hk = 0; hk < 2; ++hk) {
-        const int rho = 16 * hk + 4 * gq + (n16 >> 2);        // the row whose 8 bytes this lane addresses
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int piece = 2 * e + ((n16 >> 1) & 1);       // dims 16e + 4(n16 % 4) .. +3 live in this piece
-            off[hk][e] = (unsigned)(rho * kRowBytes + ((piece ^ v_swizzle(rho)) << 4) + 8 * (n16 & 1));
-        }
+    for (int e = 0; e < 8; ++e) {
+        const int piece = 2 * e + ((n16 >> 1) & 1);           // dims 16e + 4(n16 % 4) .. +3 live in this piece
+        off[e] = (unsigned)(rho * kRowBytes + ((piece ^ v_swizzle(rho)) << 4) + 8 * (n16 & 1));
     }
 }
 
@@ -256,14 +255,14 @@ __device__ __forceinline__ void vt_offsets(int n16, int gq, unsigned (&off)[2][8
 // (n16, gq) therefore receives V[key 16hk + 4gq + j][dim 16e + n16], j = 0..3 -- exactly
 // the A operand (row = dim 16e + n16, k-slots = the keys this lane group's P operand
 // holds).  Block e covers dims 16e .. 16e+15 (row = MFMA row).
-__device__ __forceinline__ void load_vt(const unsigned char *vb, const unsigned (&off)[2][8], Frag (&va)[8])
+__device__ __forceinline__ void load_vt(const unsigned char *vb, const unsigned (&off)[8], Frag (&va)[8])
 {
 #pragma unroll
     for (int e = 0; e < 8; ++e)
 #pragma unroll
         for (int hk = 0; hk < 2; ++hk) {
             union { short4_t s; unsigned int u[2]; } x;
-            x.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vb + off[hk][e]));
+            x.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vb + off[e] + hk * 16 * kRowBytes));
             va[e].u[2 * hk] = x.u[0];
             va[e].u[2 * hk + 1] = x.u[1];
         }

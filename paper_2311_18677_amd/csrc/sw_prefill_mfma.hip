@@ -121,7 +121,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
         }
     };
 
-    unsigned vt_off[2][8];
+    unsigned vt_off[8];
     vt_offsets(n16, gq, vt_off);
     float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
     const float lazy_raw = kLazyBits / a.scale_log2e;      // the threshold in raw score units

@@ -111,7 +111,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         const int rho = 4 * n + gq;
         voff[n] = (unsigned)(rho * kRowBytes + ((n16 ^ v_swizzle(rho)) << 4));   // rows +8, +16, +24: + 2048 each
     }
-    unsigned vt_off[2][8];
+    unsigned vt_off[8];
     vt_offsets(n16, gq, vt_off);
 
     // Block table: byte offset of the pool block that holds row 4n of tile t0 (clamped like
