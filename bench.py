@@ -383,7 +383,7 @@ def main_prefill(args):
         "prompt_tokens_per_s_attention_only": n_tokens * steps / elapsed / cfg.n_layers,
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * elapsed / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 in, f32 accumulate", "data": "synthetic",
+        "dtype": "f16", "accumulate": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_qh": cfg.n_qh, "n_kvh": cfg.n_kvh,
                    "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
                    "prompt_tokens": n_tokens, "flops_per_step": flops, "cache_sets": n_sets,
@@ -533,7 +533,7 @@ def main_handoff(args):
         "metric": "KV hand-off packing GB/s (bytes read + bytes written; % of MI355X HBM peak)",
         "value": gbps, "unit": "GB/s", "pct_of_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * elapsed / steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16 (bit copy)",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_kvh": cfg.n_kvh,
                    "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),
@@ -825,7 +825,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 in, f32 accumulate",
+        "dtype": "f16", "accumulate": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "n_req": cfg.n_req, "n_qh": cfg.n_qh, "n_kvh": cfg.n_kvh,
                    "head_dim": cfg.head_dim, "max_len": cfg.max_len, "lens": str(cfg.lens),

@@ -19,8 +19,8 @@ namespace {
 
 constexpr int kVersion = 200;   // 0.2.0
 
-// prompts up to this many positions go to the key-split prompt kernel by default
-// Workgroups of eight waves from which the shared-tile prompt kernel is the faster of the two.
+// Workgroups of eight waves from which the shared-tile prompt kernel is the faster of the
+// two on long prompts (batches of short prompts switch earlier, see causal_attn).
 constexpr long long kPrefillSharedMinGroups = 300;
 
 thread_local std::string t_last_error = "";
@@ -601,7 +601,7 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     a.max_len = max_len;
     // Two kernels.  The shared-tile kernel stages every K/V tile once for the eight waves of
     // a workgroup (the heads of a group, or more query positions of one head) and runs at a
-    // steady 36-38 % of the matrix peak once its workgroups fill the chip more than once;
+    // steady 41-45 % of the matrix peak once its workgroups fill the chip more than once;
     // with fewer its time is that of the longest prompt's last block.  The key-split kernel
     // gives every (32 queries, head) pair a workgroup of its own and splits its keys among
     // the waves: four times the workgroups, each a quarter as long, but no tile is shared.
@@ -612,7 +612,13 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     // a request's result does not depend on the rest of its batch.
     int shared_hp, shared_qw;
     sw_prefill_shape(n_req, n_kvh, a.group, max_q_len, &shared_hp, &shared_qw);
-    int which = g_prefill_kernel;
+    int which, knob_hp, knob_qw;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        which = g_prefill_kernel;
+        knob_hp = g_prefill_hp;
+        knob_qw = g_prefill_qw;
+    }
     if (which == 0) {
         // (in a mixed batch most requests are usually token-phase requests, one row each,
         // which the prompt kernel never sees: leave one row per request out of the estimate)
@@ -629,15 +635,15 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     if (which == 2) {
         a.hp = 1;
         a.qw = 1;
-        if (g_prefill_qw == 2 || g_prefill_qw == 4 || g_prefill_qw == 8) split_waves = g_prefill_qw;
+        if (knob_qw == 2 || knob_qw == 4 || knob_qw == 8) split_waves = knob_qw;
     } else {
         a.hp = shared_hp;
         a.qw = shared_qw;
-        if (g_prefill_hp > 0 && a.group % g_prefill_hp == 0) {
-            a.hp = g_prefill_hp;
+        if (knob_hp > 0 && a.group % knob_hp == 0) {
+            a.hp = knob_hp;
             a.qw = 8 / a.hp > 0 ? 8 / a.hp : 1;
         }
-        if (g_prefill_qw > 0 && a.hp * g_prefill_qw <= 8) a.qw = g_prefill_qw;
+        if (knob_qw > 0 && a.hp * knob_qw <= 8) a.qw = knob_qw;
     }
     a.n_qblocks = (max_q_len + 32 * a.qw - 1) / (32 * a.qw);      // the grid covers max_q_len query tokens
     if (pg) {
