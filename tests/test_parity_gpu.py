@@ -207,6 +207,44 @@ def test_single_launch_variant_is_repeatable_and_agrees_with_two_kernels(kernel)
     assert np.max(np.abs(first.astype(np.float64) - two.astype(np.float64))) <= 2e-3
 
 
+@pytest.mark.parametrize("combine", [1, 2])
+def test_decode_call_in_a_replayed_graph(combine):
+    # the way bench.py launches the step: captured once, replayed with eager work and
+    # synchronisation in between; every replay must give the eager call's bits (for the
+    # single-launch variant that also means its ticket counters are back at zero each time)
+    import torch
+    lens = [700, 3, 256, 1023, 64, 511, 90, 1, 0, 129]
+    cfg = wl.custom_config("gr", len(lens), 8, 1, 128, 1024)
+    batch = wl.make_batch(cfg, seed=5150, seq_lens=lens)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 128)
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, combine)
+    bufs = sw.upload_batch(batch, pad_bits=0x7E00)
+    stream = torch.cuda.Stream()
+    sw.run_batch(bufs, cfg, stream)      # the first call allocates the workspace, outside any capture
+    stream.synchronize()
+    want = bufs["out"].cpu().numpy().copy()
+    assert_parity(want, oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"]), "eager")
+    eager_out = bufs["out"]
+    graph_out = torch.full_like(eager_out, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        sw.sw_decode_attn(bufs["q"], bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], graph_out,
+                          cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(4):
+        graph_out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        print("replay", rep, "combine", combine, flush=True)
+        with torch.cuda.stream(stream):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(graph_out.cpu().numpy().view(np.uint16), want.view(np.uint16)), rep
+        eager_out.fill_(float("nan"))
+        sw.run_batch(bufs, cfg, stream)  # eager work between the replays
+        stream.synchronize()
+        assert np.array_equal(eager_out.cpu().numpy().view(np.uint16), want.view(np.uint16)), rep
+
+
 @pytest.mark.parametrize("which", ["valu", "mfma", "mfma2"])
 @pytest.mark.parametrize("n_req", [65, 300, 1100])
 def test_many_requests_exercise_every_work_map(n_req, which):
