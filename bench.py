@@ -143,13 +143,15 @@ def make_paged_set(cfg, block_size, seed, torch, np, wl, sw, dev, lens=None, roo
     return bufs
 
 
-def read_traffic(workload):
+def read_traffic(workload, summary=None):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
-    summary for this workload (profiles/pmc_<workload>.txt), or None."""
-    path = os.path.join(ROOT, "profiles", "pmc_%s.txt" % workload)
+    summary for this workload (profiles/pmc_<workload>.txt, or a line naming the workload
+    in the summary file given), or None."""
+    path = os.path.join(ROOT, "profiles", summary or "pmc_%s.txt" % workload)
+    key = "hbm_bytes_per_launch %s:" % workload if summary else "hbm_bytes_per_launch:"
     try:
         for line in open(path):
-            if line.startswith("hbm_bytes_per_launch:"):
+            if line.startswith(key):
                 return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
@@ -391,7 +393,8 @@ def main_prefill(args):
                    "kv_layout": ("block pools, block_size %d" % args.paged) if args.paged
                    else "dense, padded to max_len"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+                     "traffic": None if args.paged else read_traffic(cfg.name, "pmc_prefill.txt"),
                      "kernel": "prompt kernel (sw_prefill_split_kernel below about 77000 query tokens x heads, "
                                "sw_prefill_mfma_kernel from there)", "kernel_us": kernel_us,
                      "flops_per_launch": flops, "launches_timed": n_rec},
