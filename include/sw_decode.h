@@ -107,7 +107,11 @@ int sw_kv_layout(int n_req, int n_kvh, int head_dim, int max_len, sw_kv_layout_t
  * demand (a growing call allocates, which synchronises the device), never
  * shrunk, released by sw_release() or at process exit.  Two calls on the SAME
  * stream are ordered; calls on different streams use different workspaces and
- * may overlap.  The result of a request does not depend on which other
+ * may overlap.  The call may be recorded into a HIP graph (stream capture)
+ * once a call of the same or a larger shape has run on that stream outside
+ * any capture: a call that has to grow the workspace allocates and
+ * synchronises, which a capture does not allow (SW_ERR_HIP where the runtime
+ * refuses it).  The result of a request does not depend on which other
  * requests share the batch, and repeating a call gives the same bits.
  * n_req == 0 returns SW_OK without touching the device.
  * Errors: SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN (all
