@@ -157,8 +157,9 @@ static inline long long sw_prefill_items(const SwPrefillArgs &a, int q_block, bo
 {
     const long long by_shape = (long long)a.n_req * a.n_qblocks;
     const long long by_rows = a.n_tokens / q_block + 2LL * a.n_req;
-    // the scan costs every workgroup a little; it pays once it removes a good part of the grid
-    *compact = by_rows * 4 < by_shape * 3;
+    // the scan costs every workgroup a little (every wave reads all the lengths, ceil(n_req / 64)
+    // per lane): it pays once it removes a good part of the grid, and never for huge batches
+    *compact = by_rows * 4 < by_shape * 3 && a.n_req <= 4096;
     return *compact ? by_rows : by_shape;
 }
 bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
