@@ -309,14 +309,100 @@ def load_points(path):
     return arr[:, 0], arr[:, 1], arr[:, 2]
 
 
+MIXED_BATCHES = [8, 16, 32, 64]
+MIXED_PROMPTS = [0, 64, 128, 256, 512, 1024, 1536, 2048]
+MIXED_CONTEXT = 1536
+
+
+def measure_mixed_point(sw, torch, n_decode, ctx, prompt_tokens, n_qh=8, n_kvh=1, d=128, calls=960, n_sets=6):
+    """Microseconds per sw_mixed_attn call: n_decode token-phase requests at context ctx and,
+    if prompt_tokens > 0, one whole prompt of that many tokens in the same call (section 2.4)."""
+    dev = torch.device("cuda:0")
+    n_req = n_decode + (1 if prompt_tokens > 0 else 0)
+    max_len = max(ctx, prompt_tokens)
+    lay = sw.sw_kv_layout(n_req, n_kvh, d, max_len)
+    n_tokens = n_decode + prompt_tokens
+    g = torch.Generator(device=dev)
+    g.manual_seed(9000 * n_decode + prompt_tokens)
+    sets = []
+    for _ in range(n_sets):
+        s = {}
+        for name in ("k", "v"):
+            s[name] = torch.empty(lay.total_elems, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+        s["q"] = torch.empty(n_tokens * n_qh * d, dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=g)
+        s["out"] = torch.zeros(n_tokens * n_qh * d, dtype=torch.float16, device=dev)
+        sets.append(s)
+    lens = [ctx] * n_decode + ([prompt_tokens] if prompt_tokens > 0 else [])
+    q_lens = [1] * n_decode + ([prompt_tokens] if prompt_tokens > 0 else [])
+    starts = [0]
+    for x in q_lens[:-1]:
+        starts.append(starts[-1] + x)
+    lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
+    q_lens_d = torch.tensor(q_lens, dtype=torch.int32, device=dev)
+    starts_d = torch.tensor(starts, dtype=torch.int32, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_mixed_attn(s["q"], s["k"], s["v"], lens_d, starts_d, q_lens_d, s["out"], n_tokens, n_req,
+                         n_qh, n_kvh, d, max_len, max(1, prompt_tokens), st)
+
+    call(sets[0], stream)
+    stream.synchronize()
+    rounds = 8
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for _ in range(rounds):
+            for s in sets:
+                call(s, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    per_replay = rounds * n_sets
+    reps = max(2, calls // per_replay)
+    with torch.cuda.stream(stream):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for _ in range(reps):
+            graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (reps * per_replay) * 1e6
+
+
+def sweep_mixed(path):
+    """What a prompt riding along costs the token phase (the paper's mixed batching, section 2.4):
+    token-phase batch x prompt tokens in the same call, written as a table."""
+    import torch
+    from . import binding as sw
+    if not torch.cuda.is_available():
+        print("perf_model: no GPU visible", file=sys.stderr)
+        return 1
+    sw.load()
+    with open(path, "w") as f:
+        f.write("# sw_mixed_attn, 8 query heads on 1 KV head, head_dim 128: token-phase requests at context %d "
+                "plus one whole prompt in the same call\n# token_requests prompt_tokens microseconds_per_call\n"
+                % MIXED_CONTEXT)
+        for b in MIXED_BATCHES:
+            for p in MIXED_PROMPTS:
+                us = measure_mixed_point(sw, torch, b, MIXED_CONTEXT, p)
+                f.write("%d %d %.3f\n" % (b, p, us))
+                f.flush()
+            print("token-phase batch", b, "done", flush=True)
+            sw.sw_release()
+            torch.cuda.empty_cache()
+    return 0
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--sweep", metavar="FILE", help="measure the grid on the GPU and write it to FILE")
     ap.add_argument("--fit", metavar="FILE", help="fit the model to FILE (80:20 split) and print the errors")
     ap.add_argument("--sweep-prompt", metavar="FILE", help="the prompt-phase grid: measure and write to FILE")
     ap.add_argument("--fit-prompt", metavar="FILE", help="fit the prompt-phase model to FILE (80:20 split)")
+    ap.add_argument("--sweep-mixed", metavar="FILE", help="token-phase batch x prompt tokens in one call: measure, write")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args(argv)
+    if args.sweep_mixed:
+        return sweep_mixed(args.sweep_mixed)
     if args.sweep_prompt or args.fit_prompt:
         if args.sweep_prompt:
             rc = sweep_prompt(args.sweep_prompt)
