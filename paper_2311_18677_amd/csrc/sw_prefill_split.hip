@@ -111,6 +111,21 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
         const int rho = 4 * n + gq;
         voff[n] = (unsigned)(rho * kRowBytes + ((n16 ^ v_swizzle(rho)) << 4));   // rows +8, +16, +24: + 2048 each
     }
+    // Block table: the same per-lane offsets inside a pool block, for tiles that lie wholly
+    // inside the context (no row to clamp).  Row 4n + gq of a tile is row
+    // (t0 + 4n + gq) % block_size of its block; tiles start at multiples of 32 and blocks hold
+    // a power of two of positions, so that is (t0 % block_size) + ((4n + gq) % block_size)
+    // with a wave-uniform first term, which goes into the scalar base of the load.
+    unsigned pk_off[8], pv_off[8];
+    if (PAGED) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int rho = 4 * n + gq;
+            const unsigned row = ((unsigned)rho & (unsigned)in_block) << 8;
+            pk_off[n] = row | (unsigned)((n16 ^ (rho & 15)) << 4);
+            pv_off[n] = row | (unsigned)((n16 ^ v_swizzle(rho)) << 4);
+        }
+    }
     unsigned vt_off[8];
     vt_offsets(n16, gq, vt_off);
 
@@ -141,15 +156,14 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
             for (int n = 0; n < 8; ++n) tb.off[n] = n < 4 ? off0 : off1;
             return tb;
         }
+        // (all eight table reads first, then the arithmetic: one wait instead of eight)
+        int id[8];
+#pragma unroll
+        for (int n = 0; n < 8; ++n) id[n] = PAGED ? table[min(t0 + 4 * n, L - 1) >> a.block_shift] : 0;   // wave-uniform
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
-            tb.off[n] = 0;
-            if (PAGED) {
-                const int tu = min(t0 + 4 * n, L - 1);                // wave-uniform
-                int id = table[tu >> a.block_shift];
-                id = id < 0 ? 0 : (id >= a.n_blocks ? a.n_blocks - 1 : id);
-                tb.off[n] = 2 * (long long)id * a.stride_block;
-            }
+            const int c = id[n] < 0 ? 0 : (id[n] >= a.n_blocks ? a.n_blocks - 1 : id[n]);
+            tb.off[n] = PAGED ? 2 * (long long)c * a.stride_block : 0;
         }
         return tb;
     };
@@ -161,6 +175,11 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 #pragma unroll
             for (int n = 0; n < 8; ++n)
                 __builtin_amdgcn_global_load_lds(kslab + (tile + (n >> 2) * 4096 + koff[n & 3]), wlds + n * 1024, 16, 0, 0);
+        } else if (PAGED && t0 + kTile <= L) {
+            const long long in_blk = (long long)(((unsigned)t0 & (unsigned)in_block) << 8);
+#pragma unroll
+            for (int n = 0; n < 8; ++n)
+                __builtin_amdgcn_global_load_lds(kslab + (tb.off[n] + in_blk) + pk_off[n], wlds + n * 1024, 16, 0, 0);
         } else {
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
@@ -177,6 +196,11 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 #pragma unroll
             for (int n = 0; n < 8; ++n)
                 __builtin_amdgcn_global_load_lds(vslab + (tile + (n >> 1) * 2048 + voff[n & 1]), vlds + n * 1024, 16, 0, 0);
+        } else if (PAGED && t0 + kTile <= L) {
+            const long long in_blk = (long long)(((unsigned)t0 & (unsigned)in_block) << 8);
+#pragma unroll
+            for (int n = 0; n < 8; ++n)
+                __builtin_amdgcn_global_load_lds(vslab + (tb.off[n] + in_blk) + pv_off[n], vlds + n * 1024, 16, 0, 0);
         } else {
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
