@@ -85,7 +85,16 @@ void sw_partial_mfma2_kernel(SwArgs a)
 
     if (FUSED && blockIdx.x < (unsigned)a.n_req) sw_fused_zero_rows<kD>(a, (int)blockIdx.x);
 
-    const SwWork w = sw_find_work<PER>(a, blockIdx.x);
+    // A group of more than 16 query heads is served in head tiles of 16: consecutive
+    // workgroups take the same chunk (they run side by side and meet in L2), each its own
+    // 16 heads.  h0 = the tile's first head within the group, gn = how many it has.
+    const unsigned n_ht = (unsigned)(a.group + 15) >> 4;
+    const unsigned item = n_ht == 1 ? blockIdx.x : blockIdx.x / n_ht;
+    const int ht = n_ht == 1 ? 0 : (int)(blockIdx.x - item * n_ht);
+    const int h0 = 16 * ht;
+    const int gn = min(16, a.group - h0);
+
+    const SwWork w = sw_find_work<PER>(a, item);
     if (!w.valid) return;
     const int r = w.r, g = w.g, c = w.c;
     const int t_begin = c << a.chunk_shift;
@@ -103,10 +112,10 @@ void sw_partial_mfma2_kernel(SwArgs a)
     {
         const int row = 4 * wave + gq;
         // zero rows first, loads second: no LDS store follows a pending global->LDS load
-        if (row < 16 && row >= a.group)
+        if (row < 16 && row >= gn)
             *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
-        if (row < a.group) {       // group <= 16: waves past the fourth stage nothing
-            const uint16_t *src = a.q + (sw_q_row(a, r) * a.n_qh + g * a.group + row) * kD + 8 * (n16 ^ row);
+        if (row < gn) {            // at most 16 rows: waves past the fourth stage nothing
+            const uint16_t *src = a.q + (sw_q_row(a, r) * a.n_qh + g * a.group + h0 + row) * kD + 8 * (n16 ^ row);
             __builtin_amdgcn_global_load_lds(src, sm_q + wave * 1024, 16, 0, 0);
         }
     }
@@ -309,7 +318,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
             if (gq == 0)
                 *reinterpret_cast<uint4_t *>(vlds + (new_pos - t0) * kRowBytes + n16 * 16) =
                     *reinterpret_cast<const uint4_t *>(sm_new + 256 + n16 * 16);
-            if (gq < 2) {
+            if (gq < 2 && ht == 0) {       // every head tile patches its staged rows, the first one stores
                 long long boff = 0;
                 if (PAGED) {
                     int id = table[new_pos >> a.block_shift];
@@ -383,7 +392,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
     // row = head (stride 132 floats), column = dim; this lane owns dims
     // 32gq + 8i + e, i.e. for each i two aligned groups of four consecutive dims
     float *mo = reinterpret_cast<float *>(wlds);
-    if (n16 < a.group) {
+    if (n16 < gn) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -398,7 +407,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
     __syncthreads();
     // single-launch variant: a request of one chunk is finished here
     const bool alone = FUSED && w.L <= a.chunk;
-    for (int idx = threadIdx.x; idx < a.group * (kD / 4); idx += 64 * WAVES) {
+    for (int idx = threadIdx.x; idx < gn * (kD / 4); idx += 64 * WAVES) {
         const int hh = idx >> 5;
         const int j4 = idx & 31;
         float mx = sm_m[0][hh];
@@ -416,29 +425,29 @@ void sw_partial_mfma2_kernel(SwArgs a)
             den = fmaf(f, sm_l[w][hh], den);
         }
         if (alone) {
-            sw_store_final4<kD>(a, sw_q_row(a, r) * a.n_qh + g * a.group + hh, j4, num, den);
+            sw_store_final4<kD>(a, sw_q_row(a, r) * a.n_qh + g * a.group + h0 + hh, j4, num, den);
             continue;
         }
-        const long long slot = sw_ws_slot(a, r, g, c, hh);
+        const long long slot = sw_ws_slot(a, r, g, c, h0 + hh);
         sw_store_partial4(a.ws_o + slot * kD + 4 * j4, num, FUSED);
         if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, FUSED);
     }
     if (FUSED && !alone)
-        sw_fused_tail<kD>(a, r, g, 0, a.group, (w.L + a.chunk - 1) >> a.chunk_shift,
-                          a.counters + (r * a.n_kvh + g), &sm_flag);
+        sw_fused_tail<kD>(a, r, g, h0, gn, (w.L + a.chunk - 1) >> a.chunk_shift,
+                          a.counters + ((long long)(r * a.n_kvh + g) * n_ht + ht), &sm_flag);
 }
 
 }  // namespace
 
 bool sw_partial_mfma2_supported(const SwArgs &a)
 {
-    return a.head_dim == kD && a.group <= 16 && (a.waves == 4 || a.waves == 8);
+    return a.head_dim == kD && a.group <= 64 && (a.waves == 4 || a.waves == 8);
 }
 
 hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
 {
     if (!sw_partial_mfma2_supported(a)) return hipErrorNotSupported;
-    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
+    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks * ((a.group + 15) / 16);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks);
     const int per = sw_worklist_per(a.n_req);

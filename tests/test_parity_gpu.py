@@ -69,7 +69,7 @@ def test_configs_match_oracle(name, which):
 GROUP_SHAPES = [  # (n_qh, n_kvh, head_dim)
     (1, 1, 64), (2, 1, 64), (3, 3, 128), (4, 2, 128), (6, 2, 64), (3, 1, 128), (5, 1, 128),
     (7, 1, 64), (8, 1, 64), (16, 2, 128), (14, 1, 128), (16, 1, 128), (24, 1, 128), (64, 1, 64),
-    (12, 4, 128),
+    (12, 4, 128), (40, 1, 128), (64, 1, 128), (66, 2, 128),      # groups above 16: head tiles of 16, 16, 1
 ]
 
 
