@@ -1,5 +1,6 @@
 // Partial decode attention on the matrix cores, deep-pipelined variant
-// (gfx950, wave64), head_dim 128, up to 16 query heads per key/value head.
+// (gfx950, wave64), head_dim 128, 16 query heads of a key/value head per workgroup
+// (larger groups, up to 64 heads, in head tiles of 16).
 //
 // Same contractions, operand layouts and softmax as the kernel in
 // sw_partial_mfma.hip (S^T = K Q^T and O^T = V^T P^T on
