@@ -821,6 +821,7 @@ def main():
         "pct_of_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "decode_steps_per_s": steps_per_s,
         "model_steps_per_s_attention_only": steps_per_s / cfg.n_layers,
+        "tokens_per_s_attention_only": steps_per_s / cfg.n_layers * cfg.n_req,
         "n_gpus": 1,
         "steps": steps,
         "warmup": warmup,
