@@ -193,7 +193,7 @@ int run_step(const StepIn &in)
     if (chunk == 0) chunk = default_chunk(n_req, n_kvh, max_len);
     // keep the partial kernel's grid below 2^31 workgroups
     // (a group of more than 16 heads takes one workgroup per 16 heads and chunk)
-    while (((long long)(max_len + chunk - 1) / chunk) * n_req * n_kvh * ((group + 15) / 16) > 0x7fffffffLL) chunk *= 2;
+    while ((((long long)(max_len + chunk - 1) / chunk) * n_req * n_kvh + 7) * ((group + 15) / 16) > 0x7fffffffLL) chunk *= 2;
     const int n_chunks = (max_len + chunk - 1) / chunk;
 
     SwArgs a;

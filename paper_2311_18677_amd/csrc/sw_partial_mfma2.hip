@@ -86,12 +86,21 @@ void sw_partial_mfma2_kernel(SwArgs a)
 
     if (FUSED && blockIdx.x < (unsigned)a.n_req) sw_fused_zero_rows<kD>(a, (int)blockIdx.x);
 
-    // A group of more than 16 query heads is served in head tiles of 16: consecutive
-    // workgroups take the same chunk (they run side by side and meet in L2), each its own
-    // 16 heads.  h0 = the tile's first head within the group, gn = how many it has.
+    // A group of more than 16 query heads is served in head tiles of 16, one workgroup per
+    // tile and chunk.  Consecutive workgroups go to different XCDs (eight L2s), so the tiles
+    // of one chunk are numbered eight apart: they start almost together behind the SAME L2,
+    // where the second and later readers of the chunk find it.  With x = id % 8, y = id / 8:
+    // tile y % n_ht of item (y / n_ht) * 8 + x (the host rounds the items up to a multiple
+    // of eight; numbers past the last item find no work).
+    // h0 = the tile's first head within the group, gn = how many it has.
     const unsigned n_ht = (unsigned)(a.group + 15) >> 4;
-    const unsigned item = n_ht == 1 ? blockIdx.x : blockIdx.x / n_ht;
-    const int ht = n_ht == 1 ? 0 : (int)(blockIdx.x - item * n_ht);
+    unsigned item = blockIdx.x;
+    int ht = 0;
+    if (n_ht > 1) {
+        const unsigned x = blockIdx.x & 7u, y = blockIdx.x >> 3;
+        ht = (int)(y % n_ht);
+        item = (y / n_ht) * 8u + x;
+    }
     const int h0 = 16 * ht;
     const int gn = min(16, a.group - h0);
 
@@ -448,7 +457,9 @@ bool sw_partial_mfma2_supported(const SwArgs &a)
 hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
 {
     if (!sw_partial_mfma2_supported(a)) return hipErrorNotSupported;
-    const long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks * ((a.group + 15) / 16);
+    long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
+    const int n_ht = (a.group + 15) / 16;
+    if (n_ht > 1) blocks = (blocks + 7) / 8 * 8 * n_ht;      // see the kernel's numbering of head tiles
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks);
     const int per = sw_worklist_per(a.n_req);
