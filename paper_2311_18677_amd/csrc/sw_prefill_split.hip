@@ -41,9 +41,15 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
     __shared__ float sm_m[WAVES][kQPerWave];
     __shared__ float sm_l[WAVES][kQPerWave];
 
-    // blockIdx -> (item = (request, query block), key/value head, query head of the group)
-    const unsigned hh = blockIdx.x % (unsigned)a.group;
-    const unsigned rest = blockIdx.x / (unsigned)a.group;
+    // blockIdx -> (item = (request, query block), key/value head, query head of the group).
+    // The heads of a group walk the same K/V tiles; consecutive workgroup numbers go to
+    // different XCDs (eight L2s), so the heads of one (item, key/value head) are numbered
+    // eight apart and meet behind the same L2.  With x = id % 8, y = id / 8: head y % group
+    // of pair (y / group) * 8 + x (the host rounds the pairs up to a multiple of eight;
+    // numbers past the last pair find no item).
+    const unsigned x8 = blockIdx.x & 7u, y8 = blockIdx.x >> 3;
+    const unsigned hh = y8 % (unsigned)a.group;
+    const unsigned rest = (y8 / (unsigned)a.group) * 8u + x8;
     const int g = (int)(rest % (unsigned)a.n_kvh);
     const QItem it = find_item(a, rest / (unsigned)a.n_kvh, kQPerWave);
     if (!it.valid) return;
@@ -342,7 +348,8 @@ hipError_t sw_launch_prefill_split(const SwPrefillArgs &a_in, int waves, hipStre
     if (a_in.head_dim != kD) return hipErrorNotSupported;
     SwPrefillArgs a = a_in;
     bool compact;
-    const long long blocks = sw_prefill_items(a, kQPerWave, &compact) * a.n_qh;
+    const long long pairs = sw_prefill_items(a, kQPerWave, &compact) * a.n_kvh;
+    const long long blocks = (pairs + 7) / 8 * 8 * a.group;      // see the kernel's numbering of the heads
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     a.compact = compact;
     const dim3 grid((unsigned)blocks);
