@@ -417,6 +417,10 @@ int sw_release(void);
  *                      K/V tiles among the waves of a workgroup (up to 8 heads of a group),
  *                      2 = the kernel that splits a query block's key range over the
  *                      waves of a workgroup.  The two differ by rounding only.
+ *   SW_PARAM_MIXED_MERGE  mixed batches: where the chunks of the token-phase requests are
+ *                      merged: 0 = library default, 1 = in a combine kernel of its own,
+ *                      2 = by extra workgroups of the prompt kernel (one launch fewer;
+ *                      only with the four-wave key-split prompt kernel).  Same bits.
  */
 #define SW_PARAM_CHUNK   1
 #define SW_PARAM_KERNEL  2
@@ -425,6 +429,7 @@ int sw_release(void);
 #define SW_PARAM_PREFILL_HEADS 5
 #define SW_PARAM_PREFILL_WAVES 6
 #define SW_PARAM_PREFILL_KERNEL 7
+#define SW_PARAM_MIXED_MERGE 8
 int sw_set_param(int key, int value);
 int sw_get_param(int key, int *value);
 

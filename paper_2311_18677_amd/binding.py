@@ -28,6 +28,7 @@ SW_PARAM_WAVES = 4
 SW_PARAM_PREFILL_HEADS = 5
 SW_PARAM_PREFILL_WAVES = 6
 SW_PARAM_PREFILL_KERNEL = 7
+SW_PARAM_MIXED_MERGE = 8
 
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",

@@ -55,6 +55,7 @@ int g_waves = 0;
 int g_prefill_hp = 0;   // prompt-phase kernel: query heads per workgroup
 int g_prefill_qw = 0;   //                      waves per query head (key-split kernel: waves per workgroup)
 int g_prefill_kernel = 0;   // 0 = default, 1 = shared-tile kernel, 2 = key-split kernel
+int g_mixed_merge = 0;      // mixed batches: 0 = default, 1 = combine kernel of its own, 2 = inside the prompt kernel
 
 // per-kernel timing
 struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
@@ -168,6 +169,9 @@ struct StepIn {
     const int32_t *q_rows = nullptr, *q_lens = nullptr;
     long long n_rows = 0;
     int max_q = 0;
+    // mixed batches: if non-null and the step would launch the combine kernel, it does not;
+    // the kernel's arguments go here instead and the caller sees to the merge
+    SwArgs *defer_merge = nullptr;
 };
 
 // Policy, workspace and launches; the arguments have been validated.
@@ -309,9 +313,10 @@ int run_step(const StepIn &in)
         }
     }
 
+    const bool defer = in.defer_merge && !fused;
     SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
     ProfRec rec;
-    int prc = prof_begin(rec, !fused, &prof);
+    int prc = prof_begin(rec, !fused && !defer, &prof);
     if (prc != SW_OK) return prc;
     if (prof) {
         ev_p = {rec.ev[0], rec.ev[1]};
@@ -321,7 +326,8 @@ int run_step(const StepIn &in)
     e = which == 3 ? sw_launch_partial_mfma2(a, stream, prof ? &ev_p : nullptr)
       : which == 2 ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
                    : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
-    if (e == hipSuccess && !fused) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
+    if (e == hipSuccess && !fused && !defer) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
+    if (e == hipSuccess && defer) *in.defer_merge = a;
     if (e != hipSuccess) {
         if (prof) prof_abort(rec);
         return fail_hip(e, "kernel launch");
@@ -390,6 +396,10 @@ int sw_set_param(int key, int value)
         if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "prefill kernel must be 0, 1 or 2");
         g_prefill_kernel = value;
         return SW_OK;
+    case SW_PARAM_MIXED_MERGE:
+        if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "mixed merge must be 0, 1 or 2");
+        g_mixed_merge = value;
+        return SW_OK;
     default:
         return fail(SW_ERR_PARAM, "unknown parameter key");
     }
@@ -407,6 +417,7 @@ int sw_get_param(int key, int *value)
     case SW_PARAM_PREFILL_HEADS: *value = g_prefill_hp; return SW_OK;
     case SW_PARAM_PREFILL_WAVES: *value = g_prefill_qw; return SW_OK;
     case SW_PARAM_PREFILL_KERNEL: *value = g_prefill_kernel; return SW_OK;
+    case SW_PARAM_MIXED_MERGE: *value = g_mixed_merge; return SW_OK;
     default: return fail(SW_ERR_PARAM, "unknown parameter key");
     }
 }
@@ -613,12 +624,13 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     // a request's result does not depend on the rest of its batch.
     int shared_hp, shared_qw;
     sw_prefill_shape(n_req, n_kvh, a.group, max_q_len, &shared_hp, &shared_qw);
-    int which, knob_hp, knob_qw;
+    int which, knob_hp, knob_qw, knob_merge;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         which = g_prefill_kernel;
         knob_hp = g_prefill_hp;
         knob_qw = g_prefill_qw;
+        knob_merge = g_mixed_merge;
     }
     if (which == 0) {
         // (in a mixed batch most requests are usually token-phase requests, one row each,
@@ -674,6 +686,7 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     // (Running the two parts side by side on two streams was tried in both orders, the
     // token-phase kernels first and the prompt kernel first: 33.4 us against 32.1 us on one
     // stream for 63 token-phase requests beside a 1500-token prompt -- no gain.)
+    SwArgs merge_args = {};             // ws_o stays null unless the merge was left to the prompt kernel
     if (mixed) {
         StepIn in{};
         in.q = q; in.k = k_cache; in.v = v_cache;
@@ -687,6 +700,9 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
         in.n_blocks = pg ? pg->n_blocks : 0;
         in.stream = (hipStream_t)stream_v;
         in.q_rows = q_starts; in.q_lens = q_lens; in.n_rows = n_tokens; in.max_q = max_q_len;
+        // With the four-wave key-split kernel to follow, the chunks of the token-phase requests
+        // are merged by extra workgroups of that kernel: two launches instead of three.
+        if (which == 2 && split_waves == 4 && max_q_len > 1 && knob_merge != 1) in.defer_merge = &merge_args;
         rc = run_step(in);
         if (rc != SW_OK) return rc;
         a.skip_single = 1;
@@ -700,7 +716,8 @@ static int causal_attn(const void *q, const void *k_cache, const void *v_cache, 
     if (prc != SW_OK) return prc;
     if (prof) ev = {rec.ev[0], rec.ev[1]};
     hipError_t e;
-    e = which == 2 ? sw_launch_prefill_split(a, split_waves, (hipStream_t)stream_v, prof ? &ev : nullptr)
+    e = which == 2 ? sw_launch_prefill_split(a, split_waves, (hipStream_t)stream_v, prof ? &ev : nullptr,
+                                             merge_args.ws_o ? &merge_args : nullptr)
                    : sw_launch_prefill_mfma(a, (hipStream_t)stream_v, prof ? &ev : nullptr);
     if (e != hipSuccess) {
         if (prof) prof_abort(rec);

@@ -8,15 +8,11 @@
 // groups merge through LDS in group order.  The summation order depends only
 // on the request's own chunk count, so its bits do not depend on the batch.
 #include "sw_internal.h"
+#include "sw_merge.h"
 
 namespace {
 
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef float float2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-
-constexpr int   kGroups = 8;
-constexpr float kNegBig = -1.0e30f;
+using namespace sw_merge;
 
 template <int D>
 __global__ __launch_bounds__(kGroups * (D / 4))
@@ -58,8 +54,7 @@ void sw_combine_kernel(SwArgs a)
         return;
     }
 
-    float m = kNegBig, den = 0.f;
-    float4_t num = float4_t{0.f, 0.f, 0.f, 0.f};
+    Group mine = empty_group();
     for (int c0 = k; c0 < nc; c0 += 4 * kGroups) {
         if (c0 != k) {
 #pragma unroll
@@ -71,39 +66,20 @@ void sw_combine_kernel(SwArgs a)
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (c0 + u * kGroups < nc) {
-                const float m_new = fmaxf(m, mlc[u][0]);
-                const float f_old = __builtin_amdgcn_exp2f(m - m_new);
-                const float f_new = __builtin_amdgcn_exp2f(mlc[u][0] - m_new);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) num[t] = fmaf(f_new, x[u][t], num[t] * f_old);
-                den = fmaf(f_new, mlc[u][1], den * f_old);
-                m = m_new;
-            }
+            if (c0 + u * kGroups < nc) add_chunk(mine, mlc[u][0], mlc[u][1], x[u]);
         }
     }
-    sm_num[k][j4] = num;
-    sm_md[k][j4]  = float2_t{m, den};
+    sm_num[k][j4] = mine.num;
+    sm_md[k][j4]  = float2_t{mine.m, mine.den};
     __syncthreads();
     if (k != 0) return;
-    float mx = sm_md[0][j4][0];
-#pragma unroll
-    for (int g = 1; g < kGroups; ++g) mx = fmaxf(mx, sm_md[g][j4][0]);
-    float4_t tot = float4_t{0.f, 0.f, 0.f, 0.f};
-    float dtot = 0.f;
-#pragma unroll
-    for (int g = 0; g < kGroups; ++g) {
-        const float2_t md = sm_md[g][j4];
-        const float f = __builtin_amdgcn_exp2f(md[0] - mx);   // empty groups: 2^(-1e30 - mx) = 0
-        const float4_t v = sm_num[g][j4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) tot[t] = fmaf(f, v[t], tot[t]);
-        dtot = fmaf(f, md[1], dtot);
-    }
-    half4_t res;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) res[t] = (_Float16)(tot[t] / dtot);   // round to nearest even
-    *out = res;
+    *out = finish([&](int g) {
+        Group s;
+        s.m = sm_md[g][j4][0];
+        s.den = sm_md[g][j4][1];
+        s.num = sm_num[g][j4];
+        return s;
+    });
 }
 
 }  // namespace

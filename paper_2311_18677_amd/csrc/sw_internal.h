@@ -164,7 +164,10 @@ static inline long long sw_prefill_items(const SwPrefillArgs &a, int q_block, bo
 }
 bool       sw_prefill_mfma_supported(const SwPrefillArgs &a);
 void       sw_prefill_shape(int n_req, int n_kvh, int group, int max_len, int *hp, int *qw);
-hipError_t sw_launch_prefill_split(const SwPrefillArgs &a, int waves, hipStream_t stream, const SwLaunchEvents *ev);
+// merge != null (mixed batches, four waves): extra workgroups merge the token-phase chunks that the
+// partial kernel launched before on the same stream left in the workspace (instead of the combine kernel)
+hipError_t sw_launch_prefill_split(const SwPrefillArgs &a, int waves, hipStream_t stream, const SwLaunchEvents *ev,
+                                   const SwArgs *merge = nullptr);
 hipError_t sw_launch_prefill_mfma(const SwPrefillArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 int        sw_kv_copy_rows_per_group();
 hipError_t sw_launch_kv_copy(const SwHandoffArgs &a, bool to_dense, hipStream_t stream, const SwLaunchEvents *ev);

@@ -13,6 +13,7 @@
 // normalised and stored.  The arithmetic per tile is the one of
 // sw_prefill_mfma.hip (shared code in sw_prefill_common.h).
 #include "sw_prefill_common.h"
+#include "sw_merge.h"
 
 #include <type_traits>
 
@@ -31,10 +32,20 @@ typedef const __attribute__((address_space(4))) int32_t *const_table_t;
 
 // PAGED: K and V are block pools addressed through the request's row of the block table
 // (position t = row t % block_size of pool block table[t / block_size]).
-template <int WAVES, bool PAGED>
+// MERGE (mixed batches): the workgroups from number n_prompt on do not belong to the prompt
+// phase at all.  They merge the chunks of the token-phase requests that the partial kernel
+// of the same call, launched just before on the same stream, has left in the workspace
+// (arguments d) -- the work of the combine kernel, riding along here so that the call is
+// two launches instead of three.  Eight output rows per workgroup, one thread per four dims.
+template <int WAVES, bool PAGED, bool MERGE>
 __global__ __launch_bounds__(64 * WAVES, WAVES >= 4 ? 8 / WAVES : 2)
-void sw_prefill_split_kernel(SwPrefillArgs a)
+void sw_prefill_split_kernel(SwPrefillArgs a, SwArgs d, unsigned n_prompt)
 {
+    if (MERGE && blockIdx.x >= n_prompt) {
+        const long long rh = (long long)(blockIdx.x - n_prompt) * (64 * WAVES / (kD / 4)) + (threadIdx.x / (kD / 4));
+        if (rh < (long long)d.n_req * d.n_qh) sw_merge::merge_row_serial<kD>(d, (int)rh, (int)(threadIdx.x % (kD / 4)));
+        return;
+    }
     __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
     // the block's 32 query rows
     __shared__ __attribute__((aligned(16))) unsigned char sm_q[kQPerWave * kRowBytes];
@@ -343,24 +354,38 @@ void sw_prefill_split_kernel(SwPrefillArgs a)
 
 }  // namespace
 
-hipError_t sw_launch_prefill_split(const SwPrefillArgs &a_in, int waves, hipStream_t stream, const SwLaunchEvents *ev)
+hipError_t sw_launch_prefill_split(const SwPrefillArgs &a_in, int waves, hipStream_t stream, const SwLaunchEvents *ev,
+                                   const SwArgs *merge)
 {
     if (a_in.head_dim != kD) return hipErrorNotSupported;
     SwPrefillArgs a = a_in;
     bool compact;
     const long long pairs = sw_prefill_items(a, kQPerWave, &compact) * a.n_kvh;
-    const long long blocks = (pairs + 7) / 8 * 8 * a.group;      // see the kernel's numbering of the heads
-    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const long long n_prompt = (pairs + 7) / 8 * 8 * a.group;      // see the kernel's numbering of the heads
+    if (n_prompt <= 0 || n_prompt > 0x7fffffffLL) return hipErrorInvalidValue;
     a.compact = compact;
-    const dim3 grid((unsigned)blocks);
+    if (merge) {
+        // the token-phase rows to merge: 256 threads = 8 rows of 32 four-dim pieces
+        if (waves != 4 || merge->head_dim != kD) return hipErrorInvalidValue;
+        const long long rows = (long long)merge->n_req * merge->n_qh;
+        const long long blocks = n_prompt + (rows + 7) / 8;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)blocks);
+        return a.block_table
+            ? sw_launch(sw_prefill_split_kernel<4, true, true>, grid, dim3(256), 0, stream, ev, a, *merge, (unsigned)n_prompt)
+            : sw_launch(sw_prefill_split_kernel<4, false, true>, grid, dim3(256), 0, stream, ev, a, *merge, (unsigned)n_prompt);
+    }
+    const dim3 grid((unsigned)n_prompt);
+    const SwArgs none = {};
+    const unsigned np = (unsigned)n_prompt;
     if (a.block_table) {
-        if (waves == 8) return sw_launch(sw_prefill_split_kernel<8, true>, grid, dim3(512), 0, stream, ev, a);
-        if (waves == 4) return sw_launch(sw_prefill_split_kernel<4, true>, grid, dim3(256), 0, stream, ev, a);
-        if (waves == 2) return sw_launch(sw_prefill_split_kernel<2, true>, grid, dim3(128), 0, stream, ev, a);
+        if (waves == 8) return sw_launch(sw_prefill_split_kernel<8, true, false>, grid, dim3(512), 0, stream, ev, a, none, np);
+        if (waves == 4) return sw_launch(sw_prefill_split_kernel<4, true, false>, grid, dim3(256), 0, stream, ev, a, none, np);
+        if (waves == 2) return sw_launch(sw_prefill_split_kernel<2, true, false>, grid, dim3(128), 0, stream, ev, a, none, np);
         return hipErrorInvalidValue;
     }
-    if (waves == 8) return sw_launch(sw_prefill_split_kernel<8, false>, grid, dim3(512), 0, stream, ev, a);
-    if (waves == 4) return sw_launch(sw_prefill_split_kernel<4, false>, grid, dim3(256), 0, stream, ev, a);
-    if (waves == 2) return sw_launch(sw_prefill_split_kernel<2, false>, grid, dim3(128), 0, stream, ev, a);
+    if (waves == 8) return sw_launch(sw_prefill_split_kernel<8, false, false>, grid, dim3(512), 0, stream, ev, a, none, np);
+    if (waves == 4) return sw_launch(sw_prefill_split_kernel<4, false, false>, grid, dim3(256), 0, stream, ev, a, none, np);
+    if (waves == 2) return sw_launch(sw_prefill_split_kernel<2, false, false>, grid, dim3(128), 0, stream, ev, a, none, np);
     return hipErrorInvalidValue;
 }

@@ -12,14 +12,19 @@ pytestmark = pytest.mark.gpu
 NAN_BITS = 0x7E00
 
 
-@pytest.fixture(autouse=True, params=["default", "shared", "split4", "split8"])
+@pytest.fixture(autouse=True, params=["default", "shared", "split4", "split4_own_combine", "split8"])
 def _kernel(request):
-    which, waves = {"default": (0, 0), "shared": (1, 0), "split4": (2, 4), "split8": (2, 8)}[request.param]
+    # split4: the chunks of the token-phase requests are merged inside the prompt kernel
+    # (the default wherever that kernel runs); split4_own_combine: by the combine kernel
+    which, waves, merge = {"default": (0, 0, 0), "shared": (1, 0, 0), "split4": (2, 4, 2),
+                           "split4_own_combine": (2, 4, 1), "split8": (2, 8, 0)}[request.param]
     sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, which)
     sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, waves)
+    sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, merge)
     yield request.param
     sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 0)
     sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, 0)
+    sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, 0)
 
 
 def to_dev(a):
@@ -241,3 +246,42 @@ def test_mixed_call_in_a_replayed_graph():
         call(eager, stream)          # eager work between the replays
         stream.synchronize()
         assert np.array_equal(eager.cpu().numpy().view(np.uint16), want)
+
+
+def test_merge_inside_the_prompt_kernel_gives_the_combine_kernels_bits(_kernel):
+    # token-phase requests long enough for many chunks (two-kernel form of the token phase),
+    # beside prompts: the rows are the same bits whichever kernel merges the chunks, and
+    # the token-phase rows are sw_decode_attn's
+    if _kernel != "default":
+        pytest.skip("sets the merge itself")
+    import torch
+    lens = [2300, 40, 900, 2304, 1, 513, 2000, 0, 1500, 257, 300]
+    qls = [1, 40, 1, 1, 1, 13, 1, 1, 700, 1, 0]
+    cfg = wl.custom_config("mxmerge", len(lens), 8, 1, 128, 2304)
+    batch = wl.make_batch(cfg, seed=4900, seq_lens=lens)
+    qt, starts, nq = wl.make_mixed_queries(batch, qls)
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, 128)          # 18 chunks per long request: the two-kernel form
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 2)
+    sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, 4)
+    outs = {}
+    try:
+        for merge in (1, 2):
+            sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, merge)
+            out, ref, bufs = run_mixed(batch, qt, starts, qls, 2304, tag="merge %d" % merge)
+            assert_parity(out, ref, cfg.name)
+            outs[merge] = out.copy()
+        assert np.array_equal(outs[1].view(np.uint16), outs[2].view(np.uint16))
+        # the token-phase rows against the plain decode call on the same cache
+        dq = np.stack([qt[min(int(starts[r]), qt.shape[0] - 1)] for r in range(len(lens))])
+        d_out = torch.zeros((len(lens), 8, 128), dtype=torch.float16, device="cuda:0")
+        sw.sw_decode_attn(to_dev(dq), bufs["k_cache"], bufs["v_cache"], bufs["seq_lens"], d_out, len(lens), 8, 1, 128, 2304)
+        torch.cuda.synchronize()
+        d_np = d_out.cpu().numpy()
+        for r, (L, q) in enumerate(zip(lens, qls)):
+            if q == 1 and L > 0:
+                assert np.array_equal(outs[2][starts[r]].view(np.uint16), d_np[r].view(np.uint16)), r
+    finally:
+        sw.sw_set_param(sw.SW_PARAM_CHUNK, 0)
+        sw.sw_set_param(sw.SW_PARAM_PREFILL_KERNEL, 0)
+        sw.sw_set_param(sw.SW_PARAM_PREFILL_WAVES, 0)
+        sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, 0)
