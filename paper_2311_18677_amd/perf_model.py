@@ -314,12 +314,17 @@ MIXED_PROMPTS = [0, 64, 128, 256, 512, 1024, 1536, 2048]
 MIXED_CONTEXT = 1536
 
 
-def measure_mixed_point(sw, torch, n_decode, ctx, prompt_tokens, n_qh=8, n_kvh=1, d=128, calls=960, n_sets=6):
+MIXED_MAX_LEN = 4096
+
+
+def measure_mixed_point(sw, torch, n_decode, ctx, prompt_tokens, n_qh=8, n_kvh=1, d=128, calls=960, n_sets=6,
+                        max_len=MIXED_MAX_LEN):
     """Microseconds per sw_mixed_attn call: n_decode token-phase requests at context ctx and,
-    if prompt_tokens > 0, one whole prompt of that many tokens in the same call (section 2.4)."""
+    if prompt_tokens > 0, one whole prompt of that many tokens in the same call (section 2.4).
+    The caches are laid out for max_len positions, as a token machine's are."""
     dev = torch.device("cuda:0")
     n_req = n_decode + (1 if prompt_tokens > 0 else 0)
-    max_len = max(ctx, prompt_tokens)
+    max_len = max(max_len, ctx, prompt_tokens)
     lay = sw.sw_kv_layout(n_req, n_kvh, d, max_len)
     n_tokens = n_decode + prompt_tokens
     g = torch.Generator(device=dev)
@@ -379,8 +384,8 @@ def sweep_mixed(path):
     sw.load()
     with open(path, "w") as f:
         f.write("# sw_mixed_attn, 8 query heads on 1 KV head, head_dim 128: token-phase requests at context %d "
-                "plus one whole prompt in the same call\n# token_requests prompt_tokens microseconds_per_call\n"
-                % MIXED_CONTEXT)
+                "(caches laid out for %d positions) plus one whole prompt in the same call\n"
+                "# token_requests prompt_tokens microseconds_per_call\n" % (MIXED_CONTEXT, MIXED_MAX_LEN))
         for b in MIXED_BATCHES:
             for p in MIXED_PROMPTS:
                 us = measure_mixed_point(sw, torch, b, MIXED_CONTEXT, p)
