@@ -418,7 +418,8 @@ def main_prefill(args):
         line["config"]["algorithmic_bytes_per_step"] = kv
         line["roofline"] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                             "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
-                            "kernel": "token-phase partial + merge, then the prompt kernel (sum of the three)",
+                            "kernel": "token-phase partial kernel, then the prompt kernel with the merge of the token-phase "
+                                      "chunks riding along (sum of the kernels' times)",
                             "kernel_us": kernel_us, "bytes_per_launch": kv, "launches_timed": n_rec,
                             "tflops": achieved}
         if cpu_baseline:
