@@ -104,6 +104,10 @@ def test_params_roundtrip_and_validation():
     assert sw.sw_get_param(sw.SW_PARAM_WAVES) == 8
     sw.sw_set_param(sw.SW_PARAM_WAVES, 0)
     assert sw.sw_set_param(99, 1, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, 3, check=False) == sw.SW_ERR_PARAM
+    sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, 1)
+    assert sw.sw_get_param(sw.SW_PARAM_MIXED_MERGE) == 1
+    sw.sw_set_param(sw.SW_PARAM_MIXED_MERGE, 0)
     with pytest.raises(sw.SwError):
         sw.sw_set_param(99, 1)
 
