@@ -389,6 +389,16 @@ int sw_version(void);
 int sw_release(void);
 
 /*
+ * sw_device_status -- support: waits for the current device to go idle and reports
+ * whether any single-launch merge on it ever gave up waiting for another workgroup's
+ * partial result (the wait inside the kernel is bounded so that a kernel always ends; a
+ * give-up leaves the affected output rows wrong and sets a flag in the workspace).
+ *   gave_up   HOST, written: 0 = never, 1 = at least once since the workspace was allocated.
+ * Returns SW_OK, SW_ERR_NULL or SW_ERR_HIP.  Not part of a step; synchronises.
+ */
+int sw_device_status(int *gave_up);
+
+/*
  * Tuning and test knobs (support calls, not part of the step).  They change
  * how the step is scheduled, never what it computes.  Process-wide; set them
  * while no call is in flight.
@@ -396,13 +406,14 @@ int sw_release(void);
  *                      (split over context length); 0 = library default;
  *                      otherwise a power of two in [64, 65536].
  *   SW_PARAM_KERNEL    0 = library default choice, 1 = force the vector-ALU
- *                      partial kernel, 2 = force the matrix-core (MFMA)
- *                      partial kernel, 3 = force the matrix-core kernel that
- *                      stages both K and V through LDS (SW_ERR_UNSUPPORTED at
- *                      call time if the shape has no such kernel).
- *   SW_PARAM_COMBINE   how the chunks of a request are merged: 0 = library default,
+ *                      kernel, 2 = force the matrix-core (MFMA) kernel
+ *                      (SW_ERR_UNSUPPORTED at call time if the shape has no such
+ *                      kernel: it needs head_dim 128).
+ *   SW_PARAM_COMBINE   how the chunks of a request are merged: 0 = library default
+ *                      (the same launch wherever its workspace stays below 4 GiB),
  *                      1 = a second (combine) kernel, 2 = in the same launch, by
- *                      the workgroup that finishes a request's head group last.
+ *                      one of the workgroups of the request's head group
+ *                      (SW_ERR_UNSUPPORTED at call time above 4 GiB).
  *                      Each is deterministic; the two differ by rounding only.
  *   SW_PARAM_WAVES     waves per workgroup of the matrix-core partial kernel:
  *                      0 = library default, else 4, 8 or 16.

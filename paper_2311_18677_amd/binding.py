@@ -33,7 +33,7 @@ SW_PARAM_MIXED_MERGE = 8
 EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
            "sw_prefill_attn", "sw_mixed_attn", "sw_prefill_attn_paged", "sw_mixed_attn_paged", "sw_kv_store", "sw_kv_store_paged", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
-           "sw_last_error", "sw_version", "sw_release",
+           "sw_last_error", "sw_version", "sw_release", "sw_device_status",
            "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop", "sw_stream_read")
 
 
@@ -108,6 +108,8 @@ def load():
     lib.sw_version.argtypes = []
     lib.sw_release.restype = ci
     lib.sw_release.argtypes = []
+    lib.sw_device_status.restype = ci
+    lib.sw_device_status.argtypes = [ctypes.POINTER(ci)]
     lib.sw_set_param.restype = ci
     lib.sw_set_param.argtypes = [ci, ci]
     lib.sw_get_param.restype = ci
@@ -274,6 +276,13 @@ def sw_kv_span_plan(block_table, seq_lens, span_first, span_blocks, n_spans, n_r
 
 def sw_release():
     return _check(load().sw_release())
+
+
+def sw_device_status():
+    """1 if a single-launch merge on the current device ever gave up waiting, else 0 (synchronises)."""
+    flag = ctypes.c_int(0)
+    _check(load().sw_device_status(ctypes.byref(flag)))
+    return flag.value
 
 
 def sw_set_param(key, value, check=True):

@@ -15,12 +15,15 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsw_decode.so")
-SOURCES = ["sw_api.hip", "sw_partial_valu.hip", "sw_partial_mfma.hip", "sw_partial_mfma2.hip", "sw_combine.hip", "sw_lens.hip", "sw_prefill_mfma.hip", "sw_kv_handoff.hip", "sw_prefill_split.hip", "sw_calibrate.hip", "sw_kv_store.hip"]
+SOURCES = ["sw_api.hip", "sw_partial_valu.hip", "sw_decode_split.hip", "sw_combine.hip", "sw_lens.hip", "sw_prefill_mfma.hip", "sw_kv_handoff.hip", "sw_prefill_split.hip", "sw_calibrate.hip", "sw_kv_store.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # leading scalar kernel arguments arrive in registers with the wave (the decode kernel's
+    # length scan starts from them); kernels whose first argument is a struct are unaffected
+    "-mllvm", "-amdgpu-kernarg-preload-count=8",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

@@ -6,6 +6,7 @@
 #include "sw_internal.h"
 
 #include <algorithm>
+#include <array>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -37,12 +38,26 @@ int fail_hip(hipError_t e, const char *what)
     return fail(SW_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+// Library-owned device memory of one (device, stream).
+//   plain : partial results of the two-kernel form, (head_dim + 2) floats per slot.
+//   fused : single-launch form -- a 256-byte header (word 0: set by the device if a merge gave
+//           up), the per-unit states, then the tagged pieces (see sw_fused.h).  Both parts are
+//           allocated together and start zeroed together: an epoch that restarted from zero
+//           must never meet pieces tagged by its earlier life.
+// A block that is outgrown is not freed: a HIP graph captured earlier on the stream still
+// holds its address.  It goes to `retired` and is freed by sw_release().
 struct Workspace {
-    float *base = nullptr;       // partial results
-    size_t bytes = 0;
-    unsigned *counters = nullptr;   // ticket counters of the single-launch variant (kept at zero)
-    size_t n_counters = 0;
+    float *plain = nullptr;
+    size_t plain_bytes = 0;
+    char *fused = nullptr;
+    size_t unit_cap = 0;            // unit states the block holds
+    size_t tag_bytes = 0;           // bytes of tagged pieces the block holds
+    std::vector<void *> retired;
+    // geometry ids: one per way of laying slots out (n_kvh, group, n_chunks, head_dim)
+    std::map<std::array<int, 4>, unsigned> geometry;
 };
+constexpr size_t kFusedHeader = 256;
+constexpr unsigned kMaxGeometry = (1u << 20) - 1;
 
 std::mutex g_mu;
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
@@ -140,19 +155,15 @@ int default_chunk(int n_req, int n_kvh, int max_len)
 // Which partial kernel serves a shape when the caller has not forced one.
 int default_kernel(const SwArgs &a)
 {
-    if (sw_partial_mfma2_supported(a)) return 3;
-    return sw_partial_mfma_supported(a) && !a.block_table && !a.k_new ? 2 : 1;
+    return sw_decode_split_supported(a) ? 2 : 1;
 }
 
-// Whether the last workgroup of each unit merges the chunks itself (one launch) or a
-// second kernel does.  One launch saves a dispatch (about half a microsecond of a call
-// that takes 7-12 us on short contexts) but its merge runs behind a ticket taken at the
-// device's coherence point and reads the other chunks from there: measured faster while
-// a request has at most 8 chunks (one round of loads), slower beyond.  The choice
-// depends on max_len alone (through the chunk length), never on the batch.
-bool default_fused(int n_chunks)
+// One launch (a workgroup of each unit merges the unit's chunks, sw_fused.h) or two (a merge
+// kernel).  One launch is the default wherever its workspace of tagged pieces can be
+// addressed with 32-bit offsets; the choice never looks at the batch's lengths.
+bool fused_fits(size_t slots, int head_dim)
 {
-    return n_chunks <= 8;
+    return slots * (size_t)(head_dim / 2 + 1) * 16 < (1ull << 32);
 }
 
 // Everything one step needs, dense or block-table.
@@ -173,6 +184,72 @@ struct StepIn {
     // the kernel's arguments go here instead and the caller sees to the merge
     SwArgs *defer_merge = nullptr;
 };
+
+// Two-kernel form: slots of (head_dim + 2) floats per (request, query head, chunk).
+int workspace_plain(Workspace &ws, SwArgs &a, size_t slots, hipStream_t stream)
+{
+    (void)stream;
+    const size_t need = slots * (size_t)(a.head_dim + 2) * sizeof(float);
+    if (ws.plain_bytes < need) {
+        if (ws.plain) ws.retired.push_back(ws.plain);
+        ws.plain = nullptr;
+        ws.plain_bytes = 0;
+        const size_t grow = need + need / 4;
+        hipError_t e = hipMalloc((void **)&ws.plain, grow);
+        if (e != hipSuccess) {
+            ws.plain = nullptr;
+            return fail_hip(e, "hipMalloc(workspace)");
+        }
+        ws.plain_bytes = grow;
+    }
+    a.ws_o = ws.plain;
+    a.ws_ml = ws.plain + slots * a.head_dim;
+    return SW_OK;
+}
+
+// Single-launch form: header, unit states, tagged pieces; zeroed whenever (re)allocated,
+// in stream order before the kernel that uses them.
+int workspace_fused(Workspace &ws, SwArgs &a, size_t slots, hipStream_t stream)
+{
+    const size_t n_units = (size_t)a.n_req * a.n_qh;      // covers (request, kv head, head tile)
+    const size_t tag_need = slots * (size_t)(a.head_dim / 2 + 1) * 16;
+    bool fresh = false;
+    if (ws.unit_cap < n_units || ws.tag_bytes < tag_need) {
+        const size_t unit_cap = std::max(ws.unit_cap, n_units + n_units / 4 + 64);
+        size_t tag_bytes = std::max(ws.tag_bytes, tag_need + tag_need / 4);
+        tag_bytes = std::min<size_t>((tag_bytes + 255) & ~(size_t)255, 0xffffff00u);
+        const size_t total = kFusedHeader + unit_cap * sizeof(SwUnitState) + tag_bytes;
+        char *blk = nullptr;
+        hipError_t e = hipMalloc((void **)&blk, total);
+        if (e != hipSuccess) return fail_hip(e, "hipMalloc(workspace)");
+        if (ws.fused) ws.retired.push_back(ws.fused);
+        ws.fused = blk;
+        ws.unit_cap = unit_cap;
+        ws.tag_bytes = tag_bytes;
+        ws.geometry.clear();
+        fresh = true;
+    }
+    const std::array<int, 4> key = {a.n_kvh, a.group, a.n_chunks, a.head_dim};
+    auto it = ws.geometry.find(key);
+    if (it == ws.geometry.end()) {
+        if (ws.geometry.size() >= kMaxGeometry) {     // ids used up: start over on a clean block
+            ws.geometry.clear();
+            fresh = true;
+        }
+        const unsigned id = (unsigned)ws.geometry.size() + 1;
+        it = ws.geometry.emplace(key, id).first;
+    }
+    if (fresh) {
+        hipError_t e = hipMemsetAsync(ws.fused, 0, kFusedHeader + ws.unit_cap * sizeof(SwUnitState) + ws.tag_bytes, stream);
+        if (e != hipSuccess) return fail_hip(e, "hipMemsetAsync(workspace)");
+    }
+    a.dev_err = reinterpret_cast<unsigned *>(ws.fused);
+    a.units = reinterpret_cast<SwUnitState *>(ws.fused + kFusedHeader);
+    a.ws_tag = ws.fused + kFusedHeader + ws.unit_cap * sizeof(SwUnitState);
+    a.ws_tag_bytes = (unsigned)ws.tag_bytes;
+    a.geometry = it->second;
+    return SW_OK;
+}
 
 // Policy, workspace and launches; the arguments have been validated.
 int run_step(const StepIn &in)
@@ -243,74 +320,32 @@ int run_step(const StepIn &in)
     }
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
 
-    // 1 = vector ALU, 2 = matrix cores (V in registers), 3 = matrix cores (K and V through LDS)
+    // 1 = vector ALU, 2 = matrix cores
     int which = kernel;
     if (which == 0) which = default_kernel(a);
-    if (which == 2 && in.k_new)
-        return fail(SW_ERR_UNSUPPORTED, "the register-staged matrix-core kernel has no append form");
-    if (which == 2 && !sw_partial_mfma_supported(a))
+    if (which == 2 && !sw_decode_split_supported(a))
         return fail(SW_ERR_UNSUPPORTED, "the matrix-core kernel does not cover this shape");
-    if (which == 3 && !sw_partial_mfma2_supported(a))
-        return fail(SW_ERR_UNSUPPORTED, "the LDS-staged matrix-core kernel does not cover this shape");
-    if (which == 2 && in.block_table)
-        return fail(SW_ERR_UNSUPPORTED, "the register-staged matrix-core kernel has no block-table form");
 
-    const bool fused = combine == 0 ? default_fused(n_chunks) : combine == 2;
+    const size_t slots = (size_t)n_req * n_qh * n_chunks;
+    if (combine == 2 && !fused_fits(slots, head_dim))
+        return fail(SW_ERR_UNSUPPORTED, "the single-launch workspace would exceed 4 GiB");
+    const bool fused = combine == 0 ? fused_fits(slots, head_dim) : combine == 2;
 
-    // ---- workspace: slots of (head_dim + 2) floats per (request, query head, chunk) ----
+    // ---- workspace ----
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
-    const size_t slots = (size_t)n_req * n_qh * n_chunks;
-    const size_t o_bytes = slots * head_dim * sizeof(float);
-    const size_t need = o_bytes + slots * 2 * sizeof(float);
+    a.ws_o = a.ws_ml = nullptr;
+    a.units = nullptr;
+    a.ws_tag = nullptr;
+    a.ws_tag_bytes = 0;
+    a.geometry = 0;
+    a.dev_err = nullptr;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         Workspace &ws = g_ws[std::make_pair(dev, stream)];
-        if (ws.bytes < need) {
-            if (ws.base) {
-                e = hipStreamSynchronize(stream);   // earlier calls on this stream may still use it
-                if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
-                e = hipFree(ws.base);
-                ws.base = nullptr;
-                ws.bytes = 0;
-                if (e != hipSuccess) return fail_hip(e, "hipFree");
-            }
-            const size_t grow = need + need / 4;
-            e = hipMalloc((void **)&ws.base, grow);
-            if (e != hipSuccess) {
-                ws.base = nullptr;
-                return fail_hip(e, "hipMalloc(workspace)");
-            }
-            ws.bytes = grow;
-        }
-        a.ws_o = ws.base;
-        a.ws_ml = ws.base + slots * head_dim;
-        a.counters = nullptr;
-        if (fused) {
-            // one counter per (request, key/value head, head tile); n_req * n_qh covers it
-            const size_t n_cnt = (size_t)n_req * n_qh;
-            if (ws.n_counters < n_cnt) {
-                if (ws.counters) {
-                    e = hipStreamSynchronize(stream);
-                    if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
-                    e = hipFree(ws.counters);
-                    ws.counters = nullptr;
-                    ws.n_counters = 0;
-                    if (e != hipSuccess) return fail_hip(e, "hipFree");
-                }
-                const size_t grow = n_cnt + n_cnt / 4 + 64;
-                e = hipMalloc((void **)&ws.counters, grow * sizeof(unsigned));
-                if (e == hipSuccess) e = hipMemset(ws.counters, 0, grow * sizeof(unsigned));
-                if (e != hipSuccess) {
-                    if (ws.counters) (void)hipFree(ws.counters);
-                    ws.counters = nullptr;
-                    return fail_hip(e, "hipMalloc(counters)");
-                }
-                ws.n_counters = grow;
-            }
-            a.counters = ws.counters;
-        }
+        int rc = fused ? workspace_fused(ws, a, slots, stream) : workspace_plain(ws, a, slots, stream);
+        if (rc != SW_OK) return rc;
     }
 
     const bool defer = in.defer_merge && !fused;
@@ -323,8 +358,7 @@ int run_step(const StepIn &in)
         ev_c = {rec.ev[2], rec.ev[3]};
     }
 
-    e = which == 3 ? sw_launch_partial_mfma2(a, stream, prof ? &ev_p : nullptr)
-      : which == 2 ? sw_launch_partial_mfma(a, stream, prof ? &ev_p : nullptr)
+    e = which == 2 ? sw_launch_decode_split(a, stream, prof ? &ev_p : nullptr)
                    : sw_launch_partial_valu(a, stream, prof ? &ev_p : nullptr);
     if (e == hipSuccess && !fused && !defer) e = sw_launch_combine(a, stream, prof ? &ev_c : nullptr);
     if (e == hipSuccess && defer) *in.defer_merge = a;
@@ -372,7 +406,7 @@ int sw_set_param(int key, int value)
         g_chunk = value;
         return SW_OK;
     case SW_PARAM_KERNEL:
-        if (value < 0 || value > 3) return fail(SW_ERR_PARAM, "kernel must be 0, 1, 2 or 3");
+        if (value < 0 || value > 2) return fail(SW_ERR_PARAM, "kernel must be 0, 1 or 2");
         g_kernel = value;
         return SW_OK;
     case SW_PARAM_COMBINE:
@@ -485,13 +519,34 @@ int sw_release(void)
     for (auto &kv : g_ws) {
         hipError_t e = hipSetDevice(kv.first.first);
         if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (e == hipSuccess && kv.second.base) e = hipFree(kv.second.base);
-        if (e == hipSuccess && kv.second.counters) e = hipFree(kv.second.counters);
+        if (e == hipSuccess && kv.second.plain) e = hipFree(kv.second.plain);
+        if (e == hipSuccess && kv.second.fused) e = hipFree(kv.second.fused);
+        for (void *old : kv.second.retired)
+            if (e == hipSuccess) e = hipFree(old);
         if (e != hipSuccess && rc == SW_OK) rc = fail_hip(e, "sw_release");
     }
     g_ws.clear();
     (void)hipSetDevice(cur);
     return rc;
+}
+
+int sw_device_status(int *gave_up)
+{
+    if (!gave_up) return fail(SW_ERR_NULL, "gave_up is NULL");
+    *gave_up = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail_hip(e, "sw_device_status");
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (auto &kv : g_ws) {
+        if (kv.first.first != dev || !kv.second.fused) continue;
+        unsigned word = 0;
+        e = hipMemcpy(&word, kv.second.fused, sizeof(word), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail_hip(e, "sw_device_status");
+        if (word) *gave_up = 1;
+    }
+    return SW_OK;
 }
 
 // sw_decode_attn and sw_decode_attn_append; k_new == v_new == NULL selects the former.

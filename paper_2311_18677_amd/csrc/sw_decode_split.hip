@@ -1,28 +1,37 @@
-// Partial decode attention on the matrix cores, deep-pipelined variant
+// Token-phase (decode) attention on the matrix cores, split over context length, one launch
 // (gfx950, wave64), head_dim 128, 16 query heads of a key/value head per workgroup
 // (larger groups, up to 64 heads, in head tiles of 16).
 //
-// Same contractions, operand layouts and softmax as the kernel in
-// sw_partial_mfma.hip (S^T = K Q^T and O^T = V^T P^T on
-// v_mfma_f32_16x16x32_f16, head = lane%16), for the token phase's read of the
-// whole cached context (paper sections 2.2 and 3.5).  The difference is how V
-// travels: here BOTH K and V tiles go global->LDS, so no registers are held
-// while data is in flight and all of a wave's loads are of one kind, which
-// lets the waits count exactly.  A wave then keeps the next tile's K and V
+// The step the paper's token machines run for every generated token (sections 2.2 and
+// 3.5): the newest token's query attends over the whole cached context, which is read
+// exactly once.  S^T = K Q^T and O^T = V^T P^T run on v_mfma_f32_16x16x32_f16 with the
+// group's heads on the 16-wide N axis (head = lane % 16), so the first product's output
+// layout is the second product's B-operand layout, P never moves between lanes and every
+// softmax scalar lives in the lane that owns the head.
+//
+// A workgroup handles one item: one chunk of one (request, key/value head), found from a
+// scan of the lengths (sw_worklist.h).  A request of L positions is cut into
+// nc = ceil(L / chunk) items of (nearly) equal numbers of 32-position tiles.  K and V tiles
+// go global->LDS directly (no registers held while data is in flight, all of a wave's
+// loads of one kind, so the waits count exactly); a wave keeps the next tile's K and V
 // requests in flight while it computes the current tile:
 //
 //   wait K(i) | QK(i) from LDS | request K(i+1) | softmax(i) |
 //   wait V(i) | V(i) LDS->registers | request V(i+1) | transpose, PV(i)
 //
-// Append variant (the newest token's rows join the cache in the same pass,
-// paper section 2.2): the one wave whose tile holds the new position overwrites
-// that row of its staged K and V tiles with the new rows (brought into LDS once
-// per workgroup) and stores them to the cache in global memory; no other wave
-// or workgroup reads that position.
+// The item's result is merged with the request's other items in the same launch
+// (sw_fused.h), or -- FUSED = false -- left in the workspace for a merge kernel.
 //
-// Each wave owns 16 KB of LDS (K tile + V tile), so two 4-wave workgroups fit a
-// compute unit; with chunks of several tiles per wave the memory pipeline stays
-// busy through compute and epilogue phases.
+// Append variant (the newest token's rows join the cache in the same pass): the one wave
+// whose tile holds the new position overwrites that row of its staged K and V tiles with
+// the new rows (brought into LDS once per workgroup) and stores them to the cache in
+// global memory; no other wave or workgroup reads that position.
+//
+// Each wave owns 16 KB of LDS (K tile + V tile), so two 4-wave workgroups fit a compute unit.
+//
+// The kernel's leading arguments repeat what the length scan needs: they arrive in
+// registers with the wave (kernel-argument preload), so the lengths are requested before
+// the rest of the arguments has been fetched.
 #include "sw_internal.h"
 #include "sw_worklist.h"
 #include "sw_fused.h"
@@ -73,8 +82,16 @@ union Frag {
 
 template <int WAVES, int PER, bool FUSED, bool PAGED>
 __global__ __launch_bounds__(64 * WAVES, 2)
-void sw_partial_mfma2_kernel(SwArgs a)
+void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int chunk_shift, int n_kvh, SwArgs a_rest)
 {
+    SwArgs a = a_rest;
+    a.seq_lens = seq_lens;
+    a.n_req = n_req;
+    a.max_len = max_len;
+    a.chunk_shift = chunk_shift;
+    a.chunk = 1 << chunk_shift;
+    a.n_kvh = n_kvh;
+
     __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * kWaveLds];
     // Q rows, then (append variant) the new K row and the new V row.  One array: the
     // compiler sees no ordinary store into the new rows' part -- they arrive by
@@ -84,7 +101,9 @@ void sw_partial_mfma2_kernel(SwArgs a)
     __shared__ float sm_l[WAVES][16];
     __shared__ int sm_flag;
 
-    if (FUSED && blockIdx.x < (unsigned)a.n_req) sw_fused_zero_rows<kD>(a, (int)blockIdx.x);
+    // -- phase: workgroup started
+    // first of all the lengths: the scan needs nothing but the leading arguments
+    const SwScan<PER> scan = sw_scan_lens<PER>(a);
 
     // A group of more than 16 query heads is served in head tiles of 16, one workgroup per
     // tile and chunk.  Consecutive workgroups go to different XCDs (eight L2s), so the tiles
@@ -104,11 +123,28 @@ void sw_partial_mfma2_kernel(SwArgs a)
     const int h0 = 16 * ht;
     const int gn = min(16, a.group - h0);
 
-    const SwWork w = sw_find_work<PER>(a, item);
+    // Rows of requests with no cached position get +0; no item exists for them, so
+    // workgroup b < n_req looks after request b.
+    if (FUSED && blockIdx.x < (unsigned)a.n_req && sw_scanned_len<PER>(a, scan, (int)blockIdx.x) == 0)
+        sw_zero_rows<kD>(a, (int)blockIdx.x);
+    const SwWork w = sw_lookup<PER>(a, scan, item);
+    // -- phase: item known
     if (!w.valid) return;
     const int r = w.r, g = w.g, c = w.c;
-    const int t_begin = c << a.chunk_shift;
-    const int t_end = min(w.L, t_begin + a.chunk);
+    // the request's tiles of 32 positions, dealt evenly to its nc items
+    const unsigned n_all = (unsigned)(w.L + kTile - 1) / kTile;
+    const unsigned nc = (unsigned)(w.L + a.chunk - 1) >> a.chunk_shift;
+    const int t_begin = (int)((unsigned)c * n_all / nc) * kTile;
+    const int t_end = min(w.L, (int)(((unsigned)c + 1u) * n_all / nc) * kTile);
+    const bool alone = FUSED && nc == 1;            // the whole request: finished here, no merge
+    const long long unit = ((long long)r * a.n_kvh + g) * n_ht + ht;
+    SwFused fz;
+    if (FUSED) {
+        sw_fused_begin(a, fz, unit);
+        fz.nc = (int)nc;
+        fz.c = c;
+        fz.merger = false;
+    }
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
@@ -140,6 +176,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
         __builtin_amdgcn_global_load_lds(src, sm_new, 16, 0, 0);
     }
 
+    unsigned ticket = 0;                               // lane 0 of wave 0: the workgroup's ticket
     float m = kNegBig, l = 0.f;                        // m in raw score units
     const float lazy_raw = kLazyBits / a.scale_log2e;  // the raise threshold in raw score units
     float4_t o[8];
@@ -236,6 +273,10 @@ void sw_partial_mfma2_kernel(SwArgs a)
         // ---- S^T = K Q^T : two 16-token blocks, four 32-dim steps.
         // Outstanding, oldest first: K(t0) x8, V(t0) x8.
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        // -- phase: K tile landed
+        // Single launch: the workgroup takes its ticket while wave 0's last tile is under way,
+        // so the answer is there when the epilogue needs it.
+        if (FUSED && !MORE && wave == 0 && !alone && lane == 0) ticket = sw_fused_ticket(a, unit);
         // the new position lies in the chunk's last tile, which is some wave's last tile
         const bool has_new = !MORE && new_pos >= t0 && new_pos < t0 + kTile;     // wave-uniform
         if (has_new && gq == 0) {
@@ -395,6 +436,7 @@ void sw_partial_mfma2_kernel(SwArgs a)
         process_tile(t_begin + ti * kTile, 0, std::false_type{});
     }
 
+    // -- phase: tiles done
     // ---- the lane groups summed disjoint tokens into l
     l = quad_rows_sum(l);
 
@@ -414,9 +456,9 @@ void sw_partial_mfma2_kernel(SwArgs a)
             sm_l[wave][n16] = l;
         }
     }
+    if (FUSED && !alone && threadIdx.x == 0) sm_flag = sw_fused_is_merger(a, unit, ticket, (int)nc) ? 1 : 0;
     __syncthreads();
-    // single-launch variant: a request of one chunk is finished here
-    const bool alone = FUSED && w.L <= a.chunk;
+    if (FUSED && !alone) fz.merger = sm_flag != 0;
     for (int idx = threadIdx.x; idx < gn * (kD / 4); idx += 64 * WAVES) {
         const int hh = idx >> 5;
         const int j4 = idx & 31;
@@ -438,25 +480,27 @@ void sw_partial_mfma2_kernel(SwArgs a)
             sw_store_final4<kD>(a, sw_q_row(a, r) * a.n_qh + g * a.group + h0 + hh, j4, num, den);
             continue;
         }
+        if (FUSED) {
+            sw_fused_finish<kD>(a, fz, r, g, h0 + hh, j4, num, den, mx);
+            continue;
+        }
         const long long slot = sw_ws_slot(a, r, g, c, h0 + hh);
-        sw_store_partial4(a.ws_o + slot * kD + 4 * j4, num, FUSED);
-        if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, FUSED);
+        *reinterpret_cast<float4_t *>(a.ws_o + slot * kD + 4 * j4) = num;
+        if (j4 == 0) *reinterpret_cast<float2_t *>(a.ws_ml + slot * 2) = float2_t{mx, den};
     }
-    if (FUSED && !alone)
-        sw_fused_tail<kD>(a, r, g, h0, gn, (w.L + a.chunk - 1) >> a.chunk_shift,
-                          a.counters + ((long long)(r * a.n_kvh + g) * n_ht + ht), &sm_flag);
+    // -- phase: results stored
 }
 
 }  // namespace
 
-bool sw_partial_mfma2_supported(const SwArgs &a)
+bool sw_decode_split_supported(const SwArgs &a)
 {
     return a.head_dim == kD && a.group <= 64 && (a.waves == 4 || a.waves == 8);
 }
 
-hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
+hipError_t sw_launch_decode_split(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev)
 {
-    if (!sw_partial_mfma2_supported(a)) return hipErrorNotSupported;
+    if (!sw_decode_split_supported(a)) return hipErrorNotSupported;
     long long blocks = (long long)a.n_req * a.n_kvh * a.n_chunks;
     const int n_ht = (a.group + 15) / 16;
     if (n_ht > 1) blocks = (blocks + 7) / 8 * 8 * n_ht;      // see the kernel's numbering of head tiles
@@ -466,9 +510,11 @@ hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const Sw
     const bool paged = a.block_table != nullptr;
 #define SW_MFMA2_CASE(W, P, B)                                                                           \
     if (a.waves == W && per == P && paged == B)                                                                   \
-        return a.counters                                                                             \
-            ? sw_launch(sw_partial_mfma2_kernel<W, P, true, B>, grid, dim3(64 * W), 0, stream, ev, a)     \
-            : sw_launch(sw_partial_mfma2_kernel<W, P, false, B>, grid, dim3(64 * W), 0, stream, ev, a);
+        return a.units                                                                                \
+            ? sw_launch(sw_decode_split_kernel<W, P, true, B>, grid, dim3(64 * W), 0, stream, ev,        \
+                        a.seq_lens, a.n_req, a.max_len, a.chunk_shift, a.n_kvh, a)                        \
+            : sw_launch(sw_decode_split_kernel<W, P, false, B>, grid, dim3(64 * W), 0, stream, ev,       \
+                        a.seq_lens, a.n_req, a.max_len, a.chunk_shift, a.n_kvh, a);
 #define SW_MFMA2_WAVES(W)                                                                             \
     SW_MFMA2_CASE(W, 1, false) SW_MFMA2_CASE(W, 4, false) SW_MFMA2_CASE(W, 16, false) SW_MFMA2_CASE(W, 0, false) \
     SW_MFMA2_CASE(W, 1, true) SW_MFMA2_CASE(W, 4, true) SW_MFMA2_CASE(W, 16, true) SW_MFMA2_CASE(W, 0, true)

@@ -1,66 +1,107 @@
-// Single-launch variant of the split over context length: the workgroup that
-// finishes a (request, key/value head, head tile) last merges that unit's
-// chunks itself, so no second kernel is needed.
+// Single-launch form of the split over context length: one of the workgroups of a
+// (request, key/value head, head tile) unit merges the unit's chunks itself, so the
+// token-phase step (paper sections 2.2 and 3.5) is one kernel, not two.
 //
-// The partial results cross workgroups on different XCDs, whose L2 caches are
-// not coherent with each other.  Device-wide release/acquire fences would make
-// them coherent by writing back and invalidating a whole L2 per workgroup, which
-// costs far more than the kernel itself; instead every access to a shared
-// location is a relaxed device-scope atomic (compiled to a load/store that is
-// served at the device's coherence point, no cache maintenance), and ordering
-// comes from completion: a workgroup waits until its partial stores have been
-// acknowledged (s_waitcnt vmcnt(0), then the workgroup barrier) before one of
-// its threads takes a ticket from the unit's counter, and the holder of the last
-// ticket (nc - 1) reads the partial results only after it has seen its ticket.
-// It merges chunks 0 .. nc-1 in index order (a fixed order, so repeated calls
-// give the same bits), writes the binary16 output rows and puts the counter back to zero for the next call
-// on the stream.  Counters start at zero (cleared when the library allocates
-// them) and every launch leaves them zero.
+// The chunks' partial results cross workgroups that sit on different XCDs, whose L2
+// caches are not coherent with each other.  No fence and no store acknowledgement is
+// waited for.  Instead the data validates itself: a partial result travels as 16-byte
+// pieces, each holding two floats and a 64-bit tag, written with one device-coherent
+// 16-byte store and read back with device-coherent 16-byte loads (both served at the
+// memory side, past the L2s).  A piece is taken only when its tag is the one this call
+// of this unit uses; anything else is a piece of an earlier call whose replacement has
+// not landed yet, and the reader asks again.
+//
+//   tag = geometry id (20 bits) | the unit's epoch + 1 (44 bits)
+//
+// The epoch is a per-unit counter in device memory that the merging workgroup advances
+// at the end of every call, so tags written by one unit under one geometry grow from call
+// to call (a HIP graph replays the same kernel arguments, hence the counter lives on the
+// device); the geometry id changes whenever a call lays the workspace out differently
+// from the call before it, so pieces left by another shape never carry a live tag.
+// The workspace starts zeroed and no tag is zero.
+//
+// Who merges: every workgroup of a unit with more than one chunk takes a ticket from the
+// unit's counter when its last tile is under way; the holder of the last ticket merges.
+// All other workgroups of the unit have then taken theirs, i.e. are inside their last
+// tile or past it: they store their pieces without waiting for anything, so the merging
+// workgroup waits for stores that are already on their way (the wait is bounded anyway,
+// and a device-side flag records a give-up).  It folds chunks 0 .. nc-1 in index order
+// with a running maximum -- its own chunk from registers -- so the bits of a row do not
+// depend on which workgroup merged, and writes the binary16 rows.
 #pragma once
 #include "sw_internal.h"
 
 typedef float sw_float4_t __attribute__((ext_vector_type(4)));
 typedef float sw_float2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 sw_half4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int sw_uint4_t __attribute__((ext_vector_type(4)));
 
-// Device-coherent 8-byte accesses (p is 8-byte aligned).
-__device__ __forceinline__ void sw_coherent_store2(float *p, float x, float y)
+constexpr int kSwEpochBits = 44;
+constexpr int kSwFusedBatch = 4;              // chunks whose pieces a thread requests together
+constexpr int kSwSpinMax = 1 << 20;           // re-reads of a batch before the merge gives up
+
+// What a workgroup knows about its part in the single-launch merge.
+struct SwFused {
+    __amdgpu_buffer_rsrc_t ws;                // the tagged workspace as a raw buffer
+    unsigned tag_lo, tag_hi;                  // this call's tag of this unit
+    int  nc;                                  // chunks of the unit
+    int  c;                                   // this workgroup's chunk
+    bool merger;                              // this workgroup folds the chunks
+};
+
+// Pieces of one (chunk, head) slot: D/2 pieces of two output dims, then (m, l).
+template <int D>
+__device__ __forceinline__ unsigned sw_piece_offset(const SwArgs &a, int r, int g, int c, int hh, int p)
 {
-    union { sw_float2_t f; unsigned long long u; } v;
-    v.f = sw_float2_t{x, y};
-    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), v.u, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
+    return (unsigned)((sw_ws_slot(a, r, g, c, hh) * (D / 2 + 1) + p) * 16);
 }
 
-__device__ __forceinline__ sw_float2_t sw_coherent_load2(const float *p)
+// Device-coherent 16-byte accesses (cache policy sc1: served past the L2s).
+__device__ __forceinline__ void sw_piece_store(const SwFused &f, unsigned off, float x, float y)
 {
-    union { sw_float2_t f; unsigned long long u; } v;
-    v.u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
-                            __HIP_MEMORY_SCOPE_AGENT);
-    return v.f;
+    __builtin_amdgcn_raw_buffer_store_b128(
+        sw_uint4_t{__float_as_uint(x), __float_as_uint(y), f.tag_lo, f.tag_hi}, f.ws, off, 0, 16);
 }
 
-// Store four consecutive partial-result floats (p is 16-byte aligned); coherent
-// across the device when the single-launch variant will read them back.
-__device__ __forceinline__ void sw_store_partial4(float *p, sw_float4_t x, bool coherent)
+__device__ __forceinline__ sw_uint4_t sw_piece_load(const SwFused &f, unsigned off)
 {
-    if (coherent) {
-        sw_coherent_store2(p, x[0], x[1]);
-        sw_coherent_store2(p + 2, x[2], x[3]);
-    } else {
-        *reinterpret_cast<sw_float4_t *>(p) = x;
-    }
+    return __builtin_amdgcn_raw_buffer_load_b128(f.ws, off, 0, 16);
 }
 
-__device__ __forceinline__ void sw_store_partial2(float *p, float x, float y, bool coherent)
+// The tag a unit uses in this call, from its epoch (read through the constant address
+// space: the word was last written before this kernel started).
+__device__ __forceinline__ void sw_fused_begin(const SwArgs &a, SwFused &f, long long unit)
 {
-    if (coherent) sw_coherent_store2(p, x, y);
-    else *reinterpret_cast<sw_float2_t *>(p) = sw_float2_t{x, y};
+    typedef const __attribute__((address_space(4))) unsigned long long *const_u64_t;
+    const unsigned long long epoch = *(const_u64_t)(&a.units[unit].epoch);
+    const unsigned long long tag = ((unsigned long long)a.geometry << kSwEpochBits) |
+                                   ((epoch + 1) & ((1ull << kSwEpochBits) - 1));
+    f.tag_lo = (unsigned)tag;
+    f.tag_hi = (unsigned)(tag >> 32);
+    // the epoch has been read by here, i.e. before this workgroup can take its ticket: the
+    // merging workgroup advances it once every ticket of the unit is taken
+    asm volatile("" : "+s"(f.tag_lo), "+s"(f.tag_hi));
+    f.ws = __builtin_amdgcn_make_buffer_rsrc(a.ws_tag, 0, (int)a.ws_tag_bytes, 0x00020000);
 }
 
-// A request with a single chunk needs no merge at all: in the single-launch variant its
-// workgroup normalises and writes the output rows itself (the same arithmetic the merge
-// would do with one chunk, so the same bits), and takes no ticket.
+// One lane takes the unit's ticket (the answer may be left in flight) ...
+__device__ __forceinline__ unsigned sw_fused_ticket(const SwArgs &a, long long unit)
+{
+    return __hip_atomic_fetch_add(&a.units[unit].ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ... and the same lane reads it later: true for the workgroup that merges, which also
+// leaves the counter at zero and the epoch advanced for the next call.  (Both are read
+// again only by the next kernel on the stream.)
+__device__ __forceinline__ bool sw_fused_is_merger(const SwArgs &a, long long unit, unsigned ticket, int nc)
+{
+    if (ticket != (unsigned)(nc - 1)) return false;
+    __hip_atomic_store(&a.units[unit].ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(&a.units[unit].epoch, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+// Binary16 output of four dims (round to nearest even).
 template <int D>
 __device__ __forceinline__ void sw_store_final4(const SwArgs &a, long long rh, int j4, sw_float4_t num, float den)
 {
@@ -70,80 +111,74 @@ __device__ __forceinline__ void sw_store_final4(const SwArgs &a, long long rh, i
     *reinterpret_cast<sw_half4_t *>(reinterpret_cast<_Float16 *>(a.out) + rh * D + 4 * j4) = res;
 }
 
-// Called by every thread of the workgroup after its partial-result stores.
-//   r, g, hh_first, n_heads : heads hh_first .. hh_first + n_heads - 1 of the group of
-//                         key/value head g of request r
-//   nc                  : number of chunks of request r (>= 1)
-//   counter             : this unit's ticket counter
-//   sm_flag             : one int of LDS
+// Called by the thread that holds dims 4*j4 .. 4*j4+3 of head hh (within the group) of
+// this workgroup's chunk: num = sum_t 2^(s_t - mx) V_t over the chunk, den the sum of the
+// weights, mx the chunk's maximum (base-2 exponent units).
+//   not the merging workgroup: stores its pieces and is done;
+//   the merging workgroup: folds the unit's chunks and stores the output row's four dims.
 template <int D>
-__device__ __forceinline__ void sw_fused_tail(const SwArgs &a, int r, int g, int hh_first, int n_heads,
-                                              int nc, unsigned *counter, int *sm_flag)
+__device__ __forceinline__ void sw_fused_finish(const SwArgs &a, const SwFused &f, int r, int g, int hh, int j4,
+                                                sw_float4_t num, float den, float mx)
 {
-    __builtin_amdgcn_s_waitcnt(0);         // this thread's partial stores are acknowledged
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
-        const int last = ticket == (unsigned)(nc - 1);
-        if (last)   // everyone has arrived; ready for the next call
-            __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *sm_flag = last;
+    constexpr int P = D / 2;                  // index of the (m, l) piece
+    if (!f.merger) {
+        const unsigned off = sw_piece_offset<D>(a, r, g, f.c, hh, 2 * j4);
+        sw_piece_store(f, off, num[0], num[1]);
+        sw_piece_store(f, off + 16, num[2], num[3]);
+        if (j4 == 0) sw_piece_store(f, sw_piece_offset<D>(a, r, g, f.c, hh, P), mx, den);
+        return;
     }
-    __syncthreads();
-    if (!*sm_flag) return;
-
-    constexpr int V4 = D / 4;
-    constexpr int kBatch = 8;
-    for (int idx = threadIdx.x; idx < n_heads * V4; idx += blockDim.x) {
-        const int hh = idx / V4;
-        const int j4 = idx - hh * V4;
-        const long long rh = sw_q_row(a, r) * a.n_qh + g * a.group + hh_first + hh;
-        const long long slot0 = sw_ws_slot(a, r, g, 0, hh_first + hh);
-        const long long cs = a.group;                     // slots between consecutive chunks
-        const float *ml = a.ws_ml + slot0 * 2;
-        const float *po = a.ws_o + slot0 * D + 4 * j4;
-        // running-maximum merge, kBatch chunks' loads in flight at a time
-        float m = -1.0e30f, den = 0.f;
-        sw_float4_t num = sw_float4_t{0.f, 0.f, 0.f, 0.f};
-        for (int c0 = 0; c0 < nc; c0 += kBatch) {
-            sw_float2_t mlc[kBatch], x01[kBatch], x23[kBatch];
+    float m_run = -1.0e30f, d_run = 0.f;
+    sw_float4_t n_run = sw_float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < f.nc; c0 += kSwFusedBatch) {
+        sw_uint4_t lo[kSwFusedBatch], hi[kSwFusedBatch], ml[kSwFusedBatch];
+        bool ok = false;
+        for (int spin = 0; spin < kSwSpinMax && !ok; ++spin) {
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int c = min(c0 + u, nc - 1);       // clamped: in bounds, masked below
-                mlc[u] = sw_coherent_load2(ml + 2 * c * cs);
-                x01[u] = sw_coherent_load2(po + c * cs * D);
-                x23[u] = sw_coherent_load2(po + c * cs * D + 2);
+            for (int u = 0; u < kSwFusedBatch; ++u) {
+                const int c = min(c0 + u, f.nc - 1);     // clamped: in bounds, unused past nc
+                const unsigned off = sw_piece_offset<D>(a, r, g, c, hh, 2 * j4);
+                lo[u] = sw_piece_load(f, off);
+                hi[u] = sw_piece_load(f, off + 16);
+                ml[u] = sw_piece_load(f, sw_piece_offset<D>(a, r, g, c, hh, P));
             }
+            asm volatile("" ::: "memory");               // every round reads memory again
+            ok = true;
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                if (c0 + u < nc) {
-                    const float m_new = fmaxf(m, mlc[u][0]);
-                    const float f_old = __builtin_amdgcn_exp2f(m - m_new);
-                    const float f_new = __builtin_amdgcn_exp2f(mlc[u][0] - m_new);
-                    num[0] = fmaf(f_new, x01[u][0], num[0] * f_old);
-                    num[1] = fmaf(f_new, x01[u][1], num[1] * f_old);
-                    num[2] = fmaf(f_new, x23[u][0], num[2] * f_old);
-                    num[3] = fmaf(f_new, x23[u][1], num[3] * f_old);
-                    den = fmaf(f_new, mlc[u][1], den * f_old);
-                    m = m_new;
-                }
+            for (int u = 0; u < kSwFusedBatch; ++u) {
+                if (c0 + u >= f.nc || c0 + u == f.c) continue;
+                ok = ok && lo[u][2] == f.tag_lo && lo[u][3] == f.tag_hi &&
+                           hi[u][2] == f.tag_lo && hi[u][3] == f.tag_hi &&
+                           ml[u][2] == f.tag_lo && ml[u][3] == f.tag_hi;
             }
         }
-        sw_half4_t res;
+        if (!ok) *a.dev_err = 1u;                        // gave up on a piece: the row is wrong, the kernel ends
 #pragma unroll
-        for (int t = 0; t < 4; ++t) res[t] = (_Float16)(num[t] / den);   // round to nearest even
-        *reinterpret_cast<sw_half4_t *>(reinterpret_cast<_Float16 *>(a.out) + rh * D + 4 * j4) = res;
+        for (int u = 0; u < kSwFusedBatch; ++u) {
+            if (c0 + u >= f.nc) continue;
+            const bool own = c0 + u == f.c;
+            const float mc = own ? mx : __uint_as_float(ml[u][0]);
+            const float lc = own ? den : __uint_as_float(ml[u][1]);
+            const sw_float4_t x = own ? num
+                                      : sw_float4_t{__uint_as_float(lo[u][0]), __uint_as_float(lo[u][1]),
+                                                    __uint_as_float(hi[u][0]), __uint_as_float(hi[u][1])};
+            const float m_new = fmaxf(m_run, mc);
+            const float f_old = __builtin_amdgcn_exp2f(m_run - m_new);
+            const float f_new = __builtin_amdgcn_exp2f(mc - m_new);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) n_run[t] = fmaf(f_new, x[t], n_run[t] * f_old);
+            d_run = fmaf(f_new, lc, d_run * f_old);
+            m_run = m_new;
+        }
     }
+    sw_store_final4<D>(a, sw_q_row(a, r) * a.n_qh + g * a.group + hh, j4, n_run, d_run);
 }
 
-// Rows of requests with no cached position get +0; no chunk workgroup exists for
-// them, so workgroup b < n_req looks after request b.  Called by every thread
-// of such a workgroup before it looks for its own work item.
+// A row of +0 for every query head of a request with no cached position (no item exists
+// for such a request).  Called by every thread of the workgroup that looks after it.
 template <int D>
-__device__ __forceinline__ void sw_fused_zero_rows(const SwArgs &a, int req)
+__device__ __forceinline__ void sw_zero_rows(const SwArgs &a, int req)
 {
-    if (sw_request_len_flagged(a, req) != 0) return;      // has positions, or takes no part in the call
     sw_half4_t z = sw_half4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
     _Float16 *row = reinterpret_cast<_Float16 *>(a.out) + sw_q_row(a, req) * a.n_qh * D;
     for (int idx = threadIdx.x; idx < a.n_qh * (D / 4); idx += blockDim.x)

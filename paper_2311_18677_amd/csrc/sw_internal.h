@@ -5,6 +5,15 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+// State of one (request, key/value head, head tile) unit of the single-launch variant,
+// kept between calls: the ticket counter is zero outside a launch, the epoch counts the
+// calls in which the unit merged.
+struct SwUnitState {
+    unsigned           ticket;
+    unsigned           reserved;
+    unsigned long long epoch;
+};
+
 // Everything a kernel needs, passed by value.
 //
 // Split over context length: positions [0, L) of a request are cut into
@@ -26,7 +35,14 @@ struct SwArgs {
     uint16_t       *out;
     float          *ws_o;
     float          *ws_ml;
-    unsigned       *counters;           // single-launch variant: one ticket counter per unit, else null
+    // single-launch variant (else units is null): per-unit ticket and epoch, the workspace of
+    // tagged 16-byte pieces (see sw_fused.h), the id of the way this call lays it out, and a
+    // word the device sets if a merge gave up waiting for a piece
+    SwUnitState    *units;
+    void           *ws_tag;
+    unsigned        ws_tag_bytes;
+    unsigned        geometry;
+    unsigned       *dev_err;
     const uint16_t *k_new;              // append variant: the newest token's K rows [n_req][n_kvh][head_dim], else null
     const uint16_t *v_new;              //                 and V rows
     const int32_t  *block_table;        // block-table variant: [n_req][max_blocks] pool block ids, else null
@@ -103,9 +119,9 @@ constexpr int kSwAppendedBit = 30;
 constexpr int kSwLenMask     = (1 << kSwAppendedBit) - 1;
 constexpr int kSwSkip        = (int)0x80000000u;
 
-__device__ inline int sw_request_len_flagged(const SwArgs &a, int r)
+// (sw_flag_len: the same from a seq_lens[r] value that has already been read)
+__device__ inline int sw_flag_len(const SwArgs &a, int r, int L)
 {
-    int L = a.seq_lens[r];
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
     if (a.q_lens) {
         const int cap = L < a.max_q ? L : a.max_q;
@@ -115,6 +131,11 @@ __device__ inline int sw_request_len_flagged(const SwArgs &a, int r)
     }
     if (a.k_new && L < a.max_len) L += 1 + (1 << kSwAppendedBit);
     return L;
+}
+
+__device__ inline int sw_request_len_flagged(const SwArgs &a, int r)
+{
+    return sw_flag_len(a, r, a.seq_lens[r]);
 }
 
 // Row of q and out that belongs to request r (valid for requests that take part).
@@ -142,12 +163,9 @@ struct SwLaunchEvents {
 
 // Vector-ALU partial kernel: any group size (looped in tiles of up to 8 heads).
 hipError_t sw_launch_partial_valu(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
-// Matrix-core partial kernel: group sizes up to 16, head_dim 64 or 128.
-bool       sw_partial_mfma_supported(const SwArgs &a);
-hipError_t sw_launch_partial_mfma(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
-// Matrix-core partial kernel with both K and V staged through LDS (4 or 8 waves).
-bool       sw_partial_mfma2_supported(const SwArgs &a);
-hipError_t sw_launch_partial_mfma2(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
+// Matrix-core kernel, K and V staged through LDS (head_dim 128, groups up to 64, 4 or 8 waves).
+bool       sw_decode_split_supported(const SwArgs &a);
+hipError_t sw_launch_decode_split(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 // Merge of the chunks' partial results, normalisation and rounding to binary16.
 hipError_t sw_launch_combine(const SwArgs &a, hipStream_t stream, const SwLaunchEvents *ev);
 // Bound on the (request, block of q_block query tokens) items of a prompt-phase call, which

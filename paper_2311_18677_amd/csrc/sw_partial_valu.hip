@@ -57,11 +57,13 @@ void sw_partial_valu_kernel(SwArgs a)
     constexpr int U   = 16 / RPW;     // loads per 16-token tile
     constexpr int TPW = 16;           // tokens per wave per iteration
 
-    const bool fused = a.counters != nullptr;
-    if (fused && blockIdx.y == 0 && blockIdx.x < (unsigned)a.n_req)
-        sw_fused_zero_rows<D>(a, (int)blockIdx.x);
+    const bool fused = a.units != nullptr;
+    const SwScan<PER> scan = sw_scan_lens<PER>(a);
+    if (fused && blockIdx.y == 0 && blockIdx.x < (unsigned)a.n_req &&
+        sw_scanned_len<PER>(a, scan, (int)blockIdx.x) == 0)
+        sw_zero_rows<D>(a, (int)blockIdx.x);
 
-    const SwWork w = sw_find_work<PER>(a, blockIdx.x);
+    const SwWork w = sw_lookup<PER>(a, scan, blockIdx.x);
     if (!w.valid) return;
     const int r = w.r, g = w.g, c = w.c;
     const int ht = blockIdx.y;
@@ -213,9 +215,22 @@ void sw_partial_valu_kernel(SwArgs a)
             }
         }
     }
+    // single-launch variant: a request of one chunk is finished here; otherwise one thread
+    // takes the unit's ticket (see sw_fused.h) and the barrier hands the answer round
+    const int nc = (w.L + a.chunk - 1) >> a.chunk_shift;
+    const bool alone = fused && nc == 1;
+    const long long unit = ((long long)r * a.n_kvh + g) * gridDim.y + ht;
+    SwFused fz;
+    if (fused) {
+        sw_fused_begin(a, fz, unit);
+        fz.nc = nc;
+        fz.c = c;
+        fz.merger = false;
+        if (!alone && threadIdx.x == 0)
+            sm_flag = sw_fused_is_merger(a, unit, sw_fused_ticket(a, unit), nc) ? 1 : 0;
+    }
     __syncthreads();
-    // single-launch variant: a request of one chunk is finished here
-    const bool alone = fused && w.L <= a.chunk;
+    if (fused && !alone) fz.merger = sm_flag != 0;
     for (int idx = threadIdx.x; idx < n_valid * (D / 4); idx += 64 * kWaves) {
         const int hh = idx / (D / 4);
         const int j4 = idx - hh * (D / 4);
@@ -235,14 +250,13 @@ void sw_partial_valu_kernel(SwArgs a)
             sw_store_final4<D>(a, sw_q_row(a, r) * a.n_qh + h0 + hh, j4, num, den);
             continue;
         }
+        if (fused) {
+            sw_fused_finish<D>(a, fz, r, g, ht * GT + hh, j4, num, den, mx);
+            continue;
+        }
         const long long slot = sw_ws_slot(a, r, g, c, ht * GT + hh);
-        sw_store_partial4(a.ws_o + slot * D + 4 * j4, num, fused);
-        if (j4 == 0) sw_store_partial2(a.ws_ml + slot * 2, mx, den, fused);
-    }
-    if (fused && !alone) {
-        const int tiles = (a.group + GT - 1) / GT;
-        sw_fused_tail<D>(a, r, g, ht * GT, n_valid, (w.L + a.chunk - 1) >> a.chunk_shift,
-                         a.counters + ((long long)(r * a.n_kvh + g) * tiles + ht), &sm_flag);
+        *reinterpret_cast<sw_float4_t *>(a.ws_o + slot * D + 4 * j4) = num;
+        if (j4 == 0) *reinterpret_cast<sw_float2_t *>(a.ws_ml + slot * 2) = sw_float2_t{mx, den};
     }
 }
 

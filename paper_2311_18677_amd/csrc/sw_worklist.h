@@ -69,12 +69,18 @@ __device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
         s.total = (unsigned)a.n_req * (unsigned)a.n_kvh * (unsigned)a.n_chunks;
     } else {
         const int lane = threadIdx.x & 63;
+        // all of the lane's lengths are requested before anything else is looked at
+        int raw[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int r = lane * PER + j;
+            raw[j] = r < a.n_req ? a.seq_lens[r] : 0;
+        }
         s.mine = 0;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             const int r = lane * PER + j;
-            s.len[j] = 0;
-            if (r < a.n_req) s.len[j] = sw_request_len_flagged(a, r);
+            s.len[j] = r < a.n_req ? sw_flag_len(a, r, raw[j]) : 0;
             s.cnt[j] = ((s.len[j] & kSwLenMask) + a.chunk - 1) >> a.chunk_shift;
             s.mine += s.cnt[j];
         }
@@ -129,6 +135,22 @@ __device__ __forceinline__ SwWork sw_lookup(const SwArgs &a, const SwScan<PER> &
             before += cj;
         }
         return w;
+    }
+}
+
+// Flagged length of request req (see sw_request_len_flagged) from a finished scan; all 64
+// lanes of the wave must call it.  The direct mapping keeps no lengths and reads memory.
+template <int PER>
+__device__ __forceinline__ int sw_scanned_len(const SwArgs &a, const SwScan<PER> &s, int req)
+{
+    if constexpr (PER == 0) {
+        return sw_request_len_flagged(a, req);
+    } else {
+        const int owner = req / PER, j = req - owner * PER;
+        int v = s.len[0];
+#pragma unroll
+        for (int k = 1; k < PER; ++k) v = j == k ? s.len[k] : v;
+        return __builtin_amdgcn_readlane(v, owner);
     }
 }
 

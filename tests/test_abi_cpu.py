@@ -96,7 +96,7 @@ def test_params_roundtrip_and_validation():
     assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 100, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 32, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(sw.SW_PARAM_CHUNK, 192, check=False) == sw.SW_ERR_PARAM
-    assert sw.sw_set_param(sw.SW_PARAM_KERNEL, 4, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(sw.SW_PARAM_KERNEL, 3, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_set_param(sw.SW_PARAM_COMBINE, 3, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_get_param(sw.SW_PARAM_COMBINE) == 0
     assert sw.sw_set_param(sw.SW_PARAM_WAVES, 5, check=False) == sw.SW_ERR_PARAM

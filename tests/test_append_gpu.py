@@ -70,8 +70,8 @@ EDGE_LENS = [0, 1, -3, 3, 30, 31, 32, 33, 63, 64, 127, 128, 255, 256, 257, 400, 
 
 SHAPES = [  # n_qh, n_kvh, d, kernel (0 = default), combine
     (8, 1, 128, 0, 0), (8, 1, 128, 1, 0), (14, 14, 128, 0, 0), (8, 8, 64, 0, 0), (24, 1, 128, 0, 0),
-    (16, 2, 128, 3, 0), (6, 2, 64, 1, 0), (8, 1, 128, 3, 2), (8, 2, 128, 1, 2),
-    (40, 1, 128, 3, 0), (66, 2, 128, 3, 2),      # groups above 16: every head tile patches, the first stores
+    (16, 2, 128, 2, 0), (6, 2, 64, 1, 0), (8, 1, 128, 2, 2), (8, 2, 128, 1, 2),
+    (40, 1, 128, 2, 0), (66, 2, 128, 2, 2), (8, 1, 128, 2, 1),      # groups above 16: every head tile patches, the first stores
 ]
 
 
@@ -131,7 +131,7 @@ def test_append_full_size_configs(name):
 
 @pytest.mark.parametrize("block_size", [4, 16, 256])
 @pytest.mark.parametrize("n_qh,n_kvh,d,kernel", [(8, 1, 128, 0), (8, 1, 128, 1), (14, 14, 128, 0),
-                                                  (8, 8, 64, 0), (16, 2, 128, 3), (40, 1, 128, 3)])
+                                                  (8, 8, 64, 0), (16, 2, 128, 2), (40, 1, 128, 2)])
 def test_paged_append_matches_oracle_pool_and_dense_bits(n_qh, n_kvh, d, kernel, block_size):
     import torch
     cfg = wl.custom_config("pap%d_%d_%d" % (n_qh, n_kvh, d), len(EDGE_LENS), n_qh, n_kvh, d, 768)

@@ -48,8 +48,8 @@ def paged_ref(batch, bufs):
 
 
 SHAPES = [  # n_qh, n_kvh, d, kernel (0 = default)
-    (8, 1, 128, 0), (8, 1, 128, 1), (14, 14, 128, 0), (8, 8, 64, 0), (24, 1, 128, 0), (16, 2, 128, 3),
-    (6, 2, 64, 1), (40, 2, 128, 3),
+    (8, 1, 128, 0), (8, 1, 128, 1), (14, 14, 128, 0), (8, 8, 64, 0), (24, 1, 128, 0), (16, 2, 128, 2),
+    (6, 2, 64, 1), (40, 2, 128, 2),
 ]
 
 

@@ -11,9 +11,8 @@ from helpers import assert_parity, oracle_on_packed
 pytestmark = pytest.mark.gpu
 
 # mode -> (SW_PARAM_KERNEL, SW_PARAM_COMBINE)
-MODES = {"default": (0, 0), "valu": (1, 1), "mfma": (2, 1), "mfma2": (3, 1),
-         "valu_fused": (1, 2), "mfma_fused": (2, 2), "mfma2_fused": (3, 2)}
-ALL_MODES = ["valu", "mfma", "mfma2", "valu_fused", "mfma_fused", "mfma2_fused"]
+MODES = {"default": (0, 0), "valu": (1, 1), "mfma": (2, 1), "valu_fused": (1, 2), "mfma_fused": (2, 2)}
+ALL_MODES = ["valu", "mfma", "valu_fused", "mfma_fused"]
 
 
 def set_mode(which):
@@ -185,7 +184,7 @@ def test_permutation_batch_independence_and_repeatability(which):
         assert np.array_equal(out_s.view(np.uint16)[0], out.view(np.uint16)[r])
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3])
+@pytest.mark.parametrize("kernel", [1, 2])
 def test_single_launch_variant_is_repeatable_and_agrees_with_two_kernels(kernel):
     lens = [700, 3, 256, 1023, 64, 511, 90, 1, 0, 129]
     cfg = wl.custom_config("fz", len(lens), 8, 1, 128, 1024)
@@ -245,7 +244,7 @@ def test_decode_call_in_a_replayed_graph(combine):
         assert np.array_equal(eager_out.cpu().numpy().view(np.uint16), want.view(np.uint16)), rep
 
 
-@pytest.mark.parametrize("which", ["valu", "mfma", "mfma2"])
+@pytest.mark.parametrize("which", ["valu", "mfma", "valu_fused", "mfma_fused"])
 @pytest.mark.parametrize("n_req", [65, 300, 1100])
 def test_many_requests_exercise_every_work_map(n_req, which):
     # 65 / 300 / 1100 requests select the 4-per-lane scan, the 16-per-lane scan and
@@ -264,7 +263,7 @@ def test_many_requests_exercise_every_work_map(n_req, which):
 
 
 @pytest.mark.parametrize("waves", [4, 8, 16])
-@pytest.mark.parametrize("kernel", [2, 3])
+@pytest.mark.parametrize("kernel", [2])
 def test_waves_per_workgroup(kernel, waves):
     lens = [1000, 37, 512, 513, 0, 256]
     cfg = wl.custom_config("w%d" % waves, len(lens), 8, 1, 128, 1024)
@@ -275,8 +274,8 @@ def test_waves_per_workgroup(kernel, waves):
     try:
         out, bufs = gpu_out(batch, pad_bits=0x7E00)
     except sw.SwError as e:
-        if e.code == sw.SW_ERR_UNSUPPORTED and kernel == 3 and waves == 16:
-            pytest.skip("the LDS-staged kernel runs 4 or 8 waves")
+        if e.code == sw.SW_ERR_UNSUPPORTED and waves == 16:
+            pytest.skip("the matrix-core kernel runs 4 or 8 waves")
         raise
     ref = oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"])
     assert_parity(out, ref, cfg.name)
