@@ -40,24 +40,25 @@ int fail_hip(hipError_t e, const char *what)
 
 // Library-owned device memory of one (device, stream).
 //   plain : partial results of the two-kernel form, (head_dim + 2) floats per slot.
-//   fused : single-launch form -- a 256-byte header (word 0: set by the device if a merge gave
-//           up), the per-unit states, then the tagged pieces (see sw_fused.h).  Both parts are
-//           allocated together and start zeroed together: an epoch that restarted from zero
-//           must never meet pieces tagged by its earlier life.
+//   fused : single-launch form, one block per workspace geometry -- (n_kvh, group, n_chunks,
+//           head_dim, kernel) decide where a slot lies and which unit owns it, and a piece must
+//           only ever be overwritten by the same unit's same chunk and head (see sw_fused.h).  A block is a 256-byte
+//           header (word 0: set by the device if a merge gave up), the unit states, then the
+//           tagged pieces, sized for a number of requests and zeroed when allocated.
 // A block that is outgrown is not freed: a HIP graph captured earlier on the stream still
 // holds its address.  It goes to `retired` and is freed by sw_release().
+struct FusedBlock {
+    char *base = nullptr;
+    int n_req_cap = 0;              // requests the block is sized for
+    size_t tag_bytes = 0;
+};
 struct Workspace {
     float *plain = nullptr;
     size_t plain_bytes = 0;
-    char *fused = nullptr;
-    size_t unit_cap = 0;            // unit states the block holds
-    size_t tag_bytes = 0;           // bytes of tagged pieces the block holds
+    std::map<std::array<int, 5>, FusedBlock> fused;
     std::vector<void *> retired;
-    // geometry ids: one per way of laying slots out (n_kvh, group, n_chunks, head_dim)
-    std::map<std::array<int, 4>, unsigned> geometry;
 };
 constexpr size_t kFusedHeader = 256;
-constexpr unsigned kMaxGeometry = (1u << 20) - 1;
 
 std::mutex g_mu;
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
@@ -159,11 +160,11 @@ int default_kernel(const SwArgs &a)
 }
 
 // One launch (a workgroup of each unit merges the unit's chunks, sw_fused.h) or two (a merge
-// kernel).  One launch is the default wherever its workspace of tagged pieces can be
-// addressed with 32-bit offsets; the choice never looks at the batch's lengths.
+// kernel).  One launch is the default wherever its pieces can be addressed with 32-bit
+// offsets; the choice never looks at the batch's lengths.
 bool fused_fits(size_t slots, int head_dim)
 {
-    return slots * (size_t)(head_dim / 2 + 1) * 16 < (1ull << 32);
+    return slots * (size_t)head_dim * 8 < 0xffffff00ull;
 }
 
 // Everything one step needs, dense or block-table.
@@ -207,47 +208,39 @@ int workspace_plain(Workspace &ws, SwArgs &a, size_t slots, hipStream_t stream)
     return SW_OK;
 }
 
-// Single-launch form: header, unit states, tagged pieces; zeroed whenever (re)allocated,
-// in stream order before the kernel that uses them.
-int workspace_fused(Workspace &ws, SwArgs &a, size_t slots, hipStream_t stream)
+// Single-launch form: the block of this call's geometry (header, unit states, tagged pieces),
+// allocated and zeroed -- in stream order, before the kernel that uses it -- when the geometry
+// is new or the batch has outgrown it.
+int workspace_fused(Workspace &ws, SwArgs &a, int which, hipStream_t stream)
 {
-    const size_t n_units = (size_t)a.n_req * a.n_qh;      // covers (request, kv head, head tile)
-    const size_t tag_need = slots * (size_t)(a.head_dim / 2 + 1) * 16;
-    bool fresh = false;
-    if (ws.unit_cap < n_units || ws.tag_bytes < tag_need) {
-        const size_t unit_cap = std::max(ws.unit_cap, n_units + n_units / 4 + 64);
-        size_t tag_bytes = std::max(ws.tag_bytes, tag_need + tag_need / 4);
-        tag_bytes = std::min<size_t>((tag_bytes + 255) & ~(size_t)255, 0xffffff00u);
-        const size_t total = kFusedHeader + unit_cap * sizeof(SwUnitState) + tag_bytes;
-        char *blk = nullptr;
-        hipError_t e = hipMalloc((void **)&blk, total);
-        if (e != hipSuccess) return fail_hip(e, "hipMalloc(workspace)");
-        if (ws.fused) ws.retired.push_back(ws.fused);
-        ws.fused = blk;
-        ws.unit_cap = unit_cap;
-        ws.tag_bytes = tag_bytes;
-        ws.geometry.clear();
-        fresh = true;
-    }
-    const std::array<int, 4> key = {a.n_kvh, a.group, a.n_chunks, a.head_dim};
-    auto it = ws.geometry.find(key);
-    if (it == ws.geometry.end()) {
-        if (ws.geometry.size() >= kMaxGeometry) {     // ids used up: start over on a clean block
-            ws.geometry.clear();
-            fresh = true;
+    // (the two kernels cut a group into head tiles, i.e. units, differently)
+    const std::array<int, 5> key = {a.n_kvh, a.group, a.n_chunks, a.head_dim, which};
+    FusedBlock &blk = ws.fused[key];
+    if (blk.n_req_cap < a.n_req) {
+        // pieces of one (chunk, head) slot: head_dim / 2 of 16 bytes
+        auto pieces_bytes = [&](int n) { return (size_t)n * a.n_qh * a.n_chunks * (size_t)a.head_dim * 8; };
+        int cap = std::max(a.n_req, blk.n_req_cap * 2);
+        if (pieces_bytes(cap) >= 0xffffff00ull) cap = a.n_req;      // the caller has checked that n_req fits
+        const size_t tag_bytes = pieces_bytes(cap);
+        const size_t units_bytes = ((size_t)cap * a.n_qh * sizeof(SwUnitState) + 255) & ~(size_t)255;
+        const size_t total = kFusedHeader + units_bytes + tag_bytes;
+        char *base = nullptr;
+        hipError_t e = hipMalloc((void **)&base, total);
+        if (e == hipSuccess) {
+            e = hipMemsetAsync(base, 0, total, stream);
+            if (e != hipSuccess) (void)hipFree(base);
         }
-        const unsigned id = (unsigned)ws.geometry.size() + 1;
-        it = ws.geometry.emplace(key, id).first;
+        if (e != hipSuccess) return fail_hip(e, "hipMalloc(workspace)");
+        if (blk.base) ws.retired.push_back(blk.base);
+        blk.base = base;
+        blk.n_req_cap = cap;
+        blk.tag_bytes = tag_bytes;
     }
-    if (fresh) {
-        hipError_t e = hipMemsetAsync(ws.fused, 0, kFusedHeader + ws.unit_cap * sizeof(SwUnitState) + ws.tag_bytes, stream);
-        if (e != hipSuccess) return fail_hip(e, "hipMemsetAsync(workspace)");
-    }
-    a.dev_err = reinterpret_cast<unsigned *>(ws.fused);
-    a.units = reinterpret_cast<SwUnitState *>(ws.fused + kFusedHeader);
-    a.ws_tag = ws.fused + kFusedHeader + ws.unit_cap * sizeof(SwUnitState);
-    a.ws_tag_bytes = (unsigned)ws.tag_bytes;
-    a.geometry = it->second;
+    const size_t units_bytes = ((size_t)blk.n_req_cap * a.n_qh * sizeof(SwUnitState) + 255) & ~(size_t)255;
+    a.dev_err = reinterpret_cast<unsigned *>(blk.base);
+    a.units = reinterpret_cast<SwUnitState *>(blk.base + kFusedHeader);
+    a.ws_tag = blk.base + kFusedHeader + units_bytes;
+    a.ws_tag_bytes = (unsigned)blk.tag_bytes;
     return SW_OK;
 }
 
@@ -339,12 +332,11 @@ int run_step(const StepIn &in)
     a.units = nullptr;
     a.ws_tag = nullptr;
     a.ws_tag_bytes = 0;
-    a.geometry = 0;
     a.dev_err = nullptr;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         Workspace &ws = g_ws[std::make_pair(dev, stream)];
-        int rc = fused ? workspace_fused(ws, a, slots, stream) : workspace_plain(ws, a, slots, stream);
+        int rc = fused ? workspace_fused(ws, a, which, stream) : workspace_plain(ws, a, slots, stream);
         if (rc != SW_OK) return rc;
     }
 
@@ -520,7 +512,8 @@ int sw_release(void)
         hipError_t e = hipSetDevice(kv.first.first);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess && kv.second.plain) e = hipFree(kv.second.plain);
-        if (e == hipSuccess && kv.second.fused) e = hipFree(kv.second.fused);
+        for (auto &fb : kv.second.fused)
+            if (e == hipSuccess && fb.second.base) e = hipFree(fb.second.base);
         for (void *old : kv.second.retired)
             if (e == hipSuccess) e = hipFree(old);
         if (e != hipSuccess && rc == SW_OK) rc = fail_hip(e, "sw_release");
@@ -540,11 +533,14 @@ int sw_device_status(int *gave_up)
     if (e != hipSuccess) return fail_hip(e, "sw_device_status");
     std::lock_guard<std::mutex> lk(g_mu);
     for (auto &kv : g_ws) {
-        if (kv.first.first != dev || !kv.second.fused) continue;
-        unsigned word = 0;
-        e = hipMemcpy(&word, kv.second.fused, sizeof(word), hipMemcpyDeviceToHost);
-        if (e != hipSuccess) return fail_hip(e, "sw_device_status");
-        if (word) *gave_up = 1;
+        if (kv.first.first != dev) continue;
+        for (auto &fb : kv.second.fused) {
+            if (!fb.second.base) continue;
+            unsigned word = 0;
+            e = hipMemcpy(&word, fb.second.base, sizeof(word), hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return fail_hip(e, "sw_device_status");
+            if (word) *gave_up = 1;
+        }
     }
     return SW_OK;
 }

@@ -176,7 +176,6 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         __builtin_amdgcn_global_load_lds(src, sm_new, 16, 0, 0);
     }
 
-    unsigned ticket = 0;                               // lane 0 of wave 0: the workgroup's ticket
     float m = kNegBig, l = 0.f;                        // m in raw score units
     const float lazy_raw = kLazyBits / a.scale_log2e;  // the raise threshold in raw score units
     float4_t o[8];
@@ -274,9 +273,6 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         // Outstanding, oldest first: K(t0) x8, V(t0) x8.
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         // -- phase: K tile landed
-        // Single launch: the workgroup takes its ticket while wave 0's last tile is under way,
-        // so the answer is there when the epilogue needs it.
-        if (FUSED && !MORE && wave == 0 && !alone && lane == 0) ticket = sw_fused_ticket(a, unit);
         // the new position lies in the chunk's last tile, which is some wave's last tile
         const bool has_new = !MORE && new_pos >= t0 && new_pos < t0 + kTile;     // wave-uniform
         if (has_new && gq == 0) {
@@ -456,10 +452,19 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
             sm_l[wave][n16] = l;
         }
     }
-    if (FUSED && !alone && threadIdx.x == 0) sm_flag = sw_fused_is_merger(a, unit, ticket, (int)nc) ? 1 : 0;
     __syncthreads();
-    if (FUSED && !alone) fz.merger = sm_flag != 0;
-    for (int idx = threadIdx.x; idx < gn * (kD / 4); idx += 64 * WAVES) {
+    // Single launch: every wave's tiles are done.  One lane takes the unit's ticket; while the
+    // answer travels, the threads merge the waves and send the chunk's pieces off.
+    unsigned ticket = 0;
+    if (FUSED && !alone && threadIdx.x == 0) ticket = sw_fused_ticket(a, unit);
+    // (a group of more than 8 heads gives a thread two rows' worth of dims)
+    constexpr int kMine = (16 * (kD / 4) + 64 * WAVES - 1) / (64 * WAVES);
+    float4_t my_num[kMine];
+    float my_den[kMine], my_mx[kMine];
+#pragma unroll
+    for (int k = 0; k < kMine; ++k) {
+        const int idx = threadIdx.x + k * 64 * WAVES;
+        if (idx >= gn * (kD / 4)) break;
         const int hh = idx >> 5;
         const int j4 = idx & 31;
         float mx = sm_m[0][hh];
@@ -481,7 +486,10 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
             continue;
         }
         if (FUSED) {
-            sw_fused_finish<kD>(a, fz, r, g, h0 + hh, j4, num, den, mx);
+            sw_fused_send<kD>(a, fz, r, g, h0 + hh, j4, num, den, mx);
+            my_num[k] = num;
+            my_den[k] = den;
+            my_mx[k] = mx;
             continue;
         }
         const long long slot = sw_ws_slot(a, r, g, c, h0 + hh);
@@ -489,6 +497,20 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         if (j4 == 0) *reinterpret_cast<float2_t *>(a.ws_ml + slot * 2) = float2_t{mx, den};
     }
     // -- phase: results stored
+    if (FUSED && !alone) {
+        // the workgroup that drew the unit's last ticket folds the chunks: every other one has
+        // sent its pieces before it drew its own
+        if (threadIdx.x == 0) sm_flag = sw_fused_is_merger(a, unit, ticket, (int)nc) ? 1 : 0;
+        __syncthreads();
+        if (sm_flag == 0) return;
+#pragma unroll
+        for (int k = 0; k < kMine; ++k) {
+            const int idx = threadIdx.x + k * 64 * WAVES;
+            if (idx < gn * (kD / 4))
+                sw_fused_fold<kD>(a, fz, r, g, h0 + (idx >> 5), idx & 31, my_num[k], my_den[k], my_mx[k]);
+        }
+    }
+    // -- phase: merged
 }
 
 }  // namespace

@@ -9,9 +9,8 @@
 // kept between calls: the ticket counter is zero outside a launch, the epoch counts the
 // calls in which the unit merged.
 struct SwUnitState {
-    unsigned           ticket;
-    unsigned           reserved;
-    unsigned long long epoch;
+    unsigned ticket;
+    unsigned epoch;
 };
 
 // Everything a kernel needs, passed by value.
@@ -35,13 +34,12 @@ struct SwArgs {
     uint16_t       *out;
     float          *ws_o;
     float          *ws_ml;
-    // single-launch variant (else units is null): per-unit ticket and epoch, the workspace of
-    // tagged 16-byte pieces (see sw_fused.h), the id of the way this call lays it out, and a
-    // word the device sets if a merge gave up waiting for a piece
+    // single-launch variant (else units is null): per-unit ticket and epoch, the tagged
+    // 16-byte pieces (see sw_fused.h), and a word the device sets if a merge gave up
+    // waiting for a piece
     SwUnitState    *units;
     void           *ws_tag;
     unsigned        ws_tag_bytes;
-    unsigned        geometry;
     unsigned       *dev_err;
     const uint16_t *k_new;              // append variant: the newest token's K rows [n_req][n_kvh][head_dim], else null
     const uint16_t *v_new;              //                 and V rows

@@ -216,7 +216,8 @@ void sw_partial_valu_kernel(SwArgs a)
         }
     }
     // single-launch variant: a request of one chunk is finished here; otherwise one thread
-    // takes the unit's ticket (see sw_fused.h) and the barrier hands the answer round
+    // takes the unit's ticket (see sw_fused.h) once every wave is done, the threads send the
+    // chunk's pieces, and the workgroup that drew the last ticket folds the unit's chunks
     const int nc = (w.L + a.chunk - 1) >> a.chunk_shift;
     const bool alone = fused && nc == 1;
     const long long unit = ((long long)r * a.n_kvh + g) * gridDim.y + ht;
@@ -226,11 +227,13 @@ void sw_partial_valu_kernel(SwArgs a)
         fz.nc = nc;
         fz.c = c;
         fz.merger = false;
-        if (!alone && threadIdx.x == 0)
-            sm_flag = sw_fused_is_merger(a, unit, sw_fused_ticket(a, unit), nc) ? 1 : 0;
     }
     __syncthreads();
-    if (fused && !alone) fz.merger = sm_flag != 0;
+    unsigned ticket = 0;
+    if (fused && !alone && threadIdx.x == 0) ticket = sw_fused_ticket(a, unit);
+    // at most GT * D / 4 <= 256 (head, four dims) pairs: one per thread
+    sw_float4_t my_num = sw_float4_t{0.f, 0.f, 0.f, 0.f};
+    float my_den = 0.f, my_mx = 0.f;
     for (int idx = threadIdx.x; idx < n_valid * (D / 4); idx += 64 * kWaves) {
         const int hh = idx / (D / 4);
         const int j4 = idx - hh * (D / 4);
@@ -251,12 +254,23 @@ void sw_partial_valu_kernel(SwArgs a)
             continue;
         }
         if (fused) {
-            sw_fused_finish<D>(a, fz, r, g, ht * GT + hh, j4, num, den, mx);
+            sw_fused_send<D>(a, fz, r, g, ht * GT + hh, j4, num, den, mx);
+            my_num = num;
+            my_den = den;
+            my_mx = mx;
             continue;
         }
         const long long slot = sw_ws_slot(a, r, g, c, ht * GT + hh);
         *reinterpret_cast<sw_float4_t *>(a.ws_o + slot * D + 4 * j4) = num;
         if (j4 == 0) *reinterpret_cast<sw_float2_t *>(a.ws_ml + slot * 2) = sw_float2_t{mx, den};
+    }
+    if (fused && !alone) {
+        if (threadIdx.x == 0) sm_flag = sw_fused_is_merger(a, unit, ticket, nc) ? 1 : 0;
+        __syncthreads();
+        if (sm_flag == 0) return;
+        const int idx = threadIdx.x;
+        if (idx < n_valid * (D / 4))
+            sw_fused_fold<D>(a, fz, r, g, ht * GT + idx / (D / 4), idx % (D / 4), my_num, my_den, my_mx);
     }
 }
 
