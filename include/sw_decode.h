@@ -389,6 +389,28 @@ int sw_version(void);
 int sw_release(void);
 
 /*
+ * sw_decode_attn_static -- sw_decode_attn for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * Same arguments, same result up to the rounding of the merge (it is the two-kernel form,
+ * SW_PARAM_COMBINE = 1, bit for bit), but the partial results between its two kernels live
+ * in a static device array of SW_STATIC_SCRATCH_BYTES inside the library instead of the
+ * per-stream workspace: the call allocates and frees nothing, on the device or through any
+ * library.  A shape whose partial results, n_req * n_qh * ceil(max_len / chunk) *
+ * (head_dim + 2) * 4 bytes (chunk: SW_PARAM_CHUNK, by default 256 doubled until 16 chunks
+ * cover max_len, at most 1024), exceed that size is refused with SW_ERR_UNSUPPORTED
+ * before anything is launched.
+ * Every GPU the library runs on holds its own copy of the array until the process ends.  All
+ * calls on one GPU share it, whatever their stream: calls that overlap on one GPU race, so
+ * order them (one stream, or events).  Nothing in it needs clearing between calls: a call
+ * reads back only what it has written itself.  Not recorded by sw_prof_start/stop.
+ */
+#define SW_STATIC_SCRATCH_BYTES (32u << 20)
+int sw_decode_attn_static(const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *seq_lens, void *out,
+                          int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                          void *stream);
+
+/*
  * sw_device_status -- support: waits for the current device to go idle and reports
  * whether any single-launch merge on it ever gave up waiting for another workgroup's
  * partial result (the wait inside the kernel is bounded so that a kernel always ends; a

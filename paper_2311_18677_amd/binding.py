@@ -30,7 +30,7 @@ SW_PARAM_PREFILL_WAVES = 6
 SW_PARAM_PREFILL_KERNEL = 7
 SW_PARAM_MIXED_MERGE = 8
 
-EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_kv_paged_layout", "sw_decode_attn_paged",
+EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_decode_attn_static", "sw_kv_paged_layout", "sw_decode_attn_paged",
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
            "sw_prefill_attn", "sw_mixed_attn", "sw_prefill_attn_paged", "sw_mixed_attn_paged", "sw_kv_store", "sw_kv_store_paged", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release", "sw_device_status",
@@ -82,6 +82,8 @@ def load():
     lib.sw_kv_layout.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sw_kv_layout_t)]
     lib.sw_decode_attn.restype = ci
     lib.sw_decode_attn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.sw_decode_attn_static.restype = ci
+    lib.sw_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
     lib.sw_kv_paged_layout.restype = ci
     lib.sw_kv_paged_layout.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sw_kv_paged_layout_t)]
     lib.sw_decode_attn_paged.restype = ci
@@ -181,6 +183,14 @@ def sw_decode_attn(q, k_cache, v_cache, seq_lens, out, n_req, n_qh, n_kvh, head_
     """One decode step's attention; enqueues on `stream` and returns without waiting."""
     rc = load().sw_decode_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out),
                                n_req, n_qh, n_kvh, head_dim, max_len, _stream(stream))
+    return _check(rc) if check else rc
+
+
+def sw_decode_attn_static(q, k_cache, v_cache, seq_lens, out, n_req, n_qh, n_kvh, head_dim, max_len,
+                          stream=None, check=True):
+    """sw_decode_attn over the library's static scratch array: allocates nothing."""
+    rc = load().sw_decode_attn_static(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(out),
+                                      n_req, n_qh, n_kvh, head_dim, max_len, _stream(stream))
     return _check(rc) if check else rc
 
 

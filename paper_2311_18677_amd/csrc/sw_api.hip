@@ -60,6 +60,31 @@ struct Workspace {
 };
 constexpr size_t kFusedHeader = 256;
 
+// Workspace of sw_decode_attn_static: partial results of the two-kernel form, for callers
+// that cannot allocate.  Every GPU the library runs on holds its own copy of the array, at
+// its own address, until the process ends; host code never uses the array's name as a
+// pointer (it is a host-side stand-in), only the address hipGetSymbolAddress returns for it
+// on the device that is current at the time, looked up once per device.
+constexpr size_t kStaticScratchBytes = SW_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};      // per device, null until looked up (guarded by g_scratch_mu)
+std::mutex g_scratch_mu;
+
+int static_scratch(int dev, float **ptr)
+{
+    if (dev < 0 || dev >= kMaxDevices) return fail(SW_ERR_UNSUPPORTED, "device index above 63");
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));     // the current device is `dev`
+        if (e != hipSuccess || !p) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = static_cast<float *>(g_scratch_ptr[dev]);
+    return SW_OK;
+}
+
 std::mutex g_mu;
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 
@@ -184,6 +209,9 @@ struct StepIn {
     // mixed batches: if non-null and the step would launch the combine kernel, it does not;
     // the kernel's arguments go here instead and the caller sees to the merge
     SwArgs *defer_merge = nullptr;
+    // sw_decode_attn_static: two kernels over the library's static scratch array; no
+    // allocation, no per-kernel timing
+    bool static_ws = false;
 };
 
 // Two-kernel form: slots of (head_dim + 2) floats per (request, query head, chunk).
@@ -322,7 +350,11 @@ int run_step(const StepIn &in)
     const size_t slots = (size_t)n_req * n_qh * n_chunks;
     if (combine == 2 && !fused_fits(slots, head_dim))
         return fail(SW_ERR_UNSUPPORTED, "the single-launch workspace would exceed 4 GiB");
-    const bool fused = combine == 0 ? fused_fits(slots, head_dim) : combine == 2;
+    const bool fused = in.static_ws ? false : (combine == 0 ? fused_fits(slots, head_dim) : combine == 2);
+    if (in.static_ws && slots * (size_t)(head_dim + 2) * sizeof(float) > kStaticScratchBytes)
+        return fail(SW_ERR_UNSUPPORTED, "the partial results of this shape (n_req * n_qh * ceil(max_len / chunk) * "
+                                        "(head_dim + 2) * 4 bytes) exceed the static scratch of "
+                                        + std::to_string(kStaticScratchBytes) + " bytes");
 
     // ---- workspace ----
     int dev = 0;
@@ -333,7 +365,13 @@ int run_step(const StepIn &in)
     a.ws_tag = nullptr;
     a.ws_tag_bytes = 0;
     a.dev_err = nullptr;
-    {
+    if (in.static_ws) {
+        float *base = nullptr;
+        int rc = static_scratch(dev, &base);
+        if (rc != SW_OK) return rc;
+        a.ws_o = base;
+        a.ws_ml = base + slots * head_dim;
+    } else {
         std::lock_guard<std::mutex> lk(g_mu);
         Workspace &ws = g_ws[std::make_pair(dev, stream)];
         int rc = fused ? workspace_fused(ws, a, which, stream) : workspace_plain(ws, a, slots, stream);
@@ -343,7 +381,7 @@ int run_step(const StepIn &in)
     const bool defer = in.defer_merge && !fused;
     SwLaunchEvents ev_p = {nullptr, nullptr}, ev_c = {nullptr, nullptr};
     ProfRec rec;
-    int prc = prof_begin(rec, !fused && !defer, &prof);
+    int prc = in.static_ws ? SW_OK : prof_begin(rec, !fused && !defer, &prof);
     if (prc != SW_OK) return prc;
     if (prof) {
         ev_p = {rec.ev[0], rec.ev[1]};
@@ -550,7 +588,7 @@ static int decode_dense(const void *q, const void *k_new, const void *v_new, boo
                         const void *k_cache, const void *v_cache,
                         const int32_t *seq_lens, void *out,
                         int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
-                        void *stream_v)
+                        void *stream_v, bool static_ws = false)
 {
     // ---- validation: nothing below this block runs on bad arguments, and
     // nothing in it touches HIP ----
@@ -577,7 +615,17 @@ static int decode_dense(const void *q, const void *k_new, const void *v_new, boo
     in.n_req = n_req; in.n_qh = n_qh; in.n_kvh = n_kvh; in.head_dim = head_dim; in.max_len = max_len;
     in.block_table = nullptr; in.block_size = in.max_blocks = in.n_blocks = 0;
     in.stream = (hipStream_t)stream_v;
+    in.static_ws = static_ws;
     return run_step(in);
+}
+
+int sw_decode_attn_static(const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *seq_lens, void *out,
+                          int n_req, int n_qh, int n_kvh, int head_dim, int max_len,
+                          void *stream)
+{
+    return decode_dense(q, nullptr, nullptr, false, k_cache, v_cache, seq_lens, out,
+                        n_req, n_qh, n_kvh, head_dim, max_len, stream, true);
 }
 
 int sw_decode_attn(const void *q, const void *k_cache, const void *v_cache,
