@@ -185,8 +185,19 @@ int default_kernel(const SwArgs &a)
 }
 
 // One launch (a workgroup of each unit merges the unit's chunks, sw_fused.h) or two (a merge
-// kernel).  One launch is the default wherever its pieces can be addressed with 32-bit
-// offsets; the choice never looks at the batch's lengths.
+// kernel).  Measured over batches of 4 to 128 requests (8 query heads on one key/value head):
+// one launch wins while a request has at most 4 chunks -- 30 % where every request is a single
+// chunk and no merge happens at all, 4-7 % at 2 to 4 chunks -- and loses beyond (3 % at 8
+// chunks, 10-25 % at 14 to 28): the one workgroup that merges a unit walks its chunks on one
+// compute unit, where the merge kernel spreads every output row over lanes of its own all
+// over the chip.  The choice looks at max_len alone (through the chunk length), never at the
+// batch's lengths.
+bool default_fused(int n_chunks, size_t slots, int head_dim)
+{
+    return n_chunks <= 4 && slots * (size_t)head_dim * 8 < 0xffffff00ull;
+}
+
+// The single-launch form's pieces are addressed with 32-bit offsets.
 bool fused_fits(size_t slots, int head_dim)
 {
     return slots * (size_t)head_dim * 8 < 0xffffff00ull;
@@ -350,7 +361,7 @@ int run_step(const StepIn &in)
     const size_t slots = (size_t)n_req * n_qh * n_chunks;
     if (combine == 2 && !fused_fits(slots, head_dim))
         return fail(SW_ERR_UNSUPPORTED, "the single-launch workspace would exceed 4 GiB");
-    const bool fused = in.static_ws ? false : (combine == 0 ? fused_fits(slots, head_dim) : combine == 2);
+    const bool fused = in.static_ws ? false : (combine == 0 ? default_fused(n_chunks, slots, head_dim) : combine == 2);
     if (in.static_ws && slots * (size_t)(head_dim + 2) * sizeof(float) > kStaticScratchBytes)
         return fail(SW_ERR_UNSUPPORTED, "the partial results of this shape (n_req * n_qh * ceil(max_len / chunk) * "
                                         "(head_dim + 2) * 4 bytes) exceed the static scratch of "
