@@ -8,6 +8,12 @@ HBM, not from the last-level cache.  One JSON line is printed.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
+The K steps are launched as HIP-graph replays (whole rotations, plus one graph for
+a remainder) and timed with HIP events recorded on the stream they run on; they
+are run --repeats times and the median repeat is reported (minimum beside it).
+After the headline workload the other workloads are run briefly the same way and
+reported in the line's `configs` array.
+
 --append times the append-then-attend entry point instead (same rotation, the
 newest rows rewritten in place every call).  --decode-loop runs whole model
 steps: one append-then-attend call per layer over that many per-layer caches
@@ -58,6 +64,10 @@ def parse_args():
     ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--prefill-waves", type=int, default=0)
     ap.add_argument("--prefill-kernel", type=int, default=0)
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the K timed steps are run this many times; ms_per_step is the median")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="leave out the short runs of the other workloads (the `configs` array)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch plain device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings); 0 = none")
@@ -182,13 +192,13 @@ def stream_read_ceiling(sw, torch, n_bytes, dev, launches=400):
     reps = max(2, launches // n_bufs)
     with torch.cuda.stream(stream):
         graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    with torch.cuda.stream(stream):
-        for _ in range(reps):
-            graph.replay()
-    torch.cuda.synchronize()
-    call_us = (time.perf_counter() - t0) / (reps * n_bufs) * 1e6
+
+    def replays():
+        with torch.cuda.stream(stream):
+            for _ in range(reps):
+                graph.replay()
+
+    call_us = min(time_on_stream(torch, stream, replays)[0] for _ in range(3)) / (reps * n_bufs) * 1e3
     n_prof = min(launches, 4 * n_bufs)
     sw.sw_prof_start(n_prof)
     for i in range(n_prof):
@@ -553,6 +563,157 @@ def main_handoff(args):
     print(json.dumps(line))
 
 
+class GraphSteps:
+    """Runs exactly n steps as HIP-graph launches on one stream: whole rotations over the cache
+    sets replay one graph, a remainder replays a second graph of the rotation's first sets.
+    Nothing is launched eagerly, so every step of a timed region is launched the same way."""
+
+    def __init__(self, torch, stream, n_sets, record):
+        self.torch, self.stream, self.n_sets, self.record = torch, stream, n_sets, record
+        self.graphs = {}
+
+    def graph(self, k):
+        if k not in self.graphs:
+            g = self.torch.cuda.CUDAGraph()
+            with self.torch.cuda.graph(g, stream=self.stream):
+                self.record(k, self.torch.cuda.current_stream())
+            self.torch.cuda.synchronize()
+            self.graphs[k] = g
+        return self.graphs[k]
+
+    def prepare(self, *counts):
+        for n in counts:
+            if n >= self.n_sets:
+                self.graph(self.n_sets)
+            if n % self.n_sets:
+                self.graph(n % self.n_sets)
+
+    def run(self, n):
+        full, rem = divmod(n, self.n_sets)
+        with self.torch.cuda.stream(self.stream):
+            for _ in range(full):
+                self.graph(self.n_sets).replay()
+            if rem:
+                self.graph(rem).replay()
+
+
+def time_on_stream(torch, stream, launch):
+    """Milliseconds between two HIP events recorded on `stream` right before and right after
+    what launch() enqueues there, and the host's wall-clock time around the same region (with a
+    device synchronisation on both sides)."""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    launch()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return e0.elapsed_time(e1), 1e3 * (t1 - t0)
+
+
+def median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def parity_vs_oracle(np, out, ref):
+    diff = out - ref
+    den = np.sqrt((ref ** 2).sum(-1))
+    rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
+    return {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+
+
+def measure_other_config(name, torch, np, sw, wl, dev, steps, warmup, repeats, with_oracle):
+    """A short run of another workload on the plain entry point, library defaults: the same
+    rotation over cache sets, the same event timing, the same per-dispatch kernel times, and
+    set 0 against the oracle."""
+    cfg = wl.CONFIGS[name]
+    lay = sw.sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+    batch0 = wl.make_batch(cfg)
+    set0 = sw.upload_batch(batch0, device="cuda:0", pad_bits=0)
+    set0["kv_bytes"] = batch0.kv_bytes
+    want = -(-4 * LLC_BYTES // max(batch0.kv_bytes, 1))
+    n_sets = int(max(2, min(want, 32)))
+    sets = [set0]
+    for i in range(1, n_sets):
+        sets.append(make_device_set(cfg, lay, wl.BASE_SEED + 1000 * cfg.seed_index + i, torch, np, wl, dev))
+    stream = torch.cuda.Stream(device=dev)
+
+    def call(s, st):
+        sw.sw_decode_attn(s["q"], s["k_cache"], s["v_cache"], s["seq_lens"], s["out"],
+                          cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, st)
+
+    call(set0, stream)
+    stream.synchronize()
+    runner = GraphSteps(torch, stream, n_sets, lambda k, st: [call(s, st) for s in sets[:k]])
+    runner.prepare(steps, warmup)
+    runner.run(warmup)
+    ev_ms = [time_on_stream(torch, stream, lambda: runner.run(steps))[0] for _ in range(repeats)]
+    mean_bytes = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps)) / steps
+    n_prof = min(steps, 20 * n_sets)
+    sw.sw_prof_start(n_prof)
+    for i in range(n_prof):
+        call(sets[i % n_sets], stream)
+    p_us, c_us, n_rec = sw.sw_prof_stop()
+    prof_bytes = sum(sets[i % n_sets]["kv_bytes"] for i in range(n_rec)) / max(n_rec, 1)
+    partial_us, combine_us = p_us / max(n_rec, 1), c_us / max(n_rec, 1)
+    res = {"workload": cfg.name, "steps": steps, "warmup": warmup, "repeats": repeats,
+           "cache_sets": n_sets, "llc_resident": bool(want > n_sets),
+           "kv_bytes_per_step": mean_bytes,
+           "call_us": 1e3 * median(ev_ms) / steps, "call_us_min": 1e3 * min(ev_ms) / steps,
+           "GBps": mean_bytes * steps / (median(ev_ms) * 1e-3) / 1e9,
+           "kernel_us": partial_us, "combine_us": combine_us,
+           "kernel_GBps": prof_bytes / partial_us / 1e3 if partial_us > 0 else 0.0}
+    res["kernel_frac"] = res["kernel_GBps"] / HBM_PEAK_GBPS
+    res["traffic"] = read_traffic(cfg.name)
+    if with_oracle:
+        import oracle
+        call(set0, stream)
+        stream.synchronize()
+        out = set0["out"].cpu().numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        ref = oracle.decode_attn(batch0.q, set0["k_host"], set0["v_host"], batch0.seq_lens, cfg.n_req,
+                                 cfg.n_qh, cfg.n_kvh, cfg.head_dim, cfg.max_len, lay.stride_req,
+                                 lay.stride_kvh, lay.stride_tok)
+        res["oracle_s"] = time.perf_counter() - c0
+        res["parity_set0"] = parity_vs_oracle(np, out, ref)
+    del sets, set0, runner
+    torch.cuda.empty_cache()
+    return res
+
+
+def oracle_single_thread(np, wl, sw, name="tiny_mha", budget_s=2.0):
+    """The oracle on one host thread over the small workload: time per decode step."""
+    import oracle
+    cfg = wl.CONFIGS[name]
+    lay = sw.sw_kv_layout(cfg.n_req, cfg.n_kvh, cfg.head_dim, cfg.max_len)
+    b = wl.make_batch(cfg)
+    k = wl.pack_cache(b.k_rows, cfg, lay.stride_req, lay.stride_kvh, lay.stride_tok, lay.total_elems)
+    v = wl.pack_cache(b.v_rows, cfg, lay.stride_req, lay.stride_kvh, lay.stride_tok, lay.total_elems)
+    reps, t = 0, 0.0
+    while t < budget_s and reps < 20000:
+        c0 = time.perf_counter()
+        oracle.decode_attn(b.q, k, v, b.seq_lens, cfg.n_req, cfg.n_qh, cfg.n_kvh, cfg.head_dim,
+                           cfg.max_len, lay.stride_req, lay.stride_kvh, lay.stride_tok, n_threads=1)
+        t += time.perf_counter() - c0
+        reps += 1
+    return {"workload": cfg.name, "threads": 1, "us_per_step": 1e6 * t / reps,
+            "value": b.kv_bytes * reps / t / 1e9, "unit": "GB/s", "repetitions": reps}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -585,7 +746,7 @@ def main():
     # ---- inputs: set 0 from the host recipe (also the oracle's input), the rest on device
     append = args.append or args.decode_loop
     loop = args.decode_loop
-    room = (args.steps + args.warmup) // cfg.n_layers + 60 if loop else (1 if append else 0)
+    room = (max(1, args.repeats) * args.steps + args.warmup) // cfg.n_layers + 60 if loop else (1 if append else 0)
     batch0 = wl.make_batch(cfg)
     if args.paged:
         set0 = sw.upload_paged_batch(batch0, args.paged, device="cuda:0", pad_bits=0, room=room)
@@ -681,37 +842,32 @@ def main():
                                      lay.stride_tok)
         host0 = (k0, v0, lens1)
         out = set0["out"].cpu().numpy().astype(np.float64)
-        diff = out - ref
-        den = np.sqrt((ref ** 2).sum(-1))
-        rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
-        parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+        parity = parity_vs_oracle(np, out, ref)
 
     steps, warmup = args.steps, args.warmup
     mode = args.mode
-    graph = None
+    repeats = max(1, args.repeats)
+
+    def record(k, st):
+        for s in sets[:k]:
+            call(s, st)
+        if k == n_sets:
+            end_of_model_step(st)
+
+    runner = None
     if mode == "graph":
-        # one graph = one rotation over all sets; replayed ceil(steps / n_sets) times
         try:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                for s in sets:
-                    call(s, torch.cuda.current_stream())
-                end_of_model_step(torch.cuda.current_stream())
-            torch.cuda.synchronize()
+            runner = GraphSteps(torch, stream, n_sets, record)
+            runner.prepare(steps, warmup)
         except Exception as e:      # noqa: BLE001 -- report and fall back to eager launches
             print("bench.py: graph capture failed (%s); using eager launches" % e, file=sys.stderr)
-            graph = None
+            runner = None
             mode = "eager"
 
     def run_steps(n):
-        """Exactly n steps: whole rotations as graph replays, the remainder as eager calls."""
-        if graph is not None:
-            full, rem = divmod(n, n_sets)
-            with torch.cuda.stream(stream):
-                for _ in range(full):
-                    graph.replay()
-            for i in range(rem):
-                call(sets[i], stream)
+        """Exactly n steps on the bench stream."""
+        if runner is not None:
+            runner.run(n)
             return
         for i in range(n):
             call(sets[i % n_sets], stream)
@@ -720,25 +876,39 @@ def main():
 
     run_steps(warmup)
     torch.cuda.synchronize()
-    bytes_before = attended_bytes()
-    t0 = time.perf_counter()
-    run_steps(steps)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    elapsed = t1 - t0
-    if loop:
-        # every layer call of a model step reads the same lengths, which grow by one per
-        # model step: the mean of the first and the last step's bytes, times the calls
-        full_steps = steps // n_sets
-        bytes_last = attended_bytes() - (cfg.n_req * cfg.n_kvh * cfg.head_dim * 4 if full_steps else 0)
-        bytes_done = 0.5 * (bytes_before + bytes_last) * steps
-    elif append:
-        bytes_done = bytes_before / sets[0]["kv_bytes"] * sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
-    else:
-        bytes_done = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
+    # the K steps, `repeats` times over; each repeat timed with HIP events recorded on the
+    # bench stream itself, and with the host clock around a synchronised region beside it
+    ev_ms, wall_ms, rep_bytes = [], [], []
+    for _ in range(repeats):
+        bytes_before = attended_bytes()
+        e_ms, w_ms = time_on_stream(torch, stream, lambda: run_steps(steps))
+        if loop:
+            # every layer call of a model step reads the same lengths, which grow by one per
+            # model step: the mean of the first and the last step's bytes, times the calls
+            full_steps = steps // n_sets
+            bytes_last = attended_bytes() - (cfg.n_req * cfg.n_kvh * cfg.head_dim * 4 if full_steps else 0)
+            bytes_done = 0.5 * (bytes_before + bytes_last) * steps
+        elif append:
+            bytes_done = bytes_before / sets[0]["kv_bytes"] * sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
+        else:
+            bytes_done = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))
+        ev_ms.append(e_ms)
+        wall_ms.append(w_ms)
+        rep_bytes.append(bytes_done)
+    order = sorted(range(repeats), key=lambda i: ev_ms[i])
+    mid = order[(repeats - 1) // 2]                  # the median repeat (lower one if even)
+    elapsed = ev_ms[mid] * 1e-3
+    bytes_done = rep_bytes[mid]
     mean_bytes = bytes_done / steps
     gbps = bytes_done / elapsed / 1e9
     steps_per_s = steps / elapsed
+    timing = {"method": "HIP events recorded on the bench stream around the K graph-launched steps; "
+                        "value and ms_per_step are the median repeat",
+              "repeats": repeats,
+              "ms_per_step_median": 1e3 * elapsed / steps,
+              "ms_per_step_min": min(ev_ms) / steps,
+              "ms_per_step_max": max(ev_ms) / steps,
+              "host_clock_ms_per_step_median": median(wall_ms) / steps}
 
     # ---- per-kernel device time (HIP events attached to each dispatch, same stream, eager)
     prof_calls = min(steps, 50 * n_sets)
@@ -810,10 +980,21 @@ def main():
                                   % (cfg.name, batch0.kv_bytes, reps, t_cpu),
                         "decode_steps_per_s": reps / t_cpu}
         if not append:
-            diff = out - ref
-            den = np.sqrt((ref ** 2).sum(-1))
-            rel = np.sqrt((diff ** 2).sum(-1)) / np.where(den == 0, 1.0, den)
-            parity = {"max_abs": float(np.abs(diff).max()), "max_row_rel_l2": float(rel.max())}
+            parity = parity_vs_oracle(np, out, ref)
+        cpu_baseline["cpu_model"] = cpu_model()
+        cpu_baseline["single_thread"] = oracle_single_thread(np, wl, sw)
+
+    # ---- the other workloads, briefly (library defaults, plain entry point)
+    others = None
+    plain = not (args.paged or append or args.chunk or args.kernel or args.waves or args.combine)
+    if plain and not args.no_configs:
+        others = []
+        for name in wl.CONFIGS:
+            if name == cfg.name:
+                continue
+            others.append(measure_other_config(name, torch, np, sw, wl, dev,
+                                               steps=min(steps, 1000), warmup=min(warmup, 200),
+                                               repeats=repeats, with_oracle=not args.no_cpu_baseline))
 
     line = {
         "metric": "achieved HBM GB/s on K/V reads (% of MI355X peak) + decode steps/sec",
@@ -827,6 +1008,7 @@ def main():
         "steps": steps,
         "warmup": warmup,
         "ms_per_step": 1e3 * elapsed / steps,
+        "timing": timing,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -848,9 +1030,16 @@ def main():
                      "traffic": None if (args.paged or append) else read_traffic(cfg.name),
                      "kernel": "partial (dominant)", "kernel_us": partial_us,
                      "combine_us": combine_us, "bytes_per_launch": prof_bytes,
-                     "launches_timed": n_rec},
+                     "launches_timed": n_rec,
+                     "call_us": 1e6 * elapsed / steps,
+                     "kernels_sum_us": partial_us + combine_us,
+                     "note": "kernel_us and combine_us are HIP events attached to each dispatch of "
+                             "eager launches (each carries the events' own cost, about what an empty "
+                             "kernel reads this way); call_us is the whole call in graph-launched "
+                             "steps, where the combine's launch overlaps the dominant kernel's end"},
         "cpu_baseline": cpu_baseline,
         "parity_set0": parity,
+        "configs": others,
     }
     if ceiling is not None:
         line["roofline"]["stream_read_ceiling"] = ceiling
