@@ -924,6 +924,7 @@ def main():
             prof_bytes *= bytes_before / sets[0]["kv_bytes"]
     partial_us = p_us / max(n_rec, 1)
     combine_us = c_us / max(n_rec, 1)
+    eager_gap_us = sw.sw_prof_last_gap() / max(n_rec, 1)
     achieved = prof_bytes / (partial_us * 1e-6) / 1e9 if partial_us > 0 else 0.0
 
     # ---- the plain streaming read of the same byte count, timed the same way and at the same
@@ -1032,11 +1033,14 @@ def main():
                      "combine_us": combine_us, "bytes_per_launch": prof_bytes,
                      "launches_timed": n_rec,
                      "call_us": 1e6 * elapsed / steps,
-                     "kernels_sum_us": partial_us + combine_us,
-                     "note": "kernel_us and combine_us are HIP events attached to each dispatch of "
-                             "eager launches (each carries the events' own cost, about what an empty "
-                             "kernel reads this way); call_us is the whole call in graph-launched "
-                             "steps, where the combine's launch overlaps the dominant kernel's end"},
+                     "inter_kernel_gap_us": 1e6 * elapsed / steps - partial_us - combine_us,
+                     "eager_inter_kernel_gap_us": eager_gap_us,
+                     "note": "kernel_us and combine_us are HIP events attached to each dispatch of eager "
+                             "launches, eager_inter_kernel_gap_us the time from the first kernel's end "
+                             "event to the second's start event in those launches; call_us is the whole "
+                             "call in the graph-launched timed steps and inter_kernel_gap_us = call_us - "
+                             "kernel_us - combine_us (negative: graph-launched neighbours overlap part of "
+                             "what the per-dispatch events count for each kernel)"},
         "cpu_baseline": cpu_baseline,
         "parity_set0": parity,
         "configs": others,

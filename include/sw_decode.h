@@ -478,6 +478,12 @@ int sw_get_param(int key, int *value);
  */
 int sw_prof_start(int capacity);
 int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls);
+/*
+ * The time between the partial kernel's end event and the combine kernel's start
+ * event, in microseconds summed over the calls the last sw_prof_stop reported (0
+ * where no combine kernel ran; negative where the two overlapped).  Host pointer.
+ */
+int sw_prof_last_gap(double *gap_us_sum);
 
 /*
  * sw_stream_read -- measurement support: one kernel that reads n_bytes of device

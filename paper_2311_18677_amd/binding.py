@@ -34,7 +34,7 @@ EXPORTS = ("sw_kv_layout", "sw_decode_attn", "sw_decode_attn_static", "sw_kv_pag
            "sw_decode_attn_append", "sw_decode_attn_paged_append", "sw_advance_lens",
            "sw_prefill_attn", "sw_mixed_attn", "sw_prefill_attn_paged", "sw_mixed_attn_paged", "sw_kv_store", "sw_kv_store_paged", "sw_kv_pack", "sw_kv_unpack", "sw_kv_span_plan",
            "sw_last_error", "sw_version", "sw_release", "sw_device_status",
-           "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop", "sw_stream_read")
+           "sw_set_param", "sw_get_param", "sw_prof_start", "sw_prof_stop", "sw_prof_last_gap", "sw_stream_read")
 
 
 class sw_kv_layout_t(ctypes.Structure):
@@ -131,6 +131,8 @@ def load():
     lib.sw_stream_read.argtypes = [vp, ctypes.c_longlong, vp, ci, vp]
     lib.sw_prof_start.restype = ci
     lib.sw_prof_start.argtypes = [ci]
+    lib.sw_prof_last_gap.restype = ci
+    lib.sw_prof_last_gap.argtypes = [ctypes.POINTER(ctypes.c_double)]
     lib.sw_prof_stop.restype = ci
     lib.sw_prof_stop.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                  ctypes.POINTER(ci)]
@@ -308,6 +310,14 @@ def sw_get_param(key):
 
 def sw_prof_start(capacity):
     return _check(load().sw_prof_start(capacity))
+
+
+def sw_prof_last_gap():
+    """Microseconds between the partial kernel's end and the combine kernel's start, summed
+    over the calls the last sw_prof_stop reported."""
+    g = ctypes.c_double(0.0)
+    _check(load().sw_prof_last_gap(ctypes.byref(g)))
+    return g.value
 
 
 def sw_prof_stop():

@@ -103,6 +103,7 @@ struct ProfRec { hipEvent_t ev[4]; bool has_combine; };
 bool g_prof_on = false;
 int g_prof_cap = 0;
 std::vector<ProfRec> g_prof;
+double g_prof_gap_us = 0.0;            // partial kernel's end to combine kernel's start, summed by the last sw_prof_stop
 std::vector<hipEvent_t> g_event_pool;   // created by sw_prof_start so that profiled calls stay cheap on the host
 constexpr int kEventPoolRecords = 8192;
 
@@ -525,16 +526,18 @@ int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls)
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_prof_on) return fail(SW_ERR_STATE, "sw_prof_stop without sw_prof_start");
     g_prof_on = false;
-    double p = 0.0, c = 0.0;
+    double p = 0.0, c = 0.0, gap = 0.0;
     int n = 0, rc = SW_OK;
     for (ProfRec &rec : g_prof) {
-        float ms0 = 0.f, ms1 = 0.f;
+        float ms0 = 0.f, ms1 = 0.f, ms_gap = 0.f;
         hipError_t e = hipEventSynchronize(rec.has_combine ? rec.ev[3] : rec.ev[1]);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms0, rec.ev[0], rec.ev[1]);
         if (e == hipSuccess && rec.has_combine) e = hipEventElapsedTime(&ms1, rec.ev[2], rec.ev[3]);
+        if (e == hipSuccess && rec.has_combine) e = hipEventElapsedTime(&ms_gap, rec.ev[1], rec.ev[2]);
         if (e == hipSuccess) {
             p += 1e3 * ms0;
             c += 1e3 * ms1;
+            gap += 1e3 * ms_gap;
             ++n;
         } else if (rc == SW_OK) {
             rc = fail_hip(e, "reading profile events");
@@ -544,10 +547,19 @@ int sw_prof_stop(double *partial_us_sum, double *combine_us_sum, int *n_calls)
     g_prof.clear();
     for (hipEvent_t ev : g_event_pool) (void)hipEventDestroy(ev);
     g_event_pool.clear();
+    g_prof_gap_us = gap;
     if (partial_us_sum) *partial_us_sum = p;
     if (combine_us_sum) *combine_us_sum = c;
     if (n_calls) *n_calls = n;
     return rc;
+}
+
+int sw_prof_last_gap(double *gap_us_sum)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!gap_us_sum) return fail(SW_ERR_PARAM, "null pointer");
+    *gap_us_sum = g_prof_gap_us;
+    return SW_OK;
 }
 
 int sw_release(void)

@@ -33,17 +33,12 @@ void sw_combine_kernel(SwArgs a)
     const float4_t *po = reinterpret_cast<const float4_t *>(a.ws_o + slot0 * D) + j4;
     const long long cs = a.group;                                     // slots between consecutive chunks
 
-    // The first round of partial results is requested together with the length:
-    // slots up to n_chunks exist whether or not they were written, so the loads are
-    // in bounds, and what lies at or past the request's chunk count is never used.
+    // Partial results are requested once the length is known, so that slots nobody wrote are
+    // never fetched.  (Asking for the first chunks together with the length was measured on the
+    // five benchmark workloads: no faster on any, and it fetched up to five times the bytes
+    // that were written.)
     float2_t mlc[4];
     float4_t x[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int c = min(k + u * kGroups, a.n_chunks - 1);
-        mlc[u] = ml[c * cs];
-        x[u]   = po[c * cs * V4];
-    }
     const int lf = sw_request_len_flagged(a, r);
     if (lf == kSwSkip) return;                   // the request takes no part in this call
     const int L = lf & kSwLenMask;
@@ -56,10 +51,10 @@ void sw_combine_kernel(SwArgs a)
 
     Group mine = empty_group();
     for (int c0 = k; c0 < nc; c0 += 4 * kGroups) {
-        if (c0 != k) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = min(c0 + u * kGroups, nc - 1);     // clamped: in bounds, masked below
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * kGroups;
+            if (c < nc) {
                 mlc[u] = ml[c * cs];
                 x[u]   = po[c * cs * V4];
             }
