@@ -111,7 +111,14 @@ int sw_kv_layout(int n_req, int n_kvh, int head_dim, int max_len, sw_kv_layout_t
  * once a call of the same or a larger shape has run on that stream outside
  * any capture: a call that has to grow the workspace allocates and
  * synchronises, which a capture does not allow (SW_ERR_HIP where the runtime
- * refuses it).  The result of a request does not depend on which other
+ * refuses it).  A recorded call holds the workspace's address in its kernel
+ * arguments: a later call that grows the workspace takes a new block and leaves
+ * the old one allocated until sw_release(), so graphs recorded earlier stay
+ * valid -- until sw_release(), after which they must not be launched again.
+ * The workspace belongs to the stream the call was RECORDED on: launch such a
+ * graph on that stream, or make sure no other call that uses the same stream's
+ * workspace (eager, or another graph recorded there) can run at the same time;
+ * the library cannot order them.  The result of a request does not depend on which other
  * requests share the batch, and repeating a call gives the same bits.
  * n_req == 0 returns SW_OK without touching the device.
  * Errors: SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN (all

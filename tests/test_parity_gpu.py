@@ -206,6 +206,61 @@ def test_single_launch_variant_is_repeatable_and_agrees_with_two_kernels(kernel)
     assert np.max(np.abs(first.astype(np.float64) - two.astype(np.float64))) <= 2e-3
 
 
+@pytest.mark.parametrize("name,chunk", [("llama70b_tp8", 512), ("bloom176b_tp8", 1024), ("skewed_256", 1024)])
+def test_single_launch_variant_at_bench_size_over_many_rotations(name, chunk):
+    # The single-launch merge passes partial results between workgroups on different XCDs
+    # through tagged 16-byte pieces, with no fence; what guards it is that every piece read
+    # carries this call's tag.  Here it runs the way bench.py runs the step -- full-size
+    # batches, three cache sets rotated in one replayed graph, many replays, at most eight
+    # chunks per request -- and after every rotation each set's rows must be, bit for bit,
+    # what the first single-launch call gave for that set (the sets share one workspace, so
+    # a piece of an earlier call accepted by mistake would carry another set's values), which
+    # in turn agrees with the two-kernel form (whose merge rounds differently: all chunks
+    # against the overall maximum there, a running maximum here).  Stops at the first mismatch.
+    import torch
+    cfg = wl.CONFIGS[name]
+    sw.sw_set_param(sw.SW_PARAM_CHUNK, chunk)
+    sets, two = [], []
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, 1)
+    for i in range(3):
+        batch = wl.make_batch(cfg, seed=7300 + 10 * cfg.seed_index + i)
+        out, bufs = gpu_out(batch, pad_bits=0x7E00)
+        if i == 0:
+            assert_parity(out, oracle_on_packed(batch, bufs["k_host"], bufs["v_host"], bufs["layout"]), name)
+        del bufs["k_host"], bufs["v_host"]
+        sets.append(bufs)
+        two.append(out.astype(np.float64))
+    sw.sw_set_param(sw.SW_PARAM_COMBINE, 2)
+    stream = torch.cuda.Stream()
+    want = []
+    for i, b in enumerate(sets):         # the first call sizes the workspace, outside any capture
+        b["out"].fill_(float("nan"))
+        sw.run_batch(b, cfg, stream)
+        stream.synchronize()
+        one = b["out"].cpu().numpy()
+        assert np.max(np.abs(one.astype(np.float64) - two[i])) <= 1e-3, (name, i)
+        want.append(one.view(np.uint16).copy())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for b in sets:
+            sw.run_batch(b, cfg, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(40):
+        if rep % 8 == 0:
+            print("rotation", rep, name, flush=True)
+            for b in sets:
+                b["out"].fill_(float("nan"))
+        with torch.cuda.stream(stream):
+            for _ in range(5):
+                graph.replay()
+        stream.synchronize()
+        for i, b in enumerate(sets):
+            got = b["out"].cpu().numpy().view(np.uint16)
+            assert np.array_equal(got, want[i]), (name, "rotation", rep, "set", i,
+                                                   int((got != want[i]).sum()), "elements differ")
+    assert sw.sw_device_status() == 0
+
+
 @pytest.mark.parametrize("combine", [1, 2])
 def test_decode_call_in_a_replayed_graph(combine):
     # the way bench.py launches the step: captured once, replayed with eager work and
