@@ -80,6 +80,14 @@ union Frag {
     half8_t h;
 };
 
+// Keeps a wave-uniform value in scalar registers from here on: whatever it is computed or
+// loaded from has been waited for at this point.
+template <typename T>
+__device__ __forceinline__ void sw_pin(T &x)
+{
+    asm volatile("" : "+s"(x));
+}
+
 template <int WAVES, int PER, bool FUSED, bool PAGED>
 __global__ __launch_bounds__(64 * WAVES, 2)
 void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int chunk_shift, int n_kvh, SwArgs a_rest)
@@ -102,8 +110,40 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
     __shared__ int sm_flag;
 
     // -- phase: workgroup started
-    // first of all the lengths: the scan needs nothing but the leading arguments
-    const SwScan<PER> scan = sw_scan_lens<PER>(a);
+    // First of all the lengths: asking for them needs nothing but the leading arguments, which
+    // arrive in registers.  While they travel, every other argument the workgroup will need is
+    // read from the argument block in one go: left to itself the compiler reads each one where
+    // it is first used, past the early exit below, which puts several scalar-memory round trips
+    // in a row between knowing the item and asking for its first tile.
+    const SwRawLens<PER> raw_lens = sw_scan_issue<PER>(a);
+    sw_pin(a.q);
+    sw_pin(a.k);
+    sw_pin(a.v);
+    sw_pin(a.q_rows);
+    sw_pin(a.k_new);
+    sw_pin(a.stride_req);
+    sw_pin(a.stride_kvh);
+    sw_pin(a.group);
+    sw_pin(a.n_qh);
+    sw_pin(a.n_chunks);
+    sw_pin(a.scale_log2e);
+    if (FUSED) {
+        sw_pin(a.out);
+        sw_pin(a.units);
+        sw_pin(a.ws_tag);
+        sw_pin(a.ws_tag_bytes);
+    } else {
+        sw_pin(a.ws_o);
+        sw_pin(a.ws_ml);
+    }
+    if (PAGED) {
+        sw_pin(a.block_table);
+        sw_pin(a.stride_block);
+        sw_pin(a.block_shift);
+        sw_pin(a.max_blocks);
+        sw_pin(a.n_blocks);
+    }
+    const SwScan<PER> scan = sw_scan_finish<PER>(a, raw_lens);
 
     // A group of more than 16 query heads is served in head tiles of 16, one workgroup per
     // tile and chunk.  Consecutive workgroups go to different XCDs (eight L2s), so the tiles
@@ -359,6 +399,7 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         // Outstanding, oldest first: V(t0) x8, then K(next) x8 if there is a next tile.
         if (MORE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
         else      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        // -- phase: V tile landed
         if (has_new) {
             // all of the wave's loads have landed: patch the staged V row, then store
             // both rows to the cache (lanes 0-15 the K row, lanes 16-31 the V row)
@@ -417,6 +458,7 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         issue_k(t_begin + ti * kTile, fb);
         issue_v(t_begin + ti * kTile, fb);
     }
+    // -- phase: first loads issued
     // Q (and the new rows) must be in LDS before any wave goes on; the tile loads stay in flight
     // across the barrier.  Vector-memory operations complete in issue order, so
     // "at most the 16 tile loads outstanding" means this wave's Q load is done.

@@ -60,8 +60,32 @@ struct SwScan {
     unsigned total;    // number of item slots to walk (for PER > 0: exactly the real items)
 };
 
+// The lane's lengths as they lie in memory: sw_scan_issue requests them (all of them before
+// anything else is looked at) and sw_scan_finish turns them into the scan state, so a caller
+// can put work that does not depend on the lengths between the two.
 template <int PER>
-__device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
+struct SwRawLens {
+    int v[PER > 0 ? PER : 1];
+};
+
+template <int PER>
+__device__ __forceinline__ SwRawLens<PER> sw_scan_issue(const SwArgs &a)
+{
+    SwRawLens<PER> raw;
+    raw.v[0] = 0;
+    if constexpr (PER > 0) {
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int r = lane * PER + j;
+            raw.v[j] = r < a.n_req ? a.seq_lens[r] : 0;
+        }
+    }
+    return raw;
+}
+
+template <int PER>
+__device__ __forceinline__ SwScan<PER> sw_scan_finish(const SwArgs &a, const SwRawLens<PER> &raw)
 {
     SwScan<PER> s;
     if constexpr (PER == 0) {
@@ -69,18 +93,11 @@ __device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
         s.total = (unsigned)a.n_req * (unsigned)a.n_kvh * (unsigned)a.n_chunks;
     } else {
         const int lane = threadIdx.x & 63;
-        // all of the lane's lengths are requested before anything else is looked at
-        int raw[PER];
-#pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            const int r = lane * PER + j;
-            raw[j] = r < a.n_req ? a.seq_lens[r] : 0;
-        }
         s.mine = 0;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             const int r = lane * PER + j;
-            s.len[j] = r < a.n_req ? sw_flag_len(a, r, raw[j]) : 0;
+            s.len[j] = r < a.n_req ? sw_flag_len(a, r, raw.v[j]) : 0;
             s.cnt[j] = ((s.len[j] & kSwLenMask) + a.chunk - 1) >> a.chunk_shift;
             s.mine += s.cnt[j];
         }
@@ -88,6 +105,13 @@ __device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
         s.total = (unsigned)__builtin_amdgcn_readlane(s.incl, 63) * (unsigned)a.n_kvh;
     }
     return s;
+}
+
+template <int PER>
+__device__ __forceinline__ SwScan<PER> sw_scan_lens(const SwArgs &a)
+{
+    const SwRawLens<PER> raw = sw_scan_issue<PER>(a);
+    return sw_scan_finish<PER>(a, raw);
 }
 
 template <int PER>
