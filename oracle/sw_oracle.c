@@ -335,30 +335,13 @@ int sw_oracle_kv_append_paged(const uint16_t *k_new, const uint16_t *v_new,
 }
 
 /*
- * Prompt phase (section 2.2: all tokens of the prompt are processed in parallel
- * in one forward pass, which also produces the KV cache; section 3.5, Insight V:
- * this phase is compute bound).  Its attention is the causal form of the same
- * definition: prompt token i of request r sees cached positions 0..i, so row i is
- * exactly the token-phase routine above run with length i + 1.  It is written
- * that way: one attend_one per (request, head, token).
- *   q         binary16 bits, [n_tokens][n_qh][head_dim]; token i of request r is
- *             row q_starts[r] + i
- *   q_starts  int32 [n_req]; rows q_starts[r] .. q_starts[r] + L_r - 1 must lie in
- *             [0, n_tokens) (checked: a request that would leave it returns -5)
- *   ref       double [n_tokens][n_qh][head_dim]; rows of no request are left as
- *             they were
- * Everything else as in sw_oracle_decode_attn.
- * Pins: row i equals sw_oracle_decode_attn at length i + 1; brute force against a
- * masked dense matrix formulation; rows do not depend on later positions
- * (tests/test_oracle_pins.py).
- */
-/*
  * Mixed batch (section 2.4, "mixed batching": prompt and token phases run together in
  * one forward pass): request r contributes its LAST nq_r tokens as queries,
  * nq_r = clamp(q_lens[r], 0, min(L_r, max_q_len)); query i is the token at position
  * L_r - nq_r + i and sees cached positions 0 .. L_r - nq_r + i.  nq_r = L_r is a whole
  * prompt, nq_r = 1 a token-phase request, anything between a prompt processed in pieces.
- * q_lens == NULL means nq_r = L_r for every request (the prompt phase above).
+ * q_lens == NULL means nq_r = L_r for every request (the prompt phase,
+ * sw_oracle_prefill_attn below).
  * Still one attend_one per (request, head, query token).
  * Pins: nq = L is the prompt routine; nq = 1 is sw_oracle_decode_attn; a prompt in two
  * pieces gives the rows of the prompt in one piece, bit for bit (tests/test_oracle_pins.py).
@@ -425,6 +408,25 @@ int sw_oracle_mixed_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v
     return failed ? -4 : used;
 }
 
+/*
+ * Prompt phase (section 2.2: all tokens of the prompt are processed in parallel
+ * in one forward pass, which also produces the KV cache; section 3.5, Insight V:
+ * this phase is compute bound).  Its attention is the causal form of the same
+ * definition: prompt token i of request r sees cached positions 0..i, so row i is
+ * exactly the token-phase routine run with length i + 1.  It is written that way:
+ * the mixed routine above with every cached token a query, i.e. one attend_one per
+ * (request, head, token).
+ *   q         binary16 bits, [n_tokens][n_qh][head_dim]; token i of request r is
+ *             row q_starts[r] + i
+ *   q_starts  int32 [n_req]; rows q_starts[r] .. q_starts[r] + L_r - 1 must lie in
+ *             [0, n_tokens) (checked: a request that would leave it returns -5)
+ *   ref       double [n_tokens][n_qh][head_dim]; rows of no request are left as
+ *             they were
+ * Everything else as in sw_oracle_decode_attn.
+ * Pins: row i equals sw_oracle_decode_attn at length i + 1; brute force against a
+ * masked dense matrix formulation; rows do not depend on later positions
+ * (tests/test_oracle_pins.py).
+ */
 int sw_oracle_prefill_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                            const int32_t *seq_lens, const int32_t *q_starts, double *ref,
                            int n_req, int n_qh, int n_kvh, int head_dim, int max_len, int64_t n_tokens,
