@@ -78,8 +78,8 @@ class RegimeModel:
     """Separate piece-wise linear surfaces per context regime (discontinuous at the breaks).
 
     The library changes how it works at fixed context limits (one chunk per request up to
-    256 positions, a single launch up to 2048, longer chunks beyond 4096), and the call time
-    steps there; a continuous model would smear each step over a whole knot interval.
+    256 positions, a single launch up to 1024, two kernels beyond, longer chunks beyond 4096),
+    and the call time steps there; a continuous model would smear each step over a whole knot interval.
     regimes: list of (upper context bound inclusive, context knots inside the regime).
     """
 
@@ -152,8 +152,9 @@ CONTEXTS = (128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 81
 BATCH_KNOTS = (1, 2, 4, 8, 16, 32, 64, 128)
 CONTEXT_KNOTS = (128, 256, 512, 1024, 2048, 4096, 8192)
 # where sw_decode_attn's call time steps (context = max_len): one chunk per request up to 256
-# positions, a single launch up to 2048, two kernels beyond; context knots inside each regime
-REGIMES = ((256, (128, 256)), (2048, (384, 1024, 2048)), (8192, (3072, 4096, 6144, 8192)))
+# positions, a single launch up to 1024 (four chunks), two kernels beyond; context knots inside
+# each regime
+REGIMES = ((256, (128, 256)), (1024, (384, 1024)), (8192, (1536, 4096, 8192)))
 REGIME_BATCH_KNOTS = (1, 8, 16, 32, 64, 128)
 
 

@@ -65,7 +65,7 @@ def test_regime_model_fits_a_surface_with_steps_at_the_breaks():
 
     def truth(b, c):
         base = 3.0 + 0.002 * b * np.log2(c)                      # smooth part
-        return base + np.where(c > 256, 2.0, 0.0) + np.where(c > 2048, 1.5, 0.0)   # steps at the breaks
+        return base + np.where(c > 256, 2.0, 0.0) + np.where(c > 1024, 1.5, 0.0)   # steps at the breaks
     t = truth(b, c)
     res = pm.evaluate(b, c, t, pm.REGIME_BATCH_KNOTS, None, seed=1, regimes=pm.REGIMES)
     one = pm.evaluate(b, c, t, pm.BATCH_KNOTS, pm.CONTEXT_KNOTS, seed=1)
