@@ -274,7 +274,7 @@ __device__ __forceinline__ void load_vt(const unsigned char *vb, const unsigned 
 // tile's first position).
 __device__ __forceinline__ void softmax_block(int nb, const float4_t (&sacc)[2][2], bool diagonal, int q0, int t0,
                                               int n16, int gq, float scale_log2e, float lazy_raw,
-                                              float (&m)[2], float (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
+                                              float (&m)[2], float4_t (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
 {
     {
         float s[8];
@@ -323,7 +323,8 @@ __device__ __forceinline__ void softmax_block(int nb, const float4_t (&sacc)[2][
                 psum += pj[j];
             }
         }
-        l[nb] += psum;
+        // (psum only decides whether the maximum must be raised; the sum that normalises the
+        // row is taken from the rounded weights, by the matrix cores, in pv_block)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const half2_t h2 = __builtin_convertvector((float2_t){pj[2 * j], pj[2 * j + 1]}, half2_t);
@@ -335,18 +336,28 @@ __device__ __forceinline__ void softmax_block(int nb, const float4_t (&sacc)[2][
 
 __device__ __forceinline__ void softmax_tile(const float4_t (&sacc)[2][2], bool diagonal, int q0, int t0,
                                              int n16, int gq, float scale_log2e, float lazy_raw,
-                                             float (&m)[2], float (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
+                                             float (&m)[2], float4_t (&l)[2], float4_t (&o)[2][8], Frag (&p)[2])
 {
     softmax_block(0, sacc, diagonal, q0, t0, n16, gq, scale_log2e, lazy_raw, m, l, o, p);
     softmax_block(1, sacc, diagonal, q0, t0, n16, gq, scale_log2e, lazy_raw, m, l, o, p);
 }
 
-// O^T += V^T P^T for one query block
-__device__ __forceinline__ void pv_block(int nb, const Frag (&va)[8], const Frag (&p)[2], float4_t (&o)[2][8])
+// O^T += V^T P^T for one query block, and the sum of the same weights: one more product with
+// an all-ones operand leaves, in every element of l[nb], the tile's sum over ALL 32 keys of
+// the binary16 weights of query n16.  Numerator and denominator of a row are thus built from
+// the same rounded weights, w~_i = w_i (1 + d_i): the row's error is sum_i w_i d_i (v_i - out),
+// which vanishes where one key dominates (its v is the row) -- with the exact sum as
+// denominator it would be sum_i w_i d_i v_i, up to 2^-11 |v| for such a row, which alone
+// exceeds the error bound once |v| reaches 4.
+__device__ __forceinline__ void pv_block(int nb, const Frag (&va)[8], const Frag (&p)[2], float4_t (&o)[2][8],
+                                         float4_t (&l)[2])
 {
+    Frag ones;
+    ones.u = uint4_t{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};      // eight binary16 ones
 #pragma unroll
     for (int e = 0; e < 8; ++e)
         o[nb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[e].h, p[nb].h, o[nb][e], 0, 0, 0);
+    l[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, p[nb].h, l[nb], 0, 0, 0);
 }
 
 }  // namespace sw_prefill

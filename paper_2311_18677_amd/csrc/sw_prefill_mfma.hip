@@ -123,7 +123,8 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
 
     unsigned vt_off[8];
     vt_offsets(n16, gq, vt_off);
-    float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
+    float m[2] = {kNegBig, kNegBig};
+    float4_t l[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};   // sums of the weights (every element the same)
     const float lazy_raw = kLazyBits / a.scale_log2e;      // the threshold in raw score units
     float4_t o[2][8];
 #pragma unroll
@@ -166,9 +167,9 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
         softmax_block(0, sacc, diagonal, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
         Frag va[8];
         load_vt(vb, vt_off, va);
-        pv_block(0, va, p, o);
+        pv_block(0, va, p, o, l);
         softmax_block(1, sacc, diagonal, aw0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
-        pv_block(1, va, p, o);
+        pv_block(1, va, p, o, l);
     };
     static_assert(kBufs == 3, "the loop below is unrolled by the number of buffers");
     for (int ti = 0; ti < n_tiles; ti += kBufs) {
@@ -180,7 +181,7 @@ void sw_prefill_mfma_kernel(SwPrefillArgs a)
     // ---- this lane's query rows: dims 16e + 4gq + i
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-        const float ls = quad_rows_sum(l[nb]);
+        const float ls = l[nb][0];                    // already summed over the tile's 32 keys
         const int qpos = qw0 + 16 * nb + n16;        // query index
         const long long row = q_first + qpos;
         if (qpos < NQ && row >= 0 && row < a.n_tokens) {

@@ -230,7 +230,8 @@ void sw_prefill_split_kernel(SwPrefillArgs a, SwArgs d, unsigned n_prompt)
     };
 
     Frag qreg[2][4];
-    float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
+    float m[2] = {kNegBig, kNegBig};
+    float4_t l[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};   // sums of the weights (every element the same)
     const float lazy_raw = kLazyBits / a.scale_log2e;
     float4_t o[2][8];
 #pragma unroll
@@ -272,9 +273,9 @@ void sw_prefill_split_kernel(SwPrefillArgs a, SwArgs d, unsigned n_prompt)
             __builtin_amdgcn_s_waitcnt(0xc07f);
             issue_v(t0_next, nb);
         }
-        pv_block(0, va, p, o);
+        pv_block(0, va, p, o, l);
         softmax_block(1, sacc, diagonal, A0, t0, n16, gq, a.scale_log2e, lazy_raw, m, l, o, p);
-        pv_block(1, va, p, o);
+        pv_block(1, va, p, o, l);
     };
 
     int ti = wave;
@@ -310,7 +311,7 @@ void sw_prefill_split_kernel(SwPrefillArgs a, SwArgs d, unsigned n_prompt)
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const int qi = 16 * nb + n16;
-        const float ls = quad_rows_sum(l[nb]);
+        const float ls = l[nb][0];                    // already summed over the tile's 32 keys
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int piece = 4 * e + gq;                                 // dims 4*piece .. 4*piece+3

@@ -64,6 +64,21 @@ def test_mixed_batch_matches_oracle(n_qh, n_kvh):
     assert_parity(out, ref, cfg.name)
 
 
+def test_mixed_batch_with_key_rows_scaled_by_8():
+    # prompts, prompt pieces and token-phase requests over caches in which a tenth of the key
+    # rows is scaled by 8 (single keys dominate a row, whose value is then one V row)
+    import dataclasses
+    lens = [1500, 1800, 2048, 900, 1, 2048, 64, 1200]
+    qls = [1500, 1, 300, 1, 1, 2048, 64, 1]
+    cfg = dataclasses.replace(wl.custom_config("mxx8", len(lens), 8, 1, 128, 2048), k_row_scale=(0.1, 8.0))
+    batch = wl.make_batch(cfg, seed=8850, seq_lens=lens)
+    qt, starts, nq = wl.make_mixed_queries(batch, qls)
+    out, ref, _ = run_mixed(batch, qt, starts, qls, 2048, tag="x8")
+    assert not np.isnan(out.astype(np.float32)).any()
+    assert np.abs(ref).max() > 3.5
+    assert_parity(out, ref, cfg.name)
+
+
 def test_all_tokens_as_queries_is_the_prompt_call_bit_for_bit():
     import torch
     lens = [200, 77, 130]

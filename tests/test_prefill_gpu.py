@@ -72,6 +72,21 @@ def test_prefill_group_sizes_and_ragged_lengths(n_qh, n_kvh):
             assert np.array_equal(out[starts[r]].view(np.uint16), batch.v_rows[r][g, 0, :].view(np.uint16))
 
 
+def test_prefill_key_rows_scaled_by_8_stress_the_softmax_range():
+    # a tenth of the key rows scaled by 8, as in the skewed token-phase workload: single keys
+    # dominate a row, whose value is then one V row -- up to 4.7 in magnitude here, where the
+    # binary16 result alone rounds by up to 1.95e-3.  The bound only holds because numerator and
+    # denominator of a row are built from the same rounded weights.
+    import dataclasses
+    lens = [2048, 700, 1500, 33, 1024]
+    cfg = dataclasses.replace(wl.custom_config("pfx8", len(lens), 8, 1, 128, 2048), k_row_scale=(0.1, 8.0))
+    batch = wl.make_batch(cfg, seed=8800, seq_lens=lens)
+    qt, starts = wl.make_prefill_queries(batch)
+    out, ref = run_prefill(batch, qt, starts, tag="x8")
+    assert np.abs(ref).max() > 4.0
+    assert_parity(out, ref, cfg.name)
+
+
 def test_prefill_last_row_matches_the_decode_step():
     # the last prompt token's row is the token-phase step over the whole prompt
     import torch
