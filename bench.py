@@ -507,7 +507,7 @@ def main_handoff(args):
     elapsed = time.perf_counter() - t0
     moved = 2 * sum(sets[i % n_sets]["kv_bytes"] for i in range(steps))      # read + written
 
-    prof_calls = min(steps, 50 * n_sets)
+    prof_calls = 50 * n_sets                 # whatever K is: a series long enough to be back to back
     sw.sw_prof_start(prof_calls)
     for i in range(prof_calls):
         call(sets[i % n_sets], stream)
@@ -564,47 +564,70 @@ def main_handoff(args):
 
 
 class GraphSteps:
-    """Runs exactly n steps as HIP-graph launches on one stream: whole rotations over the cache
-    sets replay one graph, a remainder replays a second graph of the rotation's first sets.
-    Nothing is launched eagerly, so every step of a timed region is launched the same way."""
+    """Runs exactly n steps as HIP-graph launches on one stream.  A short run (up to
+    kOneGraph steps) is ONE graph of exactly n calls walking the rotation; a longer one replays
+    a graph of one whole rotation over the cache sets and, for a remainder, a second graph of
+    the rotation's first sets.  Nothing is launched eagerly, so every step of a timed region
+    is launched the same way.  record(k, stream) enqueues the rotation's first k calls (and
+    what follows a whole rotation when k is the number of sets)."""
+
+    kOneGraph = 256
 
     def __init__(self, torch, stream, n_sets, record):
         self.torch, self.stream, self.n_sets, self.record = torch, stream, n_sets, record
         self.graphs = {}
 
-    def graph(self, k):
-        if k not in self.graphs:
+    def _parts(self, n):
+        """(key of the graph, how many replays) in launch order."""
+        full, rem = divmod(n, self.n_sets)
+        if n <= self.kOneGraph:
+            return [(("run", n), 1)] if n else []
+        return [(("rot", self.n_sets), full)] + ([(("rot", rem), 1)] if rem else [])
+
+    def graph(self, key):
+        if key not in self.graphs:
+            kind, n = key
             g = self.torch.cuda.CUDAGraph()
             with self.torch.cuda.graph(g, stream=self.stream):
-                self.record(k, self.torch.cuda.current_stream())
+                st = self.torch.cuda.current_stream()
+                if kind == "rot":
+                    self.record(n, st)
+                else:
+                    full, rem = divmod(n, self.n_sets)
+                    for _ in range(full):
+                        self.record(self.n_sets, st)
+                    if rem:
+                        self.record(rem, st)
             self.torch.cuda.synchronize()
-            self.graphs[k] = g
-        return self.graphs[k]
+            self.graphs[key] = g
+        return self.graphs[key]
 
     def prepare(self, *counts):
         for n in counts:
-            if n >= self.n_sets:
-                self.graph(self.n_sets)
-            if n % self.n_sets:
-                self.graph(n % self.n_sets)
+            for key, _ in self._parts(n):
+                self.graph(key)
 
     def run(self, n):
-        full, rem = divmod(n, self.n_sets)
         with self.torch.cuda.stream(self.stream):
-            for _ in range(full):
-                self.graph(self.n_sets).replay()
-            if rem:
-                self.graph(rem).replay()
+            for key, times in self._parts(n):
+                g = self.graph(key)
+                for _ in range(times):
+                    g.replay()
 
 
-def time_on_stream(torch, stream, launch):
+def time_on_stream(torch, stream, launch, lead_in=None):
     """Milliseconds between two HIP events recorded on `stream` right before and right after
-    what launch() enqueues there, and the host's wall-clock time around the same region (with a
-    device synchronisation on both sides)."""
+    what launch() enqueues there, and the host's wall-clock time around the bracket (with a
+    device synchronisation on both sides).  lead_in(), if given, enqueues untimed work (the
+    warm-up steps) on the stream right before the first event, so that the timed work is already
+    queued when the GPU gets to it and the events see the steps, not the host's launch latency;
+    the host's wall-clock time then covers the lead-in as well."""
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    if lead_in is not None:
+        lead_in()
     e0.record(stream)
     launch()
     e1.record(stream)
@@ -660,10 +683,10 @@ def measure_other_config(name, torch, np, sw, wl, dev, steps, warmup, repeats, w
     stream.synchronize()
     runner = GraphSteps(torch, stream, n_sets, lambda k, st: [call(s, st) for s in sets[:k]])
     runner.prepare(steps, warmup)
-    runner.run(warmup)
-    ev_ms = [time_on_stream(torch, stream, lambda: runner.run(steps))[0] for _ in range(repeats)]
+    ev_ms = [time_on_stream(torch, stream, lambda: runner.run(steps), lambda: runner.run(warmup))[0]
+             for _ in range(repeats)]
     mean_bytes = sum(sets[i % n_sets]["kv_bytes"] for i in range(steps)) / steps
-    n_prof = min(steps, 20 * n_sets)
+    n_prof = 20 * n_sets
     sw.sw_prof_start(n_prof)
     for i in range(n_prof):
         call(sets[i % n_sets], stream)
@@ -746,7 +769,7 @@ def main():
     # ---- inputs: set 0 from the host recipe (also the oracle's input), the rest on device
     append = args.append or args.decode_loop
     loop = args.decode_loop
-    room = (max(1, args.repeats) * args.steps + args.warmup) // cfg.n_layers + 60 if loop else (1 if append else 0)
+    room = (max(1, args.repeats) * (args.steps + args.warmup) + args.warmup) // cfg.n_layers + 60 if loop else (1 if append else 0)
     batch0 = wl.make_batch(cfg)
     if args.paged:
         set0 = sw.upload_paged_batch(batch0, args.paged, device="cuda:0", pad_bits=0, room=room)
@@ -876,12 +899,16 @@ def main():
 
     run_steps(warmup)
     torch.cuda.synchronize()
-    # the K steps, `repeats` times over; each repeat timed with HIP events recorded on the
-    # bench stream itself, and with the host clock around a synchronised region beside it
+    # the W warm-up steps and the K timed steps, back to back, `repeats` times over; the K steps
+    # of each repeat timed with HIP events recorded on the bench stream itself, and the whole
+    # bracket (W + K steps) with the host clock around a synchronised region beside it
     ev_ms, wall_ms, rep_bytes = [], [], []
     for _ in range(repeats):
         bytes_before = attended_bytes()
-        e_ms, w_ms = time_on_stream(torch, stream, lambda: run_steps(steps))
+        if loop:
+            # the warm-up steps that lead into the timed ones advance the lengths as well
+            bytes_before += (warmup // n_sets) * cfg.n_req * cfg.n_kvh * cfg.head_dim * 4
+        e_ms, w_ms = time_on_stream(torch, stream, lambda: run_steps(steps), lambda: run_steps(warmup))
         if loop:
             # every layer call of a model step reads the same lengths, which grow by one per
             # model step: the mean of the first and the last step's bytes, times the calls
@@ -908,7 +935,8 @@ def main():
               "ms_per_step_median": 1e3 * elapsed / steps,
               "ms_per_step_min": min(ev_ms) / steps,
               "ms_per_step_max": max(ev_ms) / steps,
-              "host_clock_ms_per_step_median": median(wall_ms) / steps}
+              "host_clock_ms_per_step_median": median(wall_ms) / (steps + warmup),
+              "host_clock_covers": "warm-up and timed steps of a repeat, launch and synchronisation included"}
 
     # ---- per-kernel device time (HIP events attached to each dispatch, same stream, eager)
     prof_calls = min(steps, 50 * n_sets)
