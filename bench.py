@@ -206,10 +206,26 @@ def stream_read_ceiling(sw, torch, n_bytes, dev, launches=400):
     k_us, _, n_rec = sw.sw_prof_stop()
     kernel_us = k_us / max(n_rec, 1)
     del bufs
+    # the same kernel over one 2 GiB buffer: what streaming reads reach when launch and tail
+    # no longer count
+    big_bytes = 2 << 30
+    big = torch.empty(big_bytes // 4, dtype=torch.int32, device=dev).random_()
+    sw.sw_stream_read(big, big_bytes, sink, 0, stream)
+    stream.synchronize()
+    sw.sw_prof_start(5)
+    for _ in range(5):
+        sw.sw_stream_read(big, big_bytes, sink, 0, stream)
+    b_us, _, b_rec = sw.sw_prof_stop()
+    big_us = b_us / max(b_rec, 1)
+    del big
+    torch.cuda.empty_cache()
     return {"bytes": n_bytes, "buffers": n_bufs, "call_us": call_us, "call_GBps": n_bytes / call_us / 1e3,
             "kernel_us": kernel_us, "kernel_GBps": n_bytes / kernel_us / 1e3 if kernel_us > 0 else 0.0,
+            "large_read_bytes": big_bytes, "large_read_us": big_us,
+            "large_read_GBps": big_bytes / big_us / 1e3 if big_us > 0 else 0.0,
             "what": "sw_stream_read: one plain kernel that reads this many bytes once (grid-stride, "
-                    "16 B per lane, 8 loads in flight); a reference point, not a proven ceiling"}
+                    "16 B per lane, 8 loads in flight); a reference point, not a proven ceiling. "
+                    "large_read: the same kernel over one 2 GiB buffer"}
 
 
 def main_prefill(args):
@@ -937,6 +953,16 @@ def main():
               "ms_per_step_max": max(ev_ms) / steps,
               "host_clock_ms_per_step_median": median(wall_ms) / (steps + warmup),
               "host_clock_covers": "warm-up and timed steps of a repeat, launch and synchronisation included"}
+
+    # ---- single calls with a synchronisation between them (host clock): launch + tail overhead
+    single = []
+    for i in range(40):
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        call(sets[i % n_sets], stream)
+        stream.synchronize()
+        single.append(1e6 * (time.perf_counter() - c0))
+    timing["single_call_synchronised_us_median"] = median(single[8:])
 
     # ---- per-kernel device time (HIP events attached to each dispatch, same stream, eager)
     prof_calls = min(steps, 50 * n_sets)
