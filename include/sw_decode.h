@@ -439,13 +439,14 @@ int sw_device_status(int *gave_up);
  *                      (SW_ERR_UNSUPPORTED at call time if the shape has no such
  *                      kernel: it needs head_dim 128).
  *   SW_PARAM_COMBINE   how the chunks of a request are merged: 0 = library default
- *                      (the same launch wherever its workspace stays below 4 GiB),
+ *                      (the same launch where no request can have more than four
+ *                      chunks, i.e. max_len <= 4 * chunk; a second kernel otherwise),
  *                      1 = a second (combine) kernel, 2 = in the same launch, by
  *                      one of the workgroups of the request's head group
  *                      (SW_ERR_UNSUPPORTED at call time above 4 GiB).
  *                      Each is deterministic; the two differ by rounding only.
  *   SW_PARAM_WAVES     waves per workgroup of the matrix-core partial kernel:
- *                      0 = library default, else 4, 8 or 16.
+ *                      0 = library default (4), else 4 or 8.
  *   SW_PARAM_PREFILL_HEADS  prompt-phase kernel: query heads of a group that share a
  *                      workgroup (0 = library default; a value that does not divide
  *                      the group size is ignored).

@@ -456,8 +456,8 @@ int sw_set_param(int key, int value)
         g_combine = value;
         return SW_OK;
     case SW_PARAM_WAVES:
-        if (value != 0 && value != 4 && value != 8 && value != 16)
-            return fail(SW_ERR_PARAM, "waves must be 0, 4, 8 or 16");
+        if (value != 0 && value != 4 && value != 8)
+            return fail(SW_ERR_PARAM, "waves must be 0, 4 or 8");
         g_waves = value;
         return SW_OK;
     case SW_PARAM_PREFILL_HEADS:

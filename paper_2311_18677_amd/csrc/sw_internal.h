@@ -55,7 +55,7 @@ struct SwArgs {
     int   n_req, n_qh, n_kvh, group;   // group = n_qh / n_kvh
     int   head_dim, max_len;
     int   chunk, chunk_shift, n_chunks; // chunk = 1 << chunk_shift; n_chunks = ceil(max_len / chunk)
-    int   waves;                        // waves per workgroup of the matrix-core partial kernel (4, 8 or 16)
+    int   waves;                        // waves per workgroup of the matrix-core partial kernel (4 or 8)
     long long stride_req, stride_kvh;  // elements; the token stride is head_dim
     // block-table variant: k, v are pools; row t of request r is row t % block_size of pool
     // block block_table[r*max_blocks + t / block_size]; stride_req is unused

@@ -100,6 +100,7 @@ def test_params_roundtrip_and_validation():
     assert sw.sw_set_param(sw.SW_PARAM_COMBINE, 3, check=False) == sw.SW_ERR_PARAM
     assert sw.sw_get_param(sw.SW_PARAM_COMBINE) == 0
     assert sw.sw_set_param(sw.SW_PARAM_WAVES, 5, check=False) == sw.SW_ERR_PARAM
+    assert sw.sw_set_param(sw.SW_PARAM_WAVES, 16, check=False) == sw.SW_ERR_PARAM
     sw.sw_set_param(sw.SW_PARAM_WAVES, 8)
     assert sw.sw_get_param(sw.SW_PARAM_WAVES) == 8
     sw.sw_set_param(sw.SW_PARAM_WAVES, 0)
