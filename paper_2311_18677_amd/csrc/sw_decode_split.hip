@@ -143,7 +143,13 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         sw_pin(a.max_blocks);
         sw_pin(a.n_blocks);
     }
-    const SwScan<PER> scan = sw_scan_finish<PER>(a, raw_lens);
+
+    // ... and everything that does not depend on the item is done now, under the lengths' latency.
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
+    const int n16  = lane & 15;     // head (B operand / output column), token (A operand of QK), dim chunk (A operand of PV)
+    const int gq   = lane >> 4;     // k-slot group
+    unsigned char *wlds = lds + wave * kWaveLds;
 
     // A group of more than 16 query heads is served in head tiles of 16, one workgroup per
     // tile and chunk.  Consecutive workgroups go to different XCDs (eight L2s), so the tiles
@@ -162,6 +168,20 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
     }
     const int h0 = 16 * ht;
     const int gn = min(16, a.group - h0);
+    // Q^T rows of heads past the group are zero columns of the B operands.  Stored before any
+    // global->LDS load is issued: no LDS store may follow a pending one.
+    {
+        const int row = 4 * wave + gq;
+        if (row < 16 && row >= gn)
+            *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
+    }
+    float m = kNegBig, l = 0.f;                        // m in raw score units
+    const float lazy_raw = kLazyBits / a.scale_log2e;  // the raise threshold in raw score units
+    float4_t o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const SwScan<PER> scan = sw_scan_finish<PER>(a, raw_lens);
 
     // Rows of requests with no cached position get +0; no item exists for them, so
     // workgroup b < n_req looks after request b.
@@ -171,11 +191,21 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
     // -- phase: item known
     if (!w.valid) return;
     const int r = w.r, g = w.g, c = w.c;
-    // the request's tiles of 32 positions, dealt evenly to its nc items
+    // the request's tiles of 32 positions, dealt evenly to its nc items: n_all = q * nc + rem
+    // tiles, the first rem items take q + 1 of them.  (One division; both numbers are below
+    // 2^24, so the single-precision quotient is off by at most one and one look at the
+    // remainder settles it.)
     const unsigned n_all = (unsigned)(w.L + kTile - 1) / kTile;
     const unsigned nc = (unsigned)(w.L + a.chunk - 1) >> a.chunk_shift;
-    const int t_begin = (int)((unsigned)c * n_all / nc) * kTile;
-    const int t_end = min(w.L, (int)(((unsigned)c + 1u) * n_all / nc) * kTile);
+    unsigned quot = (unsigned)((float)n_all * __builtin_amdgcn_rcpf((float)nc));
+    quot = __builtin_amdgcn_readfirstlane(quot);
+    if (quot * nc > n_all) --quot;
+    if ((quot + 1) * nc <= n_all) ++quot;
+    const unsigned rem = n_all - quot * nc;
+    const unsigned tile_begin = (unsigned)c * quot + min((unsigned)c, rem);
+    const unsigned tile_count = quot + ((unsigned)c < rem ? 1u : 0u);
+    const int t_begin = (int)(tile_begin * kTile);
+    const int t_end = min(w.L, (int)((tile_begin + tile_count) * kTile));
     const bool alone = FUSED && nc == 1;            // the whole request: finished here, no merge
     const long long unit = ((long long)r * a.n_kvh + g) * n_ht + ht;
     SwFused fz;
@@ -186,20 +216,11 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         fz.merger = false;
     }
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
-    const int n16  = lane & 15;     // head (B operand / output column), token (A operand of QK), dim chunk (A operand of PV)
-    const int gq   = lane >> 4;     // k-slot group
-
     // ---- Q^T for the B operands goes to LDS once per workgroup (row = head, chunks
-    // swizzled like K's; heads past the group are zero columns).  Wave w covers
-    // rows 4w .. 4w+3 with one global->LDS load: lane i lands in slot i%16 of row
-    // 4w + i/16 and therefore fetches chunk slot ^ row.
+    // swizzled like K's).  Wave w covers rows 4w .. 4w+3 with one global->LDS load: lane i
+    // lands in slot i%16 of row 4w + i/16 and therefore fetches chunk slot ^ row.
     {
         const int row = 4 * wave + gq;
-        // zero rows first, loads second: no LDS store follows a pending global->LDS load
-        if (row < 16 && row >= gn)
-            *reinterpret_cast<uint4_t *>(sm_q + row * kRowBytes + n16 * 16) = uint4_t{0u, 0u, 0u, 0u};
         if (row < gn) {            // at most 16 rows: waves past the fourth stage nothing
             const uint16_t *src = a.q + (sw_q_row(a, r) * a.n_qh + g * a.group + h0 + row) * kD + 8 * (n16 ^ row);
             __builtin_amdgcn_global_load_lds(src, sm_q + wave * 1024, 16, 0, 0);
@@ -216,12 +237,6 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
         __builtin_amdgcn_global_load_lds(src, sm_new, 16, 0, 0);
     }
 
-    float m = kNegBig, l = 0.f;                        // m in raw score units
-    const float lazy_raw = kLazyBits / a.scale_log2e;  // the raise threshold in raw score units
-    float4_t o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
-
     // Row addressing: a wave-uniform 64-bit base plus a 32-bit byte offset per lane.
     // Dense layout: the base is the (request, head) slab (below 4 GiB: max_len <= 2^23
     // rows of 256 bytes).  Block-table layout: the base is the pool block of the
@@ -234,9 +249,7 @@ void sw_decode_split_kernel(const int32_t *seq_lens, int n_req, int max_len, int
     // space so that wave-uniform entries come in over the scalar path
     const_table_t table = PAGED ? (const_table_t)(a.block_table + (long long)r * a.max_blocks) : nullptr;
     const int in_block = PAGED ? (1 << a.block_shift) - 1 : ~0;
-    unsigned char *wlds = lds + wave * kWaveLds;
-
-    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+    const int n_tiles = (int)((unsigned)(t_end - t_begin + kTile - 1) / (unsigned)kTile);   // t_end > t_begin
 
     // byte offset, from the block-table base, of the block that holds row 4n of tile t0
     // (clamped like the rows themselves); unused in the dense layout
